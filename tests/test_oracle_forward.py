@@ -1,0 +1,197 @@
+"""Pins for the oracle's forward pass (CPU only).
+
+The oracle is checked against things other than itself:
+  * Hugging Face's LlamaForCausalLM in float64 (an independent implementation of the
+    LLaMA-family decoder named in Sec. 4) -- catches a wrong rotary pairing, a dropped
+    gain, a transposed weight, a wrong GQA head mapping, a wrong attention scale;
+  * torch's scaled_dot_product_attention for the ragged verify attention;
+  * torch's own float32 -> bfloat16 conversion for the rounding helper;
+  * closed forms of rotary embedding, RMSNorm and SiLU;
+  * the properties Sec. 3.1 fixes: one forward over all drafts equals scoring them one
+    step at a time; a cached forward equals a cache-free recompute; causality.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sled_oracle as O
+from paper_2506_09397_amd import synth
+from helpers import oracle_model
+
+SMALL = synth.ModelShape(n_layers=2, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ffn=64,
+                         vocab=64, dtype="f32", rope_theta=10000.0)
+SMALL_MHA = synth.ModelShape(n_layers=3, d_model=48, n_q_heads=3, n_kv_heads=3, head_dim=16, d_ffn=80,
+                             vocab=50, dtype="f32", rope_theta=500000.0)
+
+
+def _hf_model(shape, w):
+    from transformers import LlamaConfig, LlamaForCausalLM
+    cfg = LlamaConfig(vocab_size=shape.vocab, hidden_size=shape.d_model, intermediate_size=shape.d_ffn,
+                      num_hidden_layers=shape.n_layers, num_attention_heads=shape.n_q_heads,
+                      num_key_value_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+                      rms_norm_eps=shape.rms_eps, rope_theta=shape.rope_theta, max_position_embeddings=512,
+                      tie_word_embeddings=False, attention_bias=False, mlp_bias=False,
+                      attn_implementation="eager")
+    m = LlamaForCausalLM(cfg).to(torch.float64).eval()
+    sd = {"model.embed_tokens.weight": w.embed(), "model.norm.weight": w.tensor("g_final"),
+          "lm_head.weight": w.tensor("lm_head")}
+    names = {"wq": "self_attn.q_proj", "wk": "self_attn.k_proj", "wv": "self_attn.v_proj",
+             "wo": "self_attn.o_proj", "wg": "mlp.gate_proj", "wu": "mlp.up_proj", "wd": "mlp.down_proj",
+             "g_attn": "input_layernorm", "g_mlp": "post_attention_layernorm"}
+    for l in range(shape.n_layers):
+        for k, v in w.layer(l).items():
+            sd[f"model.layers.{l}.{names[k]}.weight"] = v
+    missing = m.load_state_dict({k: v.to(torch.float64) for k, v in sd.items()}, strict=True)
+    return m
+
+
+@pytest.mark.parametrize("shape", [SMALL, SMALL_MHA])
+def test_prefill_matches_hf_llama(shape):
+    w = synth.SynthWeights(shape, seed=3, std=0.2, gain_jitter=0.2)
+    om = oracle_model(shape, w)
+    toks = synth.context_tokens(23, shape.vocab, seed=1)
+    ours = O.prefill(om, toks)["logits"]
+    hf = _hf_model(shape, w)
+    with torch.no_grad():
+        ref = hf(torch.from_numpy(toks.astype(np.int64))[None]).logits[0].numpy()
+    assert ours.shape == ref.shape
+    # the library evaluates rotary angles and softmax in float32 even for a float64 model
+    assert np.abs(ours - ref).max() < 2e-5 * max(1.0, np.abs(ref).max())
+
+
+def test_cached_verify_matches_hf_llama_with_cache():
+    """k+1 query rows on top of a cache == the last k+1 rows of the full-sequence forward."""
+    shape = SMALL
+    w = synth.SynthWeights(shape, seed=5, std=0.2, gain_jitter=0.2)
+    om = oracle_model(shape, w)
+    toks = synth.context_tokens(19 + 5, shape.vocab, seed=2)
+    pf = O.prefill(om, toks[:19])
+    r = O.verify_batch(om, [{"tokens": toks[19:], "K": pf["K"], "V": pf["V"]}])[0]
+    hf = _hf_model(shape, w)
+    with torch.no_grad():
+        ref = hf(torch.from_numpy(toks.astype(np.int64))[None]).logits[0].numpy()
+    assert np.abs(r["logits"] - ref[19:]).max() < 2e-5 * max(1.0, np.abs(ref).max())
+
+
+def test_single_forward_equals_step_by_step():
+    """Sec. 3.1: the target scores all drafts in one forward; row j must equal the one-row
+    forward after committing drafts 1..j."""
+    shape = SMALL
+    w = synth.SynthWeights(shape, seed=7, std=0.2)
+    om = oracle_model(shape, w)
+    ctx = synth.context_tokens(11, shape.vocab, seed=3)
+    pf = O.prefill(om, ctx)
+    toks = synth.context_tokens(6, shape.vocab, seed=4)
+    all_at_once = O.verify_batch(om, [{"tokens": toks, "K": pf["K"], "V": pf["V"]}])[0]
+    K, V = pf["K"], pf["V"]
+    for j, t in enumerate(toks):
+        r = O.verify_batch(om, [{"tokens": [t], "K": K, "V": V}])[0]
+        assert np.abs(r["logits"][0] - all_at_once["logits"][j]).max() < 1e-11
+        assert np.abs(r["K_new"][:, 0] - all_at_once["K_new"][:, j]).max() < 1e-12
+        K = np.concatenate([K, r["K_new"]], axis=1)
+        V = np.concatenate([V, r["V_new"]], axis=1)
+
+
+def test_causality_and_batch_independence():
+    shape = SMALL
+    w = synth.SynthWeights(shape, seed=9, std=0.2)
+    om = oracle_model(shape, w)
+    pf = O.prefill(om, synth.context_tokens(9, shape.vocab, seed=5))
+    toks = synth.context_tokens(5, shape.vocab, seed=6)
+    base = O.verify_batch(om, [{"tokens": toks, "K": pf["K"], "V": pf["V"]}])[0]["logits"]
+    for j in range(1, 5):
+        t2 = toks.copy()
+        t2[j] = (t2[j] + 1) % shape.vocab
+        other = {"tokens": toks[:3], "K": pf["K"][:, :4], "V": pf["V"][:, :4]}
+        got = O.verify_batch(om, [other, {"tokens": t2, "K": pf["K"], "V": pf["V"]}])[1]["logits"]
+        assert np.array_equal(got[:j], base[:j])          # rows before the change: unchanged
+        assert np.abs(got[j] - base[j]).max() > 1e-6      # the changed row: changed
+
+
+def test_attention_rows_matches_torch_sdpa():
+    rng = np.random.default_rng(0)
+    for (n_ctx, n, Hq, Hkv, D) in [(0, 3, 2, 2, 8), (5, 1, 1, 1, 4), (17, 9, 8, 2, 16), (33, 5, 8, 1, 8)]:
+        q = rng.standard_normal((n, Hq, D))
+        K = rng.standard_normal((n_ctx + n, Hkv, D))
+        V = rng.standard_normal((n_ctx + n, Hkv, D))
+        G = Hq // Hkv
+        ours = O.attention_rows(q, K, V, n_ctx, G)
+        tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+        tk = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+        tv = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, dim=0)[None]
+        mask = torch.zeros(n, n_ctx + n, dtype=torch.bool)
+        for j in range(n):
+            mask[j, : n_ctx + j + 1] = True
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)[0]
+        assert np.abs(ours - ref.permute(1, 0, 2).numpy()).max() < 1e-12
+
+
+def test_attention_single_query_textbook():
+    """n = 1, one head: softmax(K q / sqrt(D)) V written out by hand."""
+    K = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]])[:, None, :]
+    V = np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]])[:, None, :]
+    q = np.array([[[2.0, 0.0]]])
+    s = np.array([2.0, 0.0, 2.0]) / math.sqrt(2.0)
+    p = np.exp(s) / np.exp(s).sum()
+    want = p @ V[:, 0, :]
+    got = O.attention_rows(q, K, V, 2, 1)[0, 0]
+    assert np.allclose(got, want, atol=1e-15)
+
+
+def test_rope_closed_forms():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((4, 3, 8))
+    # position 0 is the identity
+    assert np.array_equal(O.rope(x, np.zeros(4), 10000.0), x)
+    # D = 2, theta irrelevant (exponent 0): plain rotation by `pos` radians of the pair (x0, x1)
+    v = np.array([[[1.0, 0.0]]])
+    out = O.rope(v, np.array([0.5]), 123.0)[0, 0]
+    assert np.allclose(out, [math.cos(0.5), math.sin(0.5)], atol=1e-15)
+    # frequencies: pair i of D=4 turns by pos * theta^(-2i/4)
+    v = np.array([[[1.0, 1.0, 0.0, 0.0]]])
+    out = O.rope(v, np.array([3.0]), 100.0)[0, 0]
+    assert np.allclose(out, [math.cos(3.0), math.cos(0.3), math.sin(3.0), math.sin(0.3)], atol=1e-15)
+    # norm preserving per pair; relative-position property <R_a q, R_b k> = <q, R_{b-a} k>
+    y = O.rope(x, np.array([3, 7, 11, 200]), 10000.0)
+    assert np.allclose(x[..., :4] ** 2 + x[..., 4:] ** 2, y[..., :4] ** 2 + y[..., 4:] ** 2)
+    qv, kv = rng.standard_normal((1, 1, 8)), rng.standard_normal((1, 1, 8))
+    lhs = (O.rope(qv, np.array([5]), 1e4) * O.rope(kv, np.array([12]), 1e4)).sum()
+    rhs = (qv * O.rope(kv, np.array([7]), 1e4)).sum()
+    assert abs(lhs - rhs) < 1e-12
+
+
+def test_rmsnorm_and_silu_closed_forms():
+    x = np.array([[3.0, 4.0]])
+    g = np.array([2.0, 0.5])
+    want = x / math.sqrt((9 + 16) / 2 + 1e-5) * g
+    assert np.allclose(O.rmsnorm(x, g, 1e-5), want, atol=1e-15)
+    # scale invariance when eps -> 0
+    assert np.allclose(O.rmsnorm(5 * x, g, 0.0), O.rmsnorm(x, g, 0.0))
+    z = np.array([-2.0, 0.0, 1.5])
+    assert np.allclose(O.silu(z), z * (1 / (1 + np.exp(-z))))
+    assert O.silu(np.array([0.0]))[0] == 0.0
+
+
+def test_bf16_round_matches_torch_conversion():
+    g = torch.Generator().manual_seed(0)
+    x = torch.randn(20000, generator=g, dtype=torch.float32) * 3
+    # exact ties and edge values
+    edge = torch.tensor([1.0, 1.00390625, 1.01171875, -1.00390625, 0.0, 65280.0, 1e-30, 3.140625])
+    x = torch.cat([x, edge])
+    want = x.to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.bf16_round(x.to(torch.float64).numpy())
+    assert np.array_equal(got, want)
+    assert O.bf16_round(np.zeros((2, 3))).shape == (2, 3)
+
+
+def test_round_points_only_touch_storage_tensors():
+    """bf16 mode changes results by about bf16 precision and no more; exact mode is untouched."""
+    shape = synth.scaled_shape(SMALL, dtype="bf16")
+    w = synth.SynthWeights(shape, seed=11, std=0.2)
+    toks = synth.context_tokens(12, shape.vocab, seed=8)
+    a = O.prefill(oracle_model(shape, w, "exact"), toks)["logits"]
+    b = O.prefill(oracle_model(shape, w, "bf16"), toks)["logits"]
+    err = np.abs(a - b).max() / np.abs(a).max()
+    assert 1e-5 < err < 5e-2
