@@ -1,0 +1,205 @@
+/*
+ * sled.h -- C ABI of the MI355X (gfx950) library for the server-side batched
+ * verification step of SLED (arXiv 2506.09397).
+ *
+ * The paper's server queues verification requests from many edge devices, batches
+ * them, runs ONE forward pass of a shared target LLM over every request's draft
+ * tokens and applies the speculative-decoding acceptance rule (Sec. 3.1, Sec. 3.2,
+ * Sec. 3.4).  This library is that step and nothing else:
+ *
+ *   sled_verify_batch   target logits for a ragged batch of requests, each scored on
+ *                       top of its own cached context (Sec. 3.1 "one single
+ *                       forwarding"; Sec. 3.4 batching of heterogeneous devices)
+ *   sled_accept         accepted-prefix length and one corrective / bonus token per
+ *                       request (Eq. 1 and the resampling rule of Sec. 3.1; the
+ *                       feedback message of Sec. 3.2)
+ *   sled_kv_append      bring a request's context K/V into the server-side cache, or
+ *                       commit the K/V of the tokens just accepted (the iterate-until-
+ *                       done loop of Sec. 3.2)
+ *
+ * General rules
+ *   - Plain C.  Every function returns SLED_OK (0) or a negative error code; nothing
+ *     throws or aborts.  sled_last_error() gives a message for the calling thread.
+ *   - Pointers marked "dev" are device (HBM) pointers owned by the caller; the library
+ *     never frees or keeps them beyond the work it enqueues.  Pointers marked "host"
+ *     are ordinary host memory, read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
+ *     work is enqueued on it and the calls return without waiting for it, except where
+ *     stated.  Calls that touch the same pool must be issued on one stream or be ordered
+ *     by the caller.
+ *   - The library owns what sits behind its handles: packed weights, the paged K/V pool.
+ *   - Handles are not thread-safe; use one thread per handle or lock outside.
+ *
+ * Request layout.  Request i has L_i context tokens in the pool, one pending token (the
+ * last committed token, whose K/V is not cached yet) and k_i draft tokens.  Its
+ * n_i = k_i + 1 query tokens [pending, draft_1 .. draft_k] sit at positions
+ * L_i .. L_i + k_i.  A batch packs all requests' query tokens back to back:
+ * T = sum_i (k_i + 1) rows, request-major.  Logits row j of a request is the target
+ * distribution of the token that follows its j-th query token: row j-1 judges draft j,
+ * row k_i yields the bonus token.
+ */
+#ifndef SLED_H
+#define SLED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SLED_API __attribute__((visibility("default")))
+
+/* ---- status codes -------------------------------------------------------------- */
+#define SLED_OK       0
+#define SLED_EINVAL  (-1)   /* bad pointer, shape, range or unsupported configuration  */
+#define SLED_ENOMEM  (-2)   /* page pool or request table exhausted, or allocation failed */
+#define SLED_ESTATE  (-3)   /* call out of order (e.g. commit without a preceding verify) */
+#define SLED_EHIP    (-4)   /* the HIP runtime reported an error                         */
+
+/* ---- enums --------------------------------------------------------------------- */
+#define SLED_F32   0        /* weights, activations and K/V stored as float32 */
+#define SLED_BF16  1        /* stored as bfloat16; sums, softmax, residual stream, logits in float32 */
+
+#define SLED_GREEDY 0       /* exact match against the target's argmax chain */
+#define SLED_SAMPLE 1       /* speculative sampling, Eq. 1 */
+
+/* tensor ids for sled_model_load; linear weights are [out_features, in_features] row-major */
+#define SLED_T_EMBED    0   /* [vocab, d_model]                         (layer ignored) */
+#define SLED_T_WQ       1   /* [n_q_heads*head_dim, d_model]                            */
+#define SLED_T_WK       2   /* [n_kv_heads*head_dim, d_model]                           */
+#define SLED_T_WV       3   /* [n_kv_heads*head_dim, d_model]                           */
+#define SLED_T_WO       4   /* [d_model, n_q_heads*head_dim]                            */
+#define SLED_T_WGATE    5   /* [d_ffn, d_model]                                         */
+#define SLED_T_WUP      6   /* [d_ffn, d_model]                                         */
+#define SLED_T_WDOWN    7   /* [d_model, d_ffn]                                         */
+#define SLED_T_G_ATTN   8   /* [d_model] RMSNorm gain before attention                  */
+#define SLED_T_G_MLP    9   /* [d_model] RMSNorm gain before the MLP                    */
+#define SLED_T_G_FINAL 10   /* [d_model] final RMSNorm gain             (layer ignored) */
+#define SLED_T_LM_HEAD 11   /* [vocab, d_model]                         (layer ignored) */
+
+typedef struct sled_model  sled_model;
+typedef struct sled_kvpool sled_kvpool;
+
+/* LLaMA-family decoder (Sec. 4): pre-norm, RMSNorm, rotary embedding with the half-split
+ * pairing (i, i + head_dim/2), grouped-query attention (query head h reads kv head
+ * h / (n_q_heads/n_kv_heads)), SwiGLU, no biases, untied LM head. */
+typedef struct sled_shape {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;        /* SLED_F32 or SLED_BF16 */
+    float   rms_eps;
+    float   rope_theta;
+    int32_t page_size;    /* tokens per K/V page; must be 16 */
+    int32_t k_max;        /* largest number of draft tokens in one request (<= 15) */
+} sled_shape;
+
+/* ---- model --------------------------------------------------------------------- */
+
+/* Allocates device storage for all weights of `shape` in the library's packed layout.
+ * Supported: SLED_BF16 with head_dim 128, d_model and d_ffn multiples of 128, vocab a
+ * multiple of 16, (n_q_heads/n_kv_heads)*(k_max+1) <= 80; SLED_F32 with head_dim 64 or 128.
+ * Errors: SLED_EINVAL (unsupported shape), SLED_ENOMEM. */
+SLED_API int sled_model_create(const sled_shape* shape /*host*/, sled_model** out);
+
+/* Repacks one tensor from the caller's row-major array `src` (dev, model dtype) into the
+ * model.  `layer` in [0, n_layers) for per-layer tensors.  Asynchronous on `stream`; `src`
+ * may be freed once the stream has passed this point.  Errors: SLED_EINVAL. */
+SLED_API int sled_model_load(sled_model* m, int tensor_id, int layer, const void* src /*dev*/, void* stream);
+
+SLED_API int sled_model_destroy(sled_model* m);
+
+/* ---- paged K/V pool -------------------------------------------------------------- */
+
+/* A pool of `n_pages` pages of 16 tokens (all layers, K and V) shared by up to
+ * `max_requests` open requests.  The paper leaves server-side K/V caching to future work
+ * (Sec. 5); keeping each device's context resident between rounds is this library's
+ * reading of "each request carries its context".  K is stored already rotated. */
+SLED_API int sled_kvpool_create(const sled_model* m, int64_t n_pages, int max_requests, sled_kvpool** out);
+
+/* Opens an empty request (L = 0) and returns its id.  Errors: SLED_ENOMEM. */
+SLED_API int sled_kvpool_open(sled_kvpool* p, int* req_id /*host out*/);
+
+/* Returns the request's pages to the pool.  Errors: SLED_EINVAL (unknown id). */
+SLED_API int sled_kvpool_close(sled_kvpool* p, int req_id);
+
+/* Waits for `stream`, then writes the exact committed context length of each listed request
+ * to lens (host out, B ints) and tightens the host-side page accounting to it. */
+SLED_API int sled_kvpool_lengths(sled_kvpool* p, int B, const int* req_ids /*host*/, int* lens /*host out*/, void* stream);
+
+SLED_API int sled_kvpool_destroy(sled_kvpool* p);
+
+/* Two uses, chosen by accept_len:
+ *
+ * (1) accept_len == NULL: append n_tokens[i] tokens of externally produced K/V to request
+ *     req_ids[i].  k_src[i] and v_src[i] (host arrays of B dev pointers) each point to
+ *     [n_layers, n_tokens[i], n_kv_heads, head_dim] in the model dtype; K already rotated
+ *     for positions L_i .. L_i + n_tokens[i] - 1.  L_i grows by n_tokens[i].
+ *
+ * (2) accept_len != NULL (dev, B int32, as written by sled_accept): commit the K/V that the
+ *     last sled_verify_batch staged for these requests: the pending token and the first
+ *     accept_len[i] drafts become context, L_i += accept_len[i] + 1.  No data moves; the
+ *     rejected tokens' slots are overwritten by the next verify.  n_tokens, k_src, v_src
+ *     are ignored.  Requests must be the ones of the last verify (SLED_ESTATE otherwise).
+ *
+ * Errors: SLED_EINVAL, SLED_ENOMEM (no free page), SLED_ESTATE. */
+SLED_API int sled_kv_append(sled_kvpool* p, int B, const int* req_ids /*host*/, const int* n_tokens /*host*/,
+                   const void* const* k_src /*host array of dev ptrs*/, const void* const* v_src,
+                   const int32_t* accept_len /*dev or NULL*/, void* stream);
+
+/* ---- the verification step ------------------------------------------------------- */
+
+/* Bytes of scratch sled_verify_batch needs for batches of at most B_max requests, T_max
+ * packed rows and ctx_tokens_max total context tokens (sum of L_i + k_i + 1). */
+SLED_API size_t sled_verify_workspace_bytes(const sled_model* m, int B_max, int T_max, int64_t ctx_tokens_max);
+
+/* One batched verification forward.
+ *   req_ids[B], k[B]   host; 0 <= k[i] <= k_max (k[i] = 0 is a plain decode step); a request
+ *                      may appear only once in a batch
+ *   tokens[T]          dev int32, packed [pending, draft_1..draft_k] per request; ids outside
+ *                      [0, vocab) are clamped into range
+ *   logits[T, vocab]   dev float32 out, row-major, row order = tokens order
+ *   workspace          dev scratch of at least sled_verify_workspace_bytes(...) bytes,
+ *                      256-byte aligned; contents are undefined afterwards
+ * Stages the new tokens' K/V in the requests' tail slots (positions L_i .. L_i + k_i) but does
+ * not change L_i: a verify that is never committed leaves the pool logically unchanged and can
+ * simply be issued again (the retry of Sec. 3.3).  Results for a request do not depend on the
+ * other requests in the batch.
+ * Errors: SLED_EINVAL (bad k, unknown or duplicate request, small workspace), SLED_ENOMEM
+ * (no free page for the staged tokens). */
+SLED_API int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int* req_ids /*host*/, const int* k /*host*/,
+                      const int32_t* tokens /*dev*/, float* logits /*dev*/,
+                      void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
+/* Bytes of scratch sled_accept needs for T packed rows. */
+SLED_API size_t sled_accept_workspace_bytes(int B, int T, int vocab);
+
+/* Acceptance on given logits (usable without a model).
+ *   mode          SLED_GREEDY: accept_len[i] = number of leading drafts equal to the argmax of
+ *                 their judging row (lowest id on ties); out_token[i] = argmax of the row after
+ *                 the last accepted draft.
+ *                 SLED_SAMPLE: with p = softmax(logits_row / temperature), draft d judged by
+ *                 that row is accepted iff u_acc * q(d) <= p(d) (probability min(1, p/q), Eq. 1);
+ *                 at the first rejection out_token is drawn from max(0, p - q) normalised, by
+ *                 inverse CDF over ascending token ids with u_smp[i]; if no draft is rejected
+ *                 the bonus token is drawn the same way from the last row's p.
+ *   k[B]          host
+ *   logits[T,V]   dev float32; tokens[T] dev int32 (same packing as sled_verify_batch)
+ *   draft_q       dev float32 [sum k, V] probabilities, one row per draft, request-major
+ *                 (SLED_SAMPLE only; may be NULL for SLED_GREEDY, as may u_acc, u_smp)
+ *   u_acc[sum k], u_smp[B]  dev float32 uniforms in [0, 1)
+ *   accept_len[B], out_token[B]  dev int32 out; 0 <= accept_len[i] <= k[i]
+ * Inputs must be finite.  Errors: SLED_EINVAL. */
+SLED_API int sled_accept(int mode, int B, const int* k /*host*/, int vocab, float temperature,
+                const float* logits /*dev*/, const int32_t* tokens /*dev*/,
+                const float* draft_q /*dev*/, const float* u_acc /*dev*/, const float* u_smp /*dev*/,
+                int32_t* accept_len /*dev out*/, int32_t* out_token /*dev out*/,
+                void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
+/* ---- errors ---------------------------------------------------------------------- */
+SLED_API const char* sled_strerror(int code);
+SLED_API const char* sled_last_error(void);   /* message of the last failing call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLED_H */

@@ -29,8 +29,9 @@ h // group), SwiGLU MLP, no biases, untied LM head.
 Storage-rounding option.  A model whose storage type is bf16 keeps some tensors in
 bf16 between operators.  With round_points="bf16" the oracle rounds (to nearest,
 ties to even) exactly those tensors and nothing else: the normalised activations fed
-to the projections, q/k/v after rotation, the attention output, and the SwiGLU
-product.  All sums, softmax, the residual stream and the logits stay float64.
+to the projections, q/k/v after rotation, the softmax numerators that multiply V
+(see attention_rows), the attention output, and the SwiGLU product.  All sums, the
+softmax denominator, the residual stream and the logits stay float64.
 round_points="exact" rounds nothing.
 
 Pins (tests/test_oracle_*.py, no GPU): Hugging Face's LlamaForCausalLM in float64
@@ -45,6 +46,8 @@ import math
 from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
+
+LOG2E = 1.4426950408889634
 
 
 # --------------------------------------------------------------------------- rounding
@@ -89,12 +92,19 @@ def silu(z: np.ndarray) -> np.ndarray:
     return z / (1.0 + np.exp(-z))
 
 
-def attention_rows(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int, group: int) -> np.ndarray:
+def attention_rows(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int, group: int,
+                   round_points: str = "exact") -> np.ndarray:
     """Attention of n query rows that sit at positions n_ctx .. n_ctx+n-1.
 
     q[n, Hq, D]; K, V[n_ctx + n, Hkv, D] (context keys first, then the n new keys).
     Row j attends to keys 0 .. n_ctx + j: the whole context and the new keys up to
-    itself.  Scores are scaled by 1/sqrt(D).  Returns [n, Hq, D]."""
+    itself.  Scores are scaled by 1/sqrt(D).  Returns [n, Hq, D].
+
+    round_points="bf16": the softmax numerators that multiply V are stored in bf16.  They
+    are taken relative to a power of two, p = 2^(t - M) with t the score in log2 units and
+    M the smallest whole number >= max t, because only then is their rounding independent
+    of the reference (scaling by 2^n commutes with rounding).  The denominator sums the
+    unrounded numerators."""
     n, Hq, D = q.shape
     out = np.empty_like(q)
     scale = 1.0 / math.sqrt(D)
@@ -103,8 +113,13 @@ def attention_rows(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int, grou
         for j in range(n):
             m = n_ctx + j + 1
             s = (K[:m, g, :] @ q[j, h, :]) * scale
-            p = np.exp(s - s.max())
-            out[j, h, :] = (p @ V[:m, g, :]) / p.sum()
+            if round_points == "exact":
+                p = np.exp(s - s.max())
+                out[j, h, :] = (p @ V[:m, g, :]) / p.sum()
+            else:
+                t = s * LOG2E
+                p = np.exp2(t - math.ceil(t.max()))
+                out[j, h, :] = (bf16_round(p) @ V[:m, g, :]) / p.sum()
     return out
 
 
@@ -146,7 +161,7 @@ def layer_rows(model: OracleModel, W: Dict[str, np.ndarray], h: np.ndarray, posi
     v = R(v)
     K_all = np.concatenate([K_ctx, k], axis=0)
     V_all = np.concatenate([V_ctx, v], axis=0)
-    o = R(attention_rows(q, K_all, V_all, K_ctx.shape[0], model.group)).reshape(n, Hq * D)
+    o = R(attention_rows(q, K_all, V_all, K_ctx.shape[0], model.group, model.round_points)).reshape(n, Hq * D)
     h = h + o @ W["wo"].T
     x = R(rmsnorm(h, W["g_mlp"], model.rms_eps))
     a = R(silu(x @ W["wg"].T) * (x @ W["wu"].T))

@@ -1,0 +1,597 @@
+// Host side of libsled: handles, argument checks, page accounting, the per-step metadata blob
+// (ragged packing: row -> request map, page lists, attention work list) and the launch sequence
+// of one verification step.  No device work is done here except enqueueing kernels and copies.
+#include "sled_internal.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+#include <algorithm>
+#include <new>
+
+// ------------------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+void sled_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* sled_last_error(void) { return g_err; }
+
+extern "C" const char* sled_strerror(int code) {
+    switch (code) {
+        case SLED_OK: return "ok";
+        case SLED_EINVAL: return "invalid argument";
+        case SLED_ENOMEM: return "out of pages, request slots or memory";
+        case SLED_ESTATE: return "call out of order";
+        case SLED_EHIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------------------------------------ model
+static int model_alloc(sled_model* m, void** out, size_t bytes) {
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) SLED_FAIL(SLED_ENOMEM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    m->allocs.push_back(p);
+    *out = p;
+    return SLED_OK;
+}
+
+extern "C" int sled_model_create(const sled_shape* shape, sled_model** out) {
+    if (!shape || !out) SLED_FAIL(SLED_EINVAL, "sled_model_create: null argument");
+    const sled_shape& s = *shape;
+    if (s.n_layers < 1 || s.d_model < 8 || s.n_q_heads < 1 || s.n_kv_heads < 1 || s.head_dim < 2 || s.d_ffn < 8 ||
+        s.vocab < 2)
+        SLED_FAIL(SLED_EINVAL, "sled_model_create: non-positive dimension");
+    if (s.n_q_heads % s.n_kv_heads) SLED_FAIL(SLED_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+    if (s.page_size != 16) SLED_FAIL(SLED_EINVAL, "page_size must be 16");
+    if (s.k_max < 0 || s.k_max > 15) SLED_FAIL(SLED_EINVAL, "k_max must be in [0, 15]");
+    if (!(s.rms_eps >= 0.f) || !(s.rope_theta > 0.f)) SLED_FAIL(SLED_EINVAL, "bad rms_eps or rope_theta");
+    const int G = s.n_q_heads / s.n_kv_heads;
+    if (s.dtype == SLED_BF16) {
+        if (s.head_dim != 128) SLED_FAIL(SLED_EINVAL, "bf16 models need head_dim 128");
+        if (s.d_model % 128 || s.d_ffn % 128) SLED_FAIL(SLED_EINVAL, "bf16 models need d_model and d_ffn multiples of 128");
+        if (s.vocab % 16) SLED_FAIL(SLED_EINVAL, "bf16 models need vocab a multiple of 16");
+        if (G * (s.k_max + 1) > 80) SLED_FAIL(SLED_EINVAL, "(n_q_heads/n_kv_heads)*(k_max+1) must be <= 80");
+    } else if (s.dtype == SLED_F32) {
+        if (s.head_dim != 64 && s.head_dim != 128) SLED_FAIL(SLED_EINVAL, "fp32 models need head_dim 64 or 128");
+        if (s.d_model % 8 || s.d_ffn % 8) SLED_FAIL(SLED_EINVAL, "fp32 models need d_model and d_ffn multiples of 8");
+    } else {
+        SLED_FAIL(SLED_EINVAL, "unknown dtype %d", s.dtype);
+    }
+    sled_model* m = new (std::nothrow) sled_model();
+    if (!m) SLED_FAIL(SLED_ENOMEM, "host allocation failed");
+    m->s = s;
+    m->elem = s.dtype == SLED_BF16 ? 2 : 4;
+    m->n_qkv = (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim;
+    const size_t d = s.d_model, F = s.d_ffn, V = s.vocab, HD = (size_t)s.n_q_heads * s.head_dim;
+    int rc = SLED_OK;
+    auto A = [&](void** p, size_t bytes) {
+        if (rc == SLED_OK) rc = model_alloc(m, p, bytes);
+    };
+    A(&m->embed, V * d * m->elem);
+    A(&m->lm_head, V * d * m->elem);
+    A(reinterpret_cast<void**>(&m->g_final), d * sizeof(float));
+    m->layers.resize(s.n_layers);
+    for (int l = 0; l < s.n_layers && rc == SLED_OK; l++) {
+        sled_layer_weights& w = m->layers[l];
+        A(&w.w_qkv, (size_t)m->n_qkv * d * m->elem);
+        A(&w.w_o, d * HD * m->elem);
+        A(&w.w_gu, 2 * F * d * m->elem);
+        A(&w.w_down, d * F * m->elem);
+        A(reinterpret_cast<void**>(&w.g_attn), d * sizeof(float));
+        A(reinterpret_cast<void**>(&w.g_mlp), d * sizeof(float));
+    }
+    if (rc != SLED_OK) {
+        sled_model_destroy(m);
+        return rc;
+    }
+    *out = m;
+    return SLED_OK;
+}
+
+extern "C" int sled_model_destroy(sled_model* m) {
+    if (!m) return SLED_OK;
+    for (void* p : m->allocs) (void)hipFree(p);
+    delete m;
+    return SLED_OK;
+}
+
+extern "C" int sled_model_load(sled_model* m, int tensor_id, int layer, const void* src, void* stream) {
+    if (!m || !src) SLED_FAIL(SLED_EINVAL, "sled_model_load: null argument");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const sled_shape& s = m->s;
+    const int d = s.d_model, F = s.d_ffn, D = s.head_dim, HD = s.n_q_heads * D, KD = s.n_kv_heads * D;
+    const bool per_layer = tensor_id >= SLED_T_WQ && tensor_id <= SLED_T_G_MLP;
+    if (per_layer && (layer < 0 || layer >= s.n_layers)) SLED_FAIL(SLED_EINVAL, "sled_model_load: layer %d out of range", layer);
+    sled_layer_weights* w = per_layer ? &m->layers[layer] : nullptr;
+    switch (tensor_id) {
+        case SLED_T_EMBED:
+            SLED_HIP(hipMemcpyAsync(m->embed, src, (size_t)s.vocab * d * m->elem, hipMemcpyDeviceToDevice, st));
+            return SLED_OK;
+        case SLED_T_WQ: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, HD, d, 0, 1, st);
+        case SLED_T_WK: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, KD, d, HD, 1, st);
+        case SLED_T_WV: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, KD, d, HD + KD, 1, st);
+        case SLED_T_WO: return sled_launch_pack_rows(s.dtype, src, w->w_o, d, HD, 0, 1, st);
+        case SLED_T_WGATE: return sled_launch_pack_rows(s.dtype, src, w->w_gu, F, d, 0, 2, st);
+        case SLED_T_WUP: return sled_launch_pack_rows(s.dtype, src, w->w_gu, F, d, 1, 2, st);
+        case SLED_T_WDOWN: return sled_launch_pack_rows(s.dtype, src, w->w_down, d, F, 0, 1, st);
+        case SLED_T_G_ATTN: return sled_launch_copy_gain(s.dtype, src, w->g_attn, d, st);
+        case SLED_T_G_MLP: return sled_launch_copy_gain(s.dtype, src, w->g_mlp, d, st);
+        case SLED_T_G_FINAL: return sled_launch_copy_gain(s.dtype, src, m->g_final, d, st);
+        case SLED_T_LM_HEAD: return sled_launch_pack_rows(s.dtype, src, m->lm_head, s.vocab, d, 0, 1, st);
+        default: SLED_FAIL(SLED_EINVAL, "sled_model_load: unknown tensor id %d", tensor_id);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ pool
+typedef sled_kvpool::stage_slot sled_stage_slot;
+
+static int slot_alloc(sled_stage_slot& s, size_t cap) {
+    SLED_HIP(hipHostMalloc(reinterpret_cast<void**>(&s.host), cap * sizeof(int32_t), hipHostMallocDefault));
+    SLED_HIP(hipMalloc(reinterpret_cast<void**>(&s.dev), cap * sizeof(int32_t)));
+    return SLED_OK;
+}
+
+// next staging slot with room for n ints; waits until the work that last used it has finished
+static int stage_acquire(sled_kvpool* p, size_t n, sled_stage_slot** out) {
+    sled_kvpool* pv = p;
+    if (n > pv->stage_cap) {
+        // grow every slot (rare: only when a batch is larger than anything seen before)
+        size_t cap = std::max(n, pv->stage_cap * 2);
+        for (int i = 0; i < sled_kvpool::RING; i++) {
+            sled_stage_slot& s = pv->slot[i];
+            if (s.pending) SLED_HIP(hipEventSynchronize(s.ev));
+            s.pending = false;
+            (void)hipHostFree(s.host);
+            (void)hipFree(s.dev);
+            int rc = slot_alloc(s, cap);
+            if (rc != SLED_OK) return rc;
+        }
+        pv->stage_cap = cap;
+    }
+    sled_stage_slot& s = pv->slot[pv->stage_next];
+    pv->stage_next = (pv->stage_next + 1) % sled_kvpool::RING;
+    if (s.pending) SLED_HIP(hipEventSynchronize(s.ev));
+    s.pending = false;
+    *out = &s;
+    return SLED_OK;
+}
+
+static int stage_release(sled_stage_slot* s, hipStream_t st) {
+    SLED_HIP(hipEventRecord(s->ev, st));
+    s->pending = true;
+    return SLED_OK;
+}
+
+extern "C" int sled_kvpool_create(const sled_model* m, int64_t n_pages, int max_requests, sled_kvpool** out) {
+    if (!m || !out || n_pages < 1 || max_requests < 1) SLED_FAIL(SLED_EINVAL, "sled_kvpool_create: bad argument");
+    if (n_pages > (int64_t)1 << 30) SLED_FAIL(SLED_EINVAL, "sled_kvpool_create: too many pages");
+    sled_kvpool* p = new (std::nothrow) sled_kvpool();
+    if (!p) SLED_FAIL(SLED_ENOMEM, "host allocation failed");
+    p->m = m;
+    p->n_pages = n_pages;
+    p->max_requests = max_requests;
+    p->page_head_elems = (size_t)16 * m->s.head_dim;
+    p->k_pool = p->v_pool = nullptr;
+    p->len_dev = nullptr;
+    for (int i = 0; i < sled_kvpool::RING; i++) p->slot[i] = sled_stage_slot{nullptr, nullptr, nullptr, false};
+    p->stage_cap = 0;
+    p->stage_next = 0;
+    const size_t bytes = (size_t)m->s.n_layers * n_pages * m->s.n_kv_heads * p->page_head_elems * m->elem;
+    auto fail = [&](int code, const char* what, hipError_t e) {
+        sled_set_error("sled_kvpool_create: %s failed: %s", what, hipGetErrorString(e));
+        sled_kvpool_destroy(p);
+        return code;
+    };
+    hipError_t e;
+    if ((e = hipMalloc(&p->k_pool, bytes)) != hipSuccess) return fail(SLED_ENOMEM, "hipMalloc(K pool)", e);
+    if ((e = hipMalloc(&p->v_pool, bytes)) != hipSuccess) return fail(SLED_ENOMEM, "hipMalloc(V pool)", e);
+    if ((e = hipMalloc(reinterpret_cast<void**>(&p->len_dev), max_requests * sizeof(int32_t))) != hipSuccess)
+        return fail(SLED_ENOMEM, "hipMalloc(lengths)", e);
+    // pages never written hold zeros (read only under the mask, but keep them finite)
+    if ((e = hipMemset(p->k_pool, 0, bytes)) != hipSuccess) return fail(SLED_EHIP, "hipMemset", e);
+    if ((e = hipMemset(p->v_pool, 0, bytes)) != hipSuccess) return fail(SLED_EHIP, "hipMemset", e);
+    if ((e = hipMemset(p->len_dev, 0, max_requests * sizeof(int32_t))) != hipSuccess) return fail(SLED_EHIP, "hipMemset", e);
+    p->stage_cap = 1 << 16;
+    for (int i = 0; i < sled_kvpool::RING; i++) {
+        if (slot_alloc(p->slot[i], p->stage_cap) != SLED_OK) {
+            sled_kvpool_destroy(p);
+            return SLED_ENOMEM;
+        }
+        if ((e = hipEventCreateWithFlags(&p->slot[i].ev, hipEventDisableTiming)) != hipSuccess)
+            return fail(SLED_EHIP, "hipEventCreate", e);
+    }
+    if ((e = hipDeviceSynchronize()) != hipSuccess) return fail(SLED_EHIP, "hipDeviceSynchronize", e);
+    p->reqs.resize(max_requests);
+    p->free_pages.reserve(n_pages);
+    for (int64_t i = n_pages - 1; i >= 0; i--) p->free_pages.push_back((int)i);
+    *out = p;
+    return SLED_OK;
+}
+
+extern "C" int sled_kvpool_destroy(sled_kvpool* p) {
+    if (!p) return SLED_OK;
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < sled_kvpool::RING; i++) {
+        if (p->slot[i].host) (void)hipHostFree(p->slot[i].host);
+        if (p->slot[i].dev) (void)hipFree(p->slot[i].dev);
+        if (p->slot[i].ev) (void)hipEventDestroy(p->slot[i].ev);
+    }
+    if (p->k_pool) (void)hipFree(p->k_pool);
+    if (p->v_pool) (void)hipFree(p->v_pool);
+    if (p->len_dev) (void)hipFree(p->len_dev);
+    delete p;
+    return SLED_OK;
+}
+
+extern "C" int sled_kvpool_open(sled_kvpool* p, int* req_id) {
+    if (!p || !req_id) SLED_FAIL(SLED_EINVAL, "sled_kvpool_open: null argument");
+    for (int i = 0; i < p->max_requests; i++)
+        if (!p->reqs[i].open) {
+            // a closed slot's device length may be stale: the first append or verify after opening
+            // needs L = 0, so reset it in stream order of the default stream, synchronously (rare call)
+            int32_t zero = 0;
+            SLED_HIP(hipMemcpy(p->len_dev + i, &zero, sizeof(zero), hipMemcpyHostToDevice));
+            p->reqs[i] = sled_request();
+            p->reqs[i].open = true;
+            *req_id = i;
+            return SLED_OK;
+        }
+    SLED_FAIL(SLED_ENOMEM, "sled_kvpool_open: all %d request slots are in use", p->max_requests);
+}
+
+extern "C" int sled_kvpool_close(sled_kvpool* p, int req_id) {
+    if (!p || req_id < 0 || req_id >= p->max_requests || !p->reqs[req_id].open)
+        SLED_FAIL(SLED_EINVAL, "sled_kvpool_close: request %d is not open", req_id);
+    // work that still reads these pages must have finished before they are handed out again
+    SLED_HIP(hipDeviceSynchronize());
+    for (int pg : p->reqs[req_id].pages) p->free_pages.push_back(pg);
+    p->reqs[req_id] = sled_request();
+    p->last_batch.erase(std::remove(p->last_batch.begin(), p->last_batch.end(), req_id), p->last_batch.end());
+    return SLED_OK;
+}
+
+static int check_requests(sled_kvpool* p, int B, const int* req_ids, const char* who) {
+    if (B < 1) SLED_FAIL(SLED_EINVAL, "%s: empty batch", who);
+    std::vector<char> seen(p->max_requests, 0);
+    for (int i = 0; i < B; i++) {
+        int r = req_ids[i];
+        if (r < 0 || r >= p->max_requests || !p->reqs[r].open) SLED_FAIL(SLED_EINVAL, "%s: request %d is not open", who, r);
+        if (seen[r]) SLED_FAIL(SLED_EINVAL, "%s: request %d appears twice", who, r);
+        seen[r] = 1;
+    }
+    return SLED_OK;
+}
+
+// make sure request r owns pages for `tokens` tokens
+static int ensure_pages(sled_kvpool* p, int r, int tokens) {
+    sled_request& rq = p->reqs[r];
+    const int need = ceil_div(tokens, 16);
+    while ((int)rq.pages.size() < need) {
+        if (p->free_pages.empty()) SLED_FAIL(SLED_ENOMEM, "page pool exhausted (%lld pages)", (long long)p->n_pages);
+        rq.pages.push_back(p->free_pages.back());
+        p->free_pages.pop_back();
+    }
+    return SLED_OK;
+}
+
+extern "C" int sled_kvpool_lengths(sled_kvpool* p, int B, const int* req_ids, int* lens, void* stream) {
+    if (!p || !req_ids || !lens) SLED_FAIL(SLED_EINVAL, "sled_kvpool_lengths: null argument");
+    int rc = check_requests(p, B, req_ids, "sled_kvpool_lengths");
+    if (rc != SLED_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SLED_HIP(hipStreamSynchronize(st));
+    std::vector<int32_t> all(p->max_requests);
+    SLED_HIP(hipMemcpy(all.data(), p->len_dev, all.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    for (int i = 0; i < B; i++) {
+        sled_request& rq = p->reqs[req_ids[i]];
+        lens[i] = all[req_ids[i]];
+        rq.len_ub = lens[i];
+        const int keep = ceil_div(rq.len_ub, 16);
+        while ((int)rq.pages.size() > keep) {
+            p->free_pages.push_back(rq.pages.back());
+            rq.pages.pop_back();
+        }
+    }
+    return SLED_OK;
+}
+
+extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const int* n_tokens, const void* const* k_src,
+                              const void* const* v_src, const int32_t* accept_len, void* stream) {
+    if (!p || !req_ids) SLED_FAIL(SLED_EINVAL, "sled_kv_append: null argument");
+    int rc = check_requests(p, B, req_ids, "sled_kv_append");
+    if (rc != SLED_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const sled_model* m = p->m;
+    if (accept_len) {
+        // commit what the last verify staged
+        if ((int)p->last_batch.size() != B) SLED_FAIL(SLED_ESTATE, "sled_kv_append: batch differs from the last verify");
+        for (int i = 0; i < B; i++)
+            if (p->last_batch[i] != req_ids[i] || p->reqs[req_ids[i]].staged < 0)
+                SLED_FAIL(SLED_ESTATE, "sled_kv_append: request %d has nothing staged", req_ids[i]);
+        sled_stage_slot* sl;
+        if ((rc = stage_acquire(p, B, &sl)) != SLED_OK) return rc;
+        for (int i = 0; i < B; i++) sl->host[i] = req_ids[i];
+        SLED_HIP(hipMemcpyAsync(sl->dev, sl->host, B * sizeof(int32_t), hipMemcpyHostToDevice, st));
+        if ((rc = sled_launch_len_add(p->len_dev, sl->dev, nullptr, accept_len, B, st)) != SLED_OK) return rc;
+        if ((rc = stage_release(sl, st)) != SLED_OK) return rc;
+        for (int i = 0; i < B; i++) {
+            sled_request& rq = p->reqs[req_ids[i]];
+            rq.len_ub += rq.staged;  // upper bound: every staged row may have been accepted
+            rq.staged = -1;
+        }
+        p->last_batch.clear();
+        return SLED_OK;
+    }
+    if (!n_tokens || !k_src || !v_src) SLED_FAIL(SLED_EINVAL, "sled_kv_append: null argument");
+    size_t need = 2 * (size_t)B;
+    for (int i = 0; i < B; i++) {
+        if (n_tokens[i] < 0 || (n_tokens[i] > 0 && (!k_src[i] || !v_src[i])))
+            SLED_FAIL(SLED_EINVAL, "sled_kv_append: bad entry %d", i);
+        if ((rc = ensure_pages(p, req_ids[i], p->reqs[req_ids[i]].len_ub + n_tokens[i])) != SLED_OK) return rc;
+        need += p->reqs[req_ids[i]].pages.size();
+    }
+    sled_stage_slot* sl;
+    if ((rc = stage_acquire(p, need, &sl)) != SLED_OK) return rc;
+    size_t off = 2 * (size_t)B;
+    std::vector<size_t> page_off(B);
+    for (int i = 0; i < B; i++) {
+        sl->host[i] = req_ids[i];
+        sl->host[B + i] = n_tokens[i];
+        page_off[i] = off;
+        for (int pg : p->reqs[req_ids[i]].pages) sl->host[off++] = pg;
+    }
+    SLED_HIP(hipMemcpyAsync(sl->dev, sl->host, off * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    for (int i = 0; i < B; i++) {
+        if (n_tokens[i] == 0) continue;
+        if ((rc = sled_launch_kv_ingest(m, p, k_src[i], v_src[i], n_tokens[i], req_ids[i], sl->dev + page_off[i], st)) != SLED_OK)
+            return rc;
+    }
+    if ((rc = sled_launch_len_add(p->len_dev, sl->dev, sl->dev + B, nullptr, B, st)) != SLED_OK) return rc;
+    if ((rc = stage_release(sl, st)) != SLED_OK) return rc;
+    for (int i = 0; i < B; i++) {
+        sled_request& rq = p->reqs[req_ids[i]];
+        rq.len_ub += n_tokens[i];
+        rq.staged = -1;
+    }
+    return SLED_OK;
+}
+
+// ------------------------------------------------------------------------------------------ verify
+namespace {
+
+struct ws_plan {
+    size_t h, xa, xo, xf, q, partial, cs, part_o, part_ml, total;
+};
+
+int attn_chunk_pages(int64_t total_page_heads) {
+    // aim at about 1024 work items over the chip, never fewer than 4 pages per item
+    int64_t c = (total_page_heads + 1023) / 1024;
+    if (c < 4) c = 4;
+    c = (c + 3) / 4 * 4;  // four wavefronts share an item's pages
+    return (int)c;
+}
+
+int gemm_split(const sled_model* m, int T, int N, int K) { return sled_gemm_pick_split(m, T, N, K); }
+
+ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
+    const sled_shape& s = m->s;
+    const size_t T_alloc = align_up(T, 128), T_pad = align_up(T, 16);
+    const size_t d = s.d_model, F = s.d_ffn, HD = (size_t)s.n_q_heads * s.head_dim;
+    ws_plan w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += align_up(bytes, 256);
+        return o;
+    };
+    w.h = take(T_alloc * d * sizeof(float));
+    w.xa = take(T_alloc * d * m->elem);
+    w.xo = take(T_alloc * HD * m->elem);
+    w.xf = take(T_alloc * F * m->elem);
+    w.q = take(T_alloc * HD * m->elem);
+    size_t part = 0;
+    part = std::max(part, (size_t)gemm_split(m, T, m->n_qkv, s.d_model) * T_pad * m->n_qkv);
+    part = std::max(part, (size_t)gemm_split(m, T, s.d_model, (int)HD) * T_pad * d);
+    part = std::max(part, (size_t)gemm_split(m, T, s.d_model, s.d_ffn) * T_pad * d);
+    if (s.dtype == SLED_F32) part = std::max(part, T_pad * 2 * F);
+    w.partial = take(part * sizeof(float));
+    w.cs = take((size_t)T * s.head_dim * sizeof(float));
+    w.part_o = take((size_t)n_work * QT * 16 * 128 * sizeof(float));
+    w.part_ml = take((size_t)n_work * 2 * QT * 16 * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+// upper bound of the attention work list: every (request, kv head) rounds its page count up to a
+// whole chunk, and attn_chunk_pages keeps total_page_heads / chunk <= 1024
+int max_work_items(const sled_model* m, int B, int64_t ctx_tokens) {
+    const int64_t page_heads = (ctx_tokens / 16 + 2 * (int64_t)B) * m->s.n_kv_heads;
+    return (int)std::min<int64_t>(page_heads, 1024 + 4) + B * m->s.n_kv_heads;
+}
+
+}  // namespace
+
+extern "C" size_t sled_verify_workspace_bytes(const sled_model* m, int B_max, int T_max, int64_t ctx_tokens_max) {
+    if (!m || B_max < 1 || T_max < 1 || ctx_tokens_max < 0) return 0;
+    const int G = m->s.n_q_heads / m->s.n_kv_heads;
+    const int QT = ceil_div(G * (m->s.k_max + 1), 16);
+    size_t worst = 0;
+    // the split-K choice depends on T only through nothing today, but take the maximum over the
+    // padded sizes anyway so that the bound holds for every T <= T_max
+    worst = plan_workspace(m, T_max, max_work_items(m, B_max, ctx_tokens_max), QT).total;
+    return worst + 256;
+}
+
+extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int* req_ids, const int* k,
+                                 const int32_t* tokens, float* logits, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!m || !p || !req_ids || !k || !tokens || !logits || !workspace) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: null argument");
+    if (p->m != m) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: pool belongs to another model");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: workspace must be 256-byte aligned");
+    int rc = check_requests(p, B, req_ids, "sled_verify_batch");
+    if (rc != SLED_OK) return rc;
+    const sled_shape& s = m->s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int Hkv = s.n_kv_heads, G = s.n_q_heads / Hkv;
+    int T = 0, kmax = 0;
+    for (int i = 0; i < B; i++) {
+        if (k[i] < 0 || k[i] > s.k_max) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: k[%d] = %d outside [0, %d]", i, k[i], s.k_max);
+        T += k[i] + 1;
+        kmax = std::max(kmax, k[i]);
+    }
+    // pages for the staged tokens, attention work list
+    int64_t total_pages = 0;
+    for (int i = 0; i < B; i++) {
+        sled_request& rq = p->reqs[req_ids[i]];
+        if ((rc = ensure_pages(p, req_ids[i], rq.len_ub + k[i] + 1)) != SLED_OK) return rc;
+        total_pages += ceil_div(rq.len_ub + k[i] + 1, 16);
+    }
+    const int chunk = attn_chunk_pages(total_pages * Hkv);
+    std::vector<int32_t> work;
+    std::vector<int32_t> cu_work(B * Hkv + 1);
+    for (int i = 0; i < B; i++) {
+        const int np = ceil_div(p->reqs[req_ids[i]].len_ub + k[i] + 1, 16);
+        for (int g = 0; g < Hkv; g++) {
+            cu_work[i * Hkv + g] = (int)(work.size() / 4);
+            for (int p0 = 0; p0 < np; p0 += chunk) {
+                work.push_back(i);
+                work.push_back(g);
+                work.push_back(p0);
+                work.push_back(std::min(chunk, np - p0));
+            }
+        }
+    }
+    const int n_work = (int)(work.size() / 4);
+    cu_work[B * Hkv] = n_work;
+    const int QT = std::max(1, ceil_div(G * (kmax + 1), 16));
+    const ws_plan wp = plan_workspace(m, T, n_work, QT);
+    if (wp.total > workspace_bytes)
+        SLED_FAIL(SLED_EINVAL, "sled_verify_batch: workspace of %zu bytes, %zu needed", workspace_bytes, wp.total);
+
+    // metadata blob
+    const size_t n_meta = 2 * (size_t)B + 2 * ((size_t)B + 1) + 2 * (size_t)T + (size_t)total_pages + work.size() + cu_work.size();
+    sled_stage_slot* sl;
+    if ((rc = stage_acquire(p, n_meta, &sl)) != SLED_OK) return rc;
+    int32_t* hp = sl->host;
+    size_t o_req = 0, o_k = o_req + B, o_cur = o_k + B, o_cup = o_cur + B + 1, o_rr = o_cup + B + 1, o_rj = o_rr + T,
+           o_pg = o_rj + T, o_wk = o_pg + total_pages, o_cw = o_wk + work.size();
+    int row = 0, pg = 0;
+    for (int i = 0; i < B; i++) {
+        const sled_request& rq = p->reqs[req_ids[i]];
+        hp[o_req + i] = req_ids[i];
+        hp[o_k + i] = k[i];
+        hp[o_cur + i] = row;
+        hp[o_cup + i] = pg;
+        for (int j = 0; j <= k[i]; j++) {
+            hp[o_rr + row] = i;
+            hp[o_rj + row] = j;
+            row++;
+        }
+        const int np = ceil_div(rq.len_ub + k[i] + 1, 16);
+        for (int q = 0; q < np; q++) hp[o_pg + pg++] = rq.pages[q];
+    }
+    hp[o_cur + B] = row;
+    hp[o_cup + B] = pg;
+    memcpy(hp + o_wk, work.data(), work.size() * sizeof(int32_t));
+    memcpy(hp + o_cw, cu_work.data(), cu_work.size() * sizeof(int32_t));
+    SLED_HIP(hipMemcpyAsync(sl->dev, hp, n_meta * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    sled_step_meta meta;
+    meta.req_id = sl->dev + o_req;
+    meta.k = sl->dev + o_k;
+    meta.cu_rows = sl->dev + o_cur;
+    meta.cu_pages = sl->dev + o_cup;
+    meta.row_req = sl->dev + o_rr;
+    meta.row_j = sl->dev + o_rj;
+    meta.pages = sl->dev + o_pg;
+    meta.work = sl->dev + o_wk;
+    meta.cu_work = sl->dev + o_cw;
+    meta.B = B;
+    meta.T = T;
+    meta.n_work = n_work;
+
+    char* ws = static_cast<char*>(workspace);
+    float* h = reinterpret_cast<float*>(ws + wp.h);
+    void* xa = ws + wp.xa;
+    void* xo = ws + wp.xo;
+    void* xf = ws + wp.xf;
+    void* qb = ws + wp.q;
+    float* partial = reinterpret_cast<float*>(ws + wp.partial);
+    float* cs = reinterpret_cast<float*>(ws + wp.cs);
+    float* part_o = reinterpret_cast<float*>(ws + wp.part_o);
+    float* part_ml = reinterpret_cast<float*>(ws + wp.part_ml);
+    const int T_pad = (int)align_up(T, 16);
+    const int d = s.d_model, F = s.d_ffn, HD = s.n_q_heads * s.head_dim;
+    const int sp_qkv = gemm_split(m, T, m->n_qkv, d), sp_o = gemm_split(m, T, d, HD), sp_dn = gemm_split(m, T, d, F);
+
+#define SLED_TRY(x)                        \
+    do {                                   \
+        if ((rc = (x)) != SLED_OK) return rc; \
+    } while (0)
+
+    SLED_TRY(sled_launch_rope_table(m, p, meta, cs, st));
+    SLED_TRY(sled_launch_embed_norm(m, tokens, T, h, xa, m->layers[0].g_attn, st));
+    for (int l = 0; l < s.n_layers; l++) {
+        const sled_layer_weights& w = m->layers[l];
+        SLED_TRY(sled_launch_gemm(m, xa, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, sp_qkv, partial, nullptr, 0, st));
+        SLED_TRY(sled_launch_qkv_rope_store(m, p, meta, l, partial, sp_qkv, T_pad, cs, qb, st));
+        SLED_TRY(sled_launch_attention(m, p, meta, l, qb, part_o, part_ml, xo, QT, st));
+        SLED_TRY(sled_launch_gemm(m, xo, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, sp_o, partial, nullptr, 0, st));
+        SLED_TRY(sled_launch_residual_norm(m, partial, sp_o, T, T_pad, h, xa, w.g_mlp, st));
+        if (s.dtype == SLED_BF16) {
+            SLED_TRY(sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, 1, nullptr, xf, F, st));
+        } else {
+            SLED_TRY(sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, 1, partial, nullptr, 0, st));
+            SLED_TRY(sled_launch_swiglu_f32(partial, T, F, static_cast<float*>(xf), st));
+        }
+        SLED_TRY(sled_launch_gemm(m, xf, w.w_down, T, T_pad, d, F, SLED_EPI_PARTIAL, sp_dn, partial, nullptr, 0, st));
+        const float* next_gain = (l + 1 < s.n_layers) ? m->layers[l + 1].g_attn : m->g_final;
+        SLED_TRY(sled_launch_residual_norm(m, partial, sp_dn, T, T_pad, h, xa, next_gain, st));
+    }
+    SLED_TRY(sled_launch_gemm(m, xa, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, 1, logits, nullptr, 0, st));
+    SLED_TRY(stage_release(sl, st));
+#undef SLED_TRY
+
+    for (int i = 0; i < B; i++) p->reqs[req_ids[i]].staged = k[i] + 1;
+    p->last_batch.assign(req_ids, req_ids + B);
+    return SLED_OK;
+}
+
+// ------------------------------------------------------------------------------------------ accept
+extern "C" size_t sled_accept_workspace_bytes(int B, int T, int vocab) {
+    if (B < 1 || T < 1 || vocab < 2) return 0;
+    return sled_accept_ws_bytes(B, T, 16) + 256;
+}
+
+extern "C" int sled_accept(int mode, int B, const int* k, int vocab, float temperature, const float* logits,
+                           const int32_t* tokens, const float* draft_q, const float* u_acc, const float* u_smp,
+                           int32_t* accept_len, int32_t* out_token, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (!k || !logits || !tokens || !accept_len || !out_token || !workspace) SLED_FAIL(SLED_EINVAL, "sled_accept: null argument");
+    if (mode != SLED_GREEDY && mode != SLED_SAMPLE) SLED_FAIL(SLED_EINVAL, "sled_accept: unknown mode %d", mode);
+    if (B < 1 || B > 1024) SLED_FAIL(SLED_EINVAL, "sled_accept: batch size %d outside [1, 1024]", B);
+    if (vocab < 2 || vocab > 2000000) SLED_FAIL(SLED_EINVAL, "sled_accept: vocab %d unsupported", vocab);
+    if (!(temperature > 0.f)) SLED_FAIL(SLED_EINVAL, "sled_accept: temperature must be positive");
+    int T = 0, nd = 0;
+    for (int i = 0; i < B; i++) {
+        if (k[i] < 0 || k[i] > 255) SLED_FAIL(SLED_EINVAL, "sled_accept: k[%d] = %d outside [0, 255]", i, k[i]);
+        T += k[i] + 1;
+        nd += k[i];
+    }
+    if (mode == SLED_SAMPLE && (!u_smp || (nd > 0 && (!draft_q || !u_acc))))
+        SLED_FAIL(SLED_EINVAL, "sled_accept: sampling needs draft_q, u_acc and u_smp");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_accept: workspace must be 256-byte aligned");
+    const size_t need = sled_accept_ws_bytes(B, T, sled_accept_pick_split(T, vocab));
+    if (need > workspace_bytes) SLED_FAIL(SLED_EINVAL, "sled_accept: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, u_acc, u_smp, accept_len, out_token,
+                              workspace, static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,334 @@
+// Ragged speculative-verify attention over the paged K/V cache.
+//
+// Request i contributes n_i = k_i + 1 query rows at positions L_i .. L_i + k_i.  Row j attends to
+// every context key and to the new keys up to itself: a causal mask that only matters on the last
+// one or two pages.  All G query heads that share a kv head and all n_i rows of the request are
+// stacked into one tile of G * n_i "query rows", so each K/V byte is fetched from HBM once per
+// step and reused G * n_i times (this is the whole arithmetic intensity the step has).
+//
+// bf16 kernel, per work item (request, kv head, run of pages):
+//   S^T[token, qrow] = K_page * Q^T      v_mfma_f32_16x16x32_bf16, K page tile as the A operand
+//   online softmax per qrow              (a lane owns one qrow: reductions over 4 registers and
+//                                         2 cross-lane steps); the running maximum is rounded up
+//                                         to a whole number of log2 units, so the numerators
+//                                         p = 2^(s - M) are rounded to bf16 the same way whatever
+//                                         the page order or the split of the keys over wavefronts
+//   O^T[d, qrow]    += V_page^T * P^T    v_mfma_f32_16x16x16_bf16; the S^T accumulator registers
+//                                        are, unchanged, the P^T operand
+// A page (16 tokens x 128 dims of one kv head) is stored in the pool in operand order, K for the
+// first product and V for the second, so a wavefront reads a whole page with 4 + 4 contiguous
+// 1 KiB loads into registers; there is no LDS traffic in the main loop.  The four wavefronts of a
+// workgroup take alternate pages and merge their (max, sum, O) states through LDS at the end; a
+// second kernel merges the work items of one (request, kv head) in a fixed order and writes the
+// attention output in the operand order of the following projection.
+//
+// fp32 kernel (fp32 models): one wavefront per (row, query head), lanes over keys.
+#include "sled_internal.h"
+
+namespace {
+
+constexpr float NEG_BIG = -1.0e30f;
+
+template <int QT>
+__global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, const int32_t* __restrict__ len_dev,
+                                                         const bf16_t* __restrict__ Q, const bf16_t* __restrict__ k_pool,
+                                                         const bf16_t* __restrict__ v_pool, int64_t n_pages, int layer,
+                                                         int Hq, int Hkv, float scale_log2,
+                                                         float* __restrict__ part_o, float* __restrict__ part_ml) {
+    constexpr int D = 128;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* sh_o = reinterpret_cast<float*>(smem);          // [QT][8][64][4]
+    float* sh_m = sh_o + QT * 8 * 64 * 4;                  // [QT*16]
+    float* sh_l = sh_m + QT * 16;                          // [QT*16]
+
+    const int w = blockIdx.x;
+    const int b = meta.work[4 * w + 0], g = meta.work[4 * w + 1];
+    const int page0 = meta.work[4 * w + 2], npg = meta.work[4 * w + 3];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int G = Hq / Hkv;
+    const int L = len_dev[meta.req_id[b]];
+    const int n = meta.k[b] + 1;
+    const int rows = G * n;
+    const int row0 = meta.cu_rows[b];
+    const int n_valid_pages = (L + n + 15) >> 4;
+    const int page_end = min(page0 + npg, n_valid_pages);
+    const int32_t* pages = meta.pages + meta.cu_pages[b];
+    const int lq = lane & 15, lg = lane >> 4;
+
+    // Q operand tiles: qrow r = qt*16 + lane%16 -> (query position j = r / G, head g*G + r % G)
+    bf16x8_t qf[QT][4];
+    int jrow[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        const int r = qt * 16 + lq;
+        const int j = r / G, hh = r - j * G;
+        jrow[qt] = j;
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            if (r < rows) {
+                qf[qt][ks] = *reinterpret_cast<const bf16x8_t*>(Q + ((size_t)(row0 + j) * Hq + g * G + hh) * D + ks * 32 + lg * 8);
+            } else {
+                for (int e = 0; e < 8; e++) qf[qt][ks][e] = (__bf16)0.0f;
+            }
+        }
+    }
+
+    float m[QT], lsum[QT];
+    float4_t o[QT][8];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        m[qt] = NEG_BIG;
+        lsum[qt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; dt++) o[qt][dt] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    for (int pg = page0 + wv; pg < page_end; pg += 4) {
+        const int phys = pages[pg];
+        const size_t base = (((size_t)layer * n_pages + phys) * Hkv + g) * (16 * D);
+        bf16x8_t kf[4];
+        uint4 vraw[4];
+#pragma unroll
+        for (int c = 0; c < 4; c++) kf[c] = *reinterpret_cast<const bf16x8_t*>(k_pool + base + c * 512 + lane * 8);
+#pragma unroll
+        for (int c = 0; c < 4; c++) vraw[c] = *reinterpret_cast<const uint4*>(v_pool + base + c * 512 + lane * 8);
+        const bool need_mask = (pg * 16 + 15) > L;  // page reaches beyond the context: causal part / tail
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            float4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qt][ks], s, 0, 0, 0);
+            float sv[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                sv[i] = s[i] * scale_log2;
+                if (need_mask) {
+                    const int tokpos = pg * 16 + lg * 4 + i;
+                    if (tokpos > L + jrow[qt]) sv[i] = -INFINITY;
+                }
+            }
+            float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+            // The running reference is kept on whole numbers (scores are in log2 units), so every
+            // rescale below is an exact power of two and the bf16 rounding of p does not depend on
+            // the order in which pages are visited: bf16(2^(s-M)) * 2^(M-M') == bf16(2^(s-M')).
+            const float mnew = fmaxf(m[qt], ceilf(mloc));
+            const float alpha = exp2f(m[qt] - mnew);
+            float p[4];
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                p[i] = exp2f(sv[i] - mnew);
+                psum += p[i];
+            }
+            lsum[qt] = lsum[qt] * alpha + psum;
+            m[qt] = mnew;
+            short4_t pb;
+#pragma unroll
+            for (int i = 0; i < 4; i++) pb[i] = (short)f32_to_bf16(p[i]);
+#pragma unroll
+            for (int dt = 0; dt < 8; dt++) {
+                // V operand for dims dt*16 .. dt*16+15: half of the 16-byte chunk vraw[dt/2]
+                const uint4 r4 = vraw[dt >> 1];
+                uint32_t lo = (dt & 1) ? r4.z : r4.x, hi = (dt & 1) ? r4.w : r4.y;
+                short4_t va;
+                va[0] = (short)(lo & 0xffff);
+                va[1] = (short)(lo >> 16);
+                va[2] = (short)(hi & 0xffff);
+                va[3] = (short)(hi >> 16);
+                float4_t acc = o[qt][dt];
+#pragma unroll
+                for (int i = 0; i < 4; i++) acc[i] *= alpha;
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, acc, 0, 0, 0);
+            }
+        }
+    }
+    // lane-partial sums -> per-qrow sums
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        lsum[qt] += __shfl_xor(lsum[qt], 16);
+        lsum[qt] += __shfl_xor(lsum[qt], 32);
+    }
+    // merge wavefronts 1..3 into wavefront 0 through LDS, one after the other
+    for (int src = 1; src < 4; src++) {
+        if (wv == src) {
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++) {
+                if (lg == 0) {
+                    sh_m[qt * 16 + lq] = m[qt];
+                    sh_l[qt * 16 + lq] = lsum[qt];
+                }
+#pragma unroll
+                for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(sh_o + ((qt * 8 + dt) * 64 + lane) * 4) = o[qt][dt];
+            }
+        }
+        __syncthreads();
+        if (wv == 0) {
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++) {
+                const float m2 = sh_m[qt * 16 + lq], l2 = sh_l[qt * 16 + lq];
+                const float mnew = fmaxf(m[qt], m2);
+                const float a1 = exp2f(m[qt] - mnew), a2 = exp2f(m2 - mnew);
+                lsum[qt] = lsum[qt] * a1 + l2 * a2;
+                m[qt] = mnew;
+#pragma unroll
+                for (int dt = 0; dt < 8; dt++) {
+                    const float4_t o2 = *reinterpret_cast<const float4_t*>(sh_o + ((qt * 8 + dt) * 64 + lane) * 4);
+#pragma unroll
+                    for (int i = 0; i < 4; i++) o[qt][dt][i] = o[qt][dt][i] * a1 + o2[i] * a2;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (wv == 0) {
+        // partial state of work item w: rows qt*16 + lq, dims dt*16 + lg*4 + i
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            const int r = qt * 16 + lq;
+            if (lg == 0) {
+                part_ml[((size_t)w * 2 + 0) * (QT * 16) + r] = m[qt];
+                part_ml[((size_t)w * 2 + 1) * (QT * 16) + r] = lsum[qt];
+            }
+#pragma unroll
+            for (int dt = 0; dt < 8; dt++)
+                *reinterpret_cast<float4_t*>(part_o + ((size_t)w * (QT * 16) + r) * D + dt * 16 + lg * 4) = o[qt][dt];
+        }
+    }
+}
+
+// merge the work items of (request b, kv head g) in ascending page order; write bf16 output in
+// operand order for the O projection: X[t = row0 + j][col = (g*G + hh)*D + d]
+__global__ __launch_bounds__(256) void attn_combine_bf16(sled_step_meta meta, int QT16, int Hq, int Hkv,
+                                                         const float* __restrict__ part_o,
+                                                         const float* __restrict__ part_ml, bf16_t* __restrict__ X) {
+    constexpr int D = 128;
+    const int b = blockIdx.x / Hkv, g = blockIdx.x - b * Hkv;
+    const int G = Hq / Hkv;
+    const int rows = G * (meta.k[b] + 1);
+    const int row0 = meta.cu_rows[b];
+    const int w0 = meta.cu_work[blockIdx.x], w1 = meta.cu_work[blockIdx.x + 1];
+    const int Kdim = Hq * D;
+    for (int e = threadIdx.x; e < rows * (D / 4); e += 256) {
+        const int r = e / (D / 4), d4 = (e - r * (D / 4)) * 4;
+        float M = NEG_BIG;
+        for (int w = w0; w < w1; w++) M = fmaxf(M, part_ml[((size_t)w * 2 + 0) * QT16 + r]);
+        float lsum = 0.f;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int w = w0; w < w1; w++) {
+            const float f = exp2f(part_ml[((size_t)w * 2 + 0) * QT16 + r] - M);
+            lsum += part_ml[((size_t)w * 2 + 1) * QT16 + r] * f;
+            const float4 ov = *reinterpret_cast<const float4*>(part_o + ((size_t)w * QT16 + r) * D + d4);
+            acc.x += ov.x * f;
+            acc.y += ov.y * f;
+            acc.z += ov.z * f;
+            acc.w += ov.w * f;
+        }
+        const float inv = 1.0f / lsum;
+        const int j = r / G, hh = r - j * G;
+        const int t = row0 + j, col = (g * G + hh) * D + d4;
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
+        pk.y = (uint32_t)f32_to_bf16(acc.z * inv) | ((uint32_t)f32_to_bf16(acc.w * inv) << 16);
+        *reinterpret_cast<uint2*>(X + frag_offset(t, col, Kdim)) = pk;
+    }
+}
+
+// fp32 models: one wavefront per (packed row t, query head h); lanes stride over the keys
+template <int D>
+__global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev,
+                                                      const float* __restrict__ Q, const float* __restrict__ k_pool,
+                                                      const float* __restrict__ v_pool, int64_t n_pages, int layer, int Hq,
+                                                      int Hkv, float scale, float* __restrict__ X) {
+    const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const int b = meta.row_req[t], j = meta.row_j[t];
+    const int g = h / (Hq / Hkv);
+    const int nkeys = len_dev[meta.req_id[b]] + j + 1;
+    const int32_t* pages = meta.pages + meta.cu_pages[b];
+    float q[D], o[D];
+    const float* qp = Q + ((size_t)t * Hq + h) * D;
+#pragma unroll
+    for (int d = 0; d < D; d++) {
+        q[d] = qp[d];
+        o[d] = 0.f;
+    }
+    float m = NEG_BIG, l = 0.f;
+    for (int tok = lane; tok < nkeys; tok += 64) {
+        const size_t base = ((((size_t)layer * n_pages + pages[tok >> 4]) * Hkv + g) * 16 + (tok & 15)) * D;
+        const float* kp = k_pool + base;
+        const float* vp = v_pool + base;
+        float s = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; d++) s = fmaf(q[d], kp[d], s);
+        s *= scale;
+        const float mnew = fmaxf(m, s);
+        const float alpha = expf(m - mnew), p = expf(s - mnew);
+        l = l * alpha + p;
+#pragma unroll
+        for (int d = 0; d < D; d++) o[d] = o[d] * alpha + p * vp[d];
+        m = mnew;
+    }
+    float M = m;
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float f = expf(m - M);
+    l *= f;
+    for (int off = 32; off > 0; off >>= 1) l += __shfl_xor(l, off);
+    const float inv = 1.0f / l;
+    float* xp = X + (size_t)t * (Hq * D) + h * D;
+#pragma unroll
+    for (int d = 0; d < D; d++) {
+        float v = o[d] * f;
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+        if (lane == (d & 63)) xp[d] = v * inv;
+    }
+}
+
+}  // namespace
+
+size_t sled_attn_lds_bytes(int QT) { return (size_t)(QT * 8 * 64 * 4 + 2 * QT * 16) * sizeof(float); }
+
+int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
+                          float* part_o, float* part_ml, void* X_out, int QT, hipStream_t st) {
+    const sled_shape& s = m->s;
+    if (s.dtype == SLED_BF16) {
+        const float scale_log2 = 1.4426950408889634f / sqrtf((float)s.head_dim);
+        const size_t lds = sled_attn_lds_bytes(QT);
+        dim3 grid(meta.n_work), blk(256);
+#define SLED_ATTN_CASE(N)                                                                                          \
+    case N:                                                                                                        \
+        hipLaunchKernelGGL(attn_partial_bf16<N>, grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q), \
+                           static_cast<const bf16_t*>(p->k_pool), static_cast<const bf16_t*>(p->v_pool), p->n_pages,   \
+                           layer, s.n_q_heads, s.n_kv_heads, scale_log2, part_o, part_ml);                           \
+        break;
+        switch (QT) {
+            SLED_ATTN_CASE(1)
+            SLED_ATTN_CASE(2)
+            SLED_ATTN_CASE(3)
+            SLED_ATTN_CASE(4)
+            SLED_ATTN_CASE(5)
+            default:
+                SLED_FAIL(SLED_EINVAL, "attention: %d query-row tiles unsupported", QT);
+        }
+#undef SLED_ATTN_CASE
+        SLED_LAUNCH_CHECK();
+        hipLaunchKernelGGL(attn_combine_bf16, dim3(meta.B * s.n_kv_heads), dim3(256), 0, st, meta, QT * 16, s.n_q_heads,
+                           s.n_kv_heads, part_o, part_ml, static_cast<bf16_t*>(X_out));
+        SLED_LAUNCH_CHECK();
+        return SLED_OK;
+    }
+    const float scale = 1.0f / sqrtf((float)s.head_dim);
+    dim3 grid(meta.T, s.n_q_heads);
+    if (s.head_dim == 64)
+        hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(64), 0, st, meta, p->len_dev, static_cast<const float*>(Q),
+                           static_cast<const float*>(p->k_pool), static_cast<const float*>(p->v_pool), p->n_pages, layer,
+                           s.n_q_heads, s.n_kv_heads, scale, static_cast<float*>(X_out));
+    else if (s.head_dim == 128)
+        hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(64), 0, st, meta, p->len_dev, static_cast<const float*>(Q),
+                           static_cast<const float*>(p->k_pool), static_cast<const float*>(p->v_pool), p->n_pages, layer,
+                           s.n_q_heads, s.n_kv_heads, scale, static_cast<float*>(X_out));
+    else
+        SLED_FAIL(SLED_EINVAL, "attention: head_dim %d unsupported for fp32 models", s.head_dim);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}

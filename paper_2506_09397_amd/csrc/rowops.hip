@@ -1,0 +1,371 @@
+// Row-wise operators of the verify step, one workgroup per packed row.  They sit between the
+// projections and do everything that is not a contraction: embedding gather, reduction of the
+// split-K partial sums (fixed order), residual add, RMSNorm, rotary embedding, the scatter of new
+// K/V into the paged cache, SwiGLU for fp32 models, weight repacking at load time.
+//
+// Activations that feed a bf16 projection are written directly in MFMA operand order
+// (frag_offset), so the projection kernels never transpose anything.
+#include "sled_internal.h"
+
+namespace {
+
+__device__ inline float block_sum_256(float x, float* sh /*[4]*/) {
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// store 8 consecutive normalised activations of row t starting at column c0
+template <bool BF16>
+__device__ inline void store_act8(void* X, int t, int c0, int K, const float* v) {
+    if (BF16) {
+        uint32_t w[4];
+        for (int i = 0; i < 4; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4*>(static_cast<bf16_t*>(X) + frag_offset(t, c0, K)) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+        float* p = static_cast<float*>(X) + (size_t)t * K + c0;
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+}
+
+// h[t,:] = E[token]; X[t,:] = rmsnorm(h) * gain
+template <bool BF16>
+__global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restrict__ tokens, const void* __restrict__ E,
+                                                         int V, int d, float eps, const float* __restrict__ gain,
+                                                         float* __restrict__ h, void* __restrict__ X) {
+    __shared__ float sh[4];
+    const int t = blockIdx.x;
+    int tok = tokens[t];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    float ss = 0.f;
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+        float v[8];
+        if (BF16) {
+            uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(E) + (size_t)tok * d + c);
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+            for (int i = 0; i < 4; i++) {
+                v[2 * i] = bf16_to_f32((bf16_t)(w[i] & 0xffff));
+                v[2 * i + 1] = bf16_to_f32((bf16_t)(w[i] >> 16));
+            }
+        } else {
+            const float* p = static_cast<const float*>(E) + (size_t)tok * d + c;
+            for (int i = 0; i < 8; i++) v[i] = p[i];
+        }
+        for (int i = 0; i < 8; i++) {
+            h[(size_t)t * d + c + i] = v[i];
+            ss += v[i] * v[i];
+        }
+    }
+    const float tot = block_sum_256(ss, sh);
+    const float r = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+        float v[8];
+        for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
+        store_act8<BF16>(X, t, c, d, v);
+    }
+}
+
+// h[t,:] += sum_s partial[s][t][:]  (s ascending);  X[t,:] = rmsnorm(h) * gain
+template <bool BF16>
+__global__ __launch_bounds__(256) void residual_norm_kernel(const float* __restrict__ partial, int n_split, int T_pad,
+                                                            int d, float eps, const float* __restrict__ gain,
+                                                            float* __restrict__ h, void* __restrict__ X) {
+    __shared__ float sh[4];
+    const int t = blockIdx.x;
+    float ss = 0.f;
+    for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
+        float4 a = *reinterpret_cast<const float4*>(h + (size_t)t * d + c);
+        for (int s = 0; s < n_split; s++) {
+            float4 p = *reinterpret_cast<const float4*>(partial + ((size_t)s * T_pad + t) * d + c);
+            a.x += p.x;
+            a.y += p.y;
+            a.z += p.z;
+            a.w += p.w;
+        }
+        *reinterpret_cast<float4*>(h + (size_t)t * d + c) = a;
+        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+    const float tot = block_sum_256(ss, sh);
+    const float r = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+        float v[8];
+        for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
+        store_act8<BF16>(X, t, c, d, v);
+    }
+}
+
+// cos/sin of pos * theta^(-2i/D) for every packed row, evaluated in float64, stored as float32
+__global__ void rope_table_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev, int half, double theta,
+                                  float2* __restrict__ cs) {
+    const int t = blockIdx.x;
+    const int b = meta.row_req[t];
+    const int pos = len_dev[meta.req_id[b]] + meta.row_j[t];
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
+        double inv = pow(theta, -(double)i / (double)half);
+        double ang = (double)pos * inv;
+        cs[(size_t)t * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+    }
+}
+
+// Reduce the QKV partial sums of row t, rotate q and k, write q to Q[T, Hq, D] and k, v into the
+// request's page slot for position L + j.
+template <bool BF16>
+__global__ __launch_bounds__(256) void qkv_rope_store_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev,
+                                                             const float* __restrict__ partial, int n_split, int T_pad,
+                                                             int Hq, int Hkv, int D, const float2* __restrict__ cs,
+                                                             void* __restrict__ Q, void* __restrict__ k_pool,
+                                                             void* __restrict__ v_pool, int64_t n_pages, int layer) {
+    const int t = blockIdx.x;
+    const int b = meta.row_req[t];
+    const int pos = len_dev[meta.req_id[b]] + meta.row_j[t];
+    const int page = meta.pages[meta.cu_pages[b] + (pos >> 4)];
+    const int slot = pos & 15;
+    const int half = D >> 1;
+    const int n_qkv = (Hq + 2 * Hkv) * D;
+    const size_t head_elems = (size_t)16 * D;
+    auto fetch = [&](int col) {
+        float a = 0.f;
+        for (int s = 0; s < n_split; s++) a += partial[((size_t)s * T_pad + t) * n_qkv + col];
+        return a;
+    };
+    // rotary pairs of q and k heads
+    const int n_pairs = (Hq + Hkv) * half;
+    for (int e = threadIdx.x; e < n_pairs; e += 256) {
+        const int head = e / half, i = e - head * half;
+        const int c1 = head * D + i, c2 = c1 + half;
+        const float x1 = fetch(c1), x2 = fetch(c2);
+        const float2 sc = cs[(size_t)t * half + i];
+        const float y1 = x1 * sc.x - x2 * sc.y;
+        const float y2 = x2 * sc.x + x1 * sc.y;
+        if (head < Hq) {
+            if (BF16) {
+                bf16_t* q = static_cast<bf16_t*>(Q) + ((size_t)t * Hq + head) * D;
+                q[i] = f32_to_bf16(y1);
+                q[i + half] = f32_to_bf16(y2);
+            } else {
+                float* q = static_cast<float*>(Q) + ((size_t)t * Hq + head) * D;
+                q[i] = y1;
+                q[i + half] = y2;
+            }
+        } else {
+            const int g = head - Hq;
+            const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
+            if (BF16) {
+                // K page-head block in operand order: element (slot, dd) at
+                //   (dd/32)*512 + (((dd%32)/8)*16 + slot)*8 + dd%8
+                bf16_t* kp = static_cast<bf16_t*>(k_pool) + base;
+                const int d1 = i, d2 = i + half;
+                kp[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) << 4) + slot) * 8 + (d1 & 7)] = f32_to_bf16(y1);
+                kp[(d2 >> 5) * 512 + ((((d2 & 31) >> 3) << 4) + slot) * 8 + (d2 & 7)] = f32_to_bf16(y2);
+            } else {
+                float* kp = static_cast<float*>(k_pool) + base + (size_t)slot * D;
+                kp[i] = y1;
+                kp[i + half] = y2;
+            }
+        }
+    }
+    // v heads: no rotation
+    for (int e = threadIdx.x; e < Hkv * D; e += 256) {
+        const int g = e / D, dd = e - g * D;
+        const float v = fetch((Hq + Hkv) * D + e);
+        const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
+        if (BF16) {
+            // V page-head block: element (slot, dd) at (((dd/16)/2)*64 + (slot/4)*16 + dd%16)*8 + ((dd/16)%2)*4 + slot%4
+            const int dt = dd >> 4;
+            static_cast<bf16_t*>(v_pool)[base + ((size_t)((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15))) * 8 + (dt & 1) * 4 +
+                                         (slot & 3)] = f32_to_bf16(v);
+        } else {
+            static_cast<float*>(v_pool)[base + (size_t)slot * D + dd] = v;
+        }
+    }
+}
+
+// fp32 models: a[t, f] = silu(gu[t, 2f]) * gu[t, 2f+1]
+__global__ void swiglu_f32_kernel(const float* __restrict__ gu, int T, int F, float* __restrict__ a) {
+    const size_t n = (size_t)T * F;
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const float g = gu[2 * e], u = gu[2 * e + 1];
+        a[e] = g / (1.f + expf(-g)) * u;
+    }
+}
+
+// externally produced K/V [n_layers, n_tok, Hkv, D] -> page slots of positions L .. L+n_tok-1
+template <bool BF16>
+__global__ void kv_ingest_kernel(const void* __restrict__ k_src, const void* __restrict__ v_src, int n_tok, int Hkv, int D,
+                                 const int32_t* __restrict__ len_dev, int req_id, const int32_t* __restrict__ pages,
+                                 void* __restrict__ k_pool, void* __restrict__ v_pool, int64_t n_pages) {
+    const int tk = blockIdx.x, layer = blockIdx.y;
+    const int pos = len_dev[req_id] + tk;
+    const int page = pages[pos >> 4];
+    const int slot = pos & 15;
+    const size_t head_elems = (size_t)16 * D;
+    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+        const int g = e / D, dd = e - g * D;
+        const size_t src = (((size_t)layer * n_tok + tk) * Hkv + g) * D + dd;
+        const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
+        if (BF16) {
+            const int dt = dd >> 4;
+            static_cast<bf16_t*>(k_pool)[base + (dd >> 5) * 512 + ((((dd & 31) >> 3) << 4) + slot) * 8 + (dd & 7)] =
+                static_cast<const bf16_t*>(k_src)[src];
+            static_cast<bf16_t*>(v_pool)[base + ((size_t)((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15))) * 8 +
+                                         (dt & 1) * 4 + (slot & 3)] = static_cast<const bf16_t*>(v_src)[src];
+        } else {
+            static_cast<float*>(k_pool)[base + (size_t)slot * D + dd] = static_cast<const float*>(k_src)[src];
+            static_cast<float*>(v_pool)[base + (size_t)slot * D + dd] = static_cast<const float*>(v_src)[src];
+        }
+    }
+}
+
+// len[req_ids[i]] += add[i]            (accept == nullptr)
+// len[req_ids[i]] += accept[i] + 1     (otherwise)
+__global__ void len_add_kernel(int32_t* __restrict__ len_dev, const int32_t* __restrict__ req_ids,
+                               const int32_t* __restrict__ add, const int32_t* __restrict__ accept, int B) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= B) return;
+    len_dev[req_ids[i]] += accept ? accept[i] + 1 : add[i];
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) p[e] = v;
+}
+
+// ----- weight repacking --------------------------------------------------------------------
+// rows [0, rows) of src[rows, K] go to destination rows dst_row0 + r * dst_row_stride of a packed
+// (bf16, operand order) or row-major (f32) matrix with K columns.
+template <bool BF16>
+__global__ void pack_rows_kernel(const void* __restrict__ src, void* __restrict__ dst, int rows, int K, int dst_row0,
+                                 int dst_row_stride) {
+    const size_t n8 = (size_t)rows * (K / 8);
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n8; e += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / (K / 8));
+        const int c = (int)(e - (size_t)r * (K / 8)) * 8;
+        const int dr = dst_row0 + r * dst_row_stride;
+        if (BF16) {
+            uint4 v = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(src) + (size_t)r * K + c);
+            *reinterpret_cast<uint4*>(static_cast<bf16_t*>(dst) + frag_offset(dr, c, K)) = v;
+        } else {
+            const float* s = static_cast<const float*>(src) + (size_t)r * K + c;
+            float* d = static_cast<float*>(dst) + (size_t)dr * K + c;
+            for (int i = 0; i < 8; i++) d[i] = s[i];
+        }
+    }
+}
+
+template <bool BF16>
+__global__ void copy_gain_kernel(const void* __restrict__ src, float* __restrict__ dst, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    dst[i] = BF16 ? bf16_to_f32(static_cast<const bf16_t*>(src)[i]) : static_cast<const float*>(src)[i];
+}
+
+}  // namespace
+
+int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
+                          hipStream_t st) {
+    const size_t n8 = (size_t)rows * (K / 8);
+    int grid = (int)((n8 + 255) / 256);
+    if (grid > 65535) grid = 65535;
+    if (grid < 1) grid = 1;
+    if (dtype == SLED_BF16)
+        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride);
+    else
+        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStream_t st) {
+    if (dtype == SLED_BF16)
+        hipLaunchKernelGGL(copy_gain_kernel<true>, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, n);
+    else
+        hipLaunchKernelGGL(copy_gain_kernel<false>, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, n);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, const float* gain,
+                           hipStream_t st) {
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(embed_norm_kernel<true>, dim3(T), dim3(256), 0, st, tokens, m->embed, m->s.vocab, m->s.d_model,
+                           m->s.rms_eps, gain, h, X);
+    else
+        hipLaunchKernelGGL(embed_norm_kernel<false>, dim3(T), dim3(256), 0, st, tokens, m->embed, m->s.vocab, m->s.d_model,
+                           m->s.rms_eps, gain, h, X);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
+                              const float* gain, hipStream_t st) {
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(residual_norm_kernel<true>, dim3(T), dim3(256), 0, st, partial, n_split, T_pad, m->s.d_model,
+                           m->s.rms_eps, gain, h, X);
+    else
+        hipLaunchKernelGGL(residual_norm_kernel<false>, dim3(T), dim3(256), 0, st, partial, n_split, T_pad, m->s.d_model,
+                           m->s.rms_eps, gain, h, X);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs,
+                           hipStream_t st) {
+    hipLaunchKernelGGL(rope_table_kernel, dim3(meta.T), dim3(64), 0, st, meta, p->len_dev, m->s.head_dim / 2,
+                       (double)m->s.rope_theta, reinterpret_cast<float2*>(cs));
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
+                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, hipStream_t st) {
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(qkv_rope_store_kernel<true>, dim3(meta.T), dim3(256), 0, st, meta, p->len_dev, partial, n_split,
+                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q,
+                           p->k_pool, p->v_pool, p->n_pages, layer);
+    else
+        hipLaunchKernelGGL(qkv_rope_store_kernel<false>, dim3(meta.T), dim3(256), 0, st, meta, p->len_dev, partial, n_split,
+                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q,
+                           p->k_pool, p->v_pool, p->n_pages, layer);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_swiglu_f32(const float* gu, int T, int F, float* a, hipStream_t st) {
+    size_t n = (size_t)T * F;
+    int grid = (int)((n + 255) / 256);
+    if (grid > 4096) grid = 4096;
+    hipLaunchKernelGGL(swiglu_f32_kernel, dim3(grid), dim3(256), 0, st, gu, T, F, a);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_kv_ingest(const sled_model* m, const sled_kvpool* p, const void* k_src, const void* v_src, int n_tokens,
+                          int req_id, const int32_t* pages_dev, hipStream_t st) {
+    dim3 grid(n_tokens, m->s.n_layers);
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(kv_ingest_kernel<true>, grid, dim3(256), 0, st, k_src, v_src, n_tokens, m->s.n_kv_heads,
+                           m->s.head_dim, p->len_dev, req_id, pages_dev, p->k_pool, p->v_pool, p->n_pages);
+    else
+        hipLaunchKernelGGL(kv_ingest_kernel<false>, grid, dim3(256), 0, st, k_src, v_src, n_tokens, m->s.n_kv_heads,
+                           m->s.head_dim, p->len_dev, req_id, pages_dev, p->k_pool, p->v_pool, p->n_pages);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int32_t* add_dev, const int32_t* accept_dev,
+                        int B, hipStream_t st) {
+    hipLaunchKernelGGL(len_add_kernel, dim3((B + 63) / 64), dim3(64), 0, st, len_dev, req_ids_dev, add_dev, accept_dev, B);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st) {
+    int grid = (int)((n + 255) / 256);
+    if (grid > 4096) grid = 4096;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(grid), dim3(256), 0, st, p, v, n);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}

@@ -1,0 +1,178 @@
+// Internal declarations shared by the translation units of libsled (HIP, gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+#include <string>
+
+#include "../../include/sled.h"
+
+// ------------------------------------------------------------------------------------------
+// error plumbing
+// ------------------------------------------------------------------------------------------
+void sled_set_error(const char* fmt, ...);
+
+#define SLED_FAIL(code, ...)            \
+    do {                                \
+        sled_set_error(__VA_ARGS__);    \
+        return (code);                  \
+    } while (0)
+
+#define SLED_HIP(expr)                                                                        \
+    do {                                                                                      \
+        hipError_t _e = (expr);                                                               \
+        if (_e != hipSuccess)                                                                 \
+            SLED_FAIL(SLED_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, __LINE__); \
+    } while (0)
+
+#define SLED_LAUNCH_CHECK()                                                                   \
+    do {                                                                                      \
+        hipError_t _e = hipGetLastError();                                                    \
+        if (_e != hipSuccess)                                                                 \
+            SLED_FAIL(SLED_EHIP, "kernel launch failed: %s (%s:%d)", hipGetErrorString(_e), __FILE__, __LINE__); \
+    } while (0)
+
+// ------------------------------------------------------------------------------------------
+// bf16 helpers (storage type is a raw 16-bit pattern; arithmetic is always fp32)
+// ------------------------------------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v) {
+    union { uint32_t u; float f; } c;
+    c.u = ((uint32_t)v) << 16;
+    return c.f;
+}
+
+// round to nearest, ties to even; inputs are finite by contract
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    uint32_t u = c.u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
+
+// ------------------------------------------------------------------------------------------
+// Packed operand layout for the bf16 MFMA kernels ("fragment order").
+//
+// A matrix M[R, K] (R = rows: output features of a weight, or tokens of an activation; K the
+// contraction axis) is stored as tiles of 16 rows x 32 k.  Tile (rt, ks) occupies 512
+// consecutive elements; inside it, lane l of a wavefront owns the 8 consecutive elements
+//     M[rt*16 + l%16][ks*32 + (l/16)*8 + j],  j = 0..7
+// which is exactly the operand register content of v_mfma_f32_16x16x32_bf16.  A wavefront
+// therefore loads one operand tile with a single fully coalesced 1 KiB access.
+// ------------------------------------------------------------------------------------------
+__host__ __device__ inline size_t frag_offset(int r, int k, int K) {
+    int rt = r >> 4, rl = r & 15, ks = k >> 5, kk = k & 31;
+    return ((size_t)rt * (K >> 5) + ks) * 512 + (size_t)(((kk >> 3) << 4) + rl) * 8 + (kk & 7);
+}
+
+// ------------------------------------------------------------------------------------------
+// handles
+// ------------------------------------------------------------------------------------------
+struct sled_layer_weights {
+    void* w_qkv;    // [ (Hq+2Hkv)*D, d ]  rows: q heads, then k heads, then v heads
+    void* w_o;      // [ d, Hq*D ]
+    void* w_gu;     // [ 2F, d ] row 2f = gate f, row 2f+1 = up f
+    void* w_down;   // [ d, F ]
+    float* g_attn;  // [d]
+    float* g_mlp;   // [d]
+};
+
+struct sled_model {
+    sled_shape s;
+    int n_qkv;                 // (Hq + 2 Hkv) * D
+    size_t elem;               // bytes per stored element
+    void* embed;               // [V, d] model dtype, row-major
+    void* lm_head;             // [V, d] packed (bf16) or row-major (f32)
+    float* g_final;
+    std::vector<sled_layer_weights> layers;
+    std::vector<void*> allocs;
+};
+
+struct sled_request {
+    bool open = false;
+    int len_ub = 0;            // host-side upper bound of the committed length
+    int staged = -1;           // k+1 of the last verify (rows staged), -1 if none
+    std::vector<int> pages;
+};
+
+struct sled_kvpool {
+    const sled_model* m;
+    int64_t n_pages;
+    int max_requests;
+    size_t page_head_elems;    // 16 * head_dim
+    void* k_pool;              // [n_layers][n_pages][Hkv][16*D] in the layout of the dtype
+    void* v_pool;
+    int32_t* len_dev;          // [max_requests] committed context length of each request
+    std::vector<sled_request> reqs;
+    std::vector<int> free_pages;
+    std::vector<int> last_batch;   // request ids of the last verify
+    // ring of pinned-host + device staging buffers for per-call metadata (page lists, row maps)
+    static const int RING = 8;
+    struct stage_slot {
+        int32_t* host;
+        int32_t* dev;
+        hipEvent_t ev;
+        bool pending;          // ev has been recorded and not yet waited for
+    };
+    stage_slot slot[RING];
+    size_t stage_cap;          // ints per slot
+    int stage_next;
+};
+
+// per-step metadata blob, device side (offsets in int32 units from the blob start)
+struct sled_step_meta {
+    const int32_t* req_id;     // [B]
+    const int32_t* k;          // [B]
+    const int32_t* cu_rows;    // [B+1]
+    const int32_t* cu_pages;   // [B+1]
+    const int32_t* row_req;    // [T]   index into the batch (not the request id)
+    const int32_t* row_j;      // [T]   index of the row inside its request
+    const int32_t* pages;      // [sum pages]
+    const int32_t* work;       // [n_work * 4]  attention work items: batch index, kv head, first page, n pages
+    const int32_t* cu_work;    // [B*Hkv + 1]   first work item of each (batch index, kv head)
+    int B, T, n_work;
+};
+
+// ------------------------------------------------------------------------------------------
+// kernel launchers (defined in the .hip files); all return SLED_OK or an error code
+// ------------------------------------------------------------------------------------------
+// rowops.hip
+int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
+                          hipStream_t st);
+int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStream_t st);
+int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, const float* gain,
+                           hipStream_t st);
+int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
+                              const float* gain, hipStream_t st);
+int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs, hipStream_t st);
+int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
+                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, hipStream_t st);
+int sled_launch_swiglu_f32(const float* gu, int T, int F, float* a, hipStream_t st);
+int sled_launch_kv_ingest(const sled_model* m, const sled_kvpool* p, const void* k_src, const void* v_src, int n_tokens,
+                          int req_id, const int32_t* pages_dev, hipStream_t st);
+int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int32_t* add_dev, const int32_t* accept_dev,
+                        int B, hipStream_t st);
+
+// gemm.hip:  out = X[T, K] * W[N, K]^T
+enum { SLED_EPI_PARTIAL = 0, SLED_EPI_SWIGLU = 1, SLED_EPI_STORE = 2 };
+int sled_gemm_pick_split(const sled_model* m, int T, int N, int K);
+int sled_launch_gemm(const sled_model* m, const void* X, const void* W, int T, int T_pad, int N, int K, int epilogue,
+                     int split_k, float* out_f32, void* out_act, int F_act, hipStream_t st);
+
+// attention.hip
+int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
+                          float* part_o, float* part_ml, void* X_out, int QT, hipStream_t st);
+
+// accept.hip
+size_t sled_accept_ws_bytes(int B, int T, int n_split);
+int sled_accept_pick_split(int T, int vocab);
+int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, float temperature, const float* logits,
+                       const int32_t* tokens, const float* draft_q, const float* u_acc, const float* u_smp,
+                       int32_t* accept_len, int32_t* out_token, void* ws, hipStream_t st);

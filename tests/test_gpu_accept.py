@@ -1,0 +1,100 @@
+"""GPU parity of sled_accept against the oracle (through the C ABI)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_09397_amd import sled, synth
+from gpu_common import compare_accept, oracle_accept, run_accept_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("vocab,k", [
+    (1024, [4, 4, 4, 4]),
+    (1000, [0, 3, 8, 1, 0, 5]),        # vocab not a multiple of the vector width, k = 0 requests
+    (4099, [8] * 7),                    # odd vocab: scalar path, several tiles + ragged tail in the draw
+    (32000, [2, 4, 6, 8] * 8),
+    (130, [1, 2]),
+])
+@pytest.mark.parametrize("sigma", [0.25, 1.0, 4.0])
+def test_sampling_matches_oracle_small(vocab, k, sigma):
+    case = synth.accept_case(k, vocab, sigma, seed=vocab + int(sigma * 10), device="cuda")
+    a, t = run_accept_gpu(sled.SAMPLE, case, vocab)
+    want = oracle_accept(sled.SAMPLE, case)
+    n_sub = compare_accept(sled.SAMPLE, k, a, t, want, f"V={vocab} sigma={sigma}")
+    assert n_sub <= 1
+
+
+@pytest.mark.parametrize("vocab,k", [(1024, [4, 4, 4, 4]), (1000, [0, 3, 8, 1]), (128256, [2, 8, 5, 3, 7, 4] * 3)])
+def test_greedy_matches_oracle(vocab, k):
+    case = synth.accept_case(k, vocab, 0.25, seed=5, device="cuda")
+    # make about half of the drafts equal to the target argmax so that accepted lengths vary
+    logits = case.logits
+    off = 0
+    g = torch.Generator(device="cuda").manual_seed(1)
+    for ki in k:
+        for j in range(ki):
+            if torch.rand(1, generator=g, device="cuda").item() < 0.7:
+                case.tokens[off + 1 + j] = int(torch.argmax(logits[off + j]))
+        off += ki + 1
+    a, t = run_accept_gpu(sled.GREEDY, case, vocab)
+    want = oracle_accept(sled.GREEDY, case)
+    assert compare_accept(sled.GREEDY, k, a, t, want) == 0
+    assert max(int(x) for x in a) > 0
+
+
+def test_greedy_ties_take_lowest_id():
+    vocab, k = 4096, [3, 2]
+    T = sum(k) + len(k)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    logits = torch.randint(0, 4, (T, vocab), generator=g, device="cuda").float()   # many exact ties
+    tokens = torch.zeros(T, dtype=torch.int32, device="cuda")
+    first_max = torch.argmax((logits == logits.max(dim=1, keepdim=True).values).float(), dim=1)
+    tokens[1:4] = first_max[0:3].int()
+    tokens[5] = first_max[4].int()
+    tokens[6] = (first_max[5] + 1).int()     # wrong on purpose
+    case = synth.AcceptCase(k, logits, tokens, None, None, None)
+    a, t = run_accept_gpu(sled.GREEDY, case, vocab)
+    assert a.tolist() == [3, 1]
+    assert t.tolist() == [int(first_max[3]), int(first_max[5])]
+
+
+@pytest.mark.parametrize("temperature", [0.7, 2.0])
+def test_sampling_with_temperature(temperature):
+    vocab, k = 5000, [4, 3, 8, 0, 2]
+    case = synth.accept_case(k, vocab, 1.0, seed=17, device="cuda")
+    a, t = run_accept_gpu(sled.SAMPLE, case, vocab, temperature)
+    want = oracle_accept(sled.SAMPLE, case, temperature)
+    assert compare_accept(sled.SAMPLE, k, a, t, want) <= 1
+
+
+@pytest.mark.parametrize("sigma", [0.25, 1.0, 4.0])
+def test_acceptance_alone_full_size(sigma):
+    """256 requests x (8 drafts + 1 bonus row) x vocab 128256, target logits N(0, 2)."""
+    vocab, k = 128256, [8] * 256
+    case = synth.accept_case(k, vocab, sigma, seed=int(sigma * 100), device="cuda")
+    a, t = run_accept_gpu(sled.SAMPLE, case, vocab)
+    want = oracle_accept(sled.SAMPLE, case)
+    n_sub = compare_accept(sled.SAMPLE, k, a, t, want, f"sigma={sigma}")
+    assert n_sub <= 3
+    mean_a = float(np.mean(a))
+    # acceptance falls as the draft distribution moves away from the target
+    lo, hi = {0.25: (3.5, 7.0), 1.0: (0.8, 2.8), 4.0: (0.0, 0.4)}[sigma]
+    assert lo <= mean_a <= hi, mean_a
+
+
+def test_accept_argument_errors():
+    vocab, k = 1024, [2, 2]
+    case = synth.accept_case(k, vocab, 1.0, seed=1, device="cuda")
+    a = torch.zeros(2, dtype=torch.int32, device="cuda")
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(2, 6, vocab))
+    with pytest.raises(sled.SledError) as e:
+        sled.sled_accept(5, k, vocab, 1.0, case.logits, case.tokens, case.q, case.u_acc, case.u_smp, a, a.clone(), ws)
+    assert e.value.code == sled.EINVAL
+    with pytest.raises(sled.SledError):
+        sled.sled_accept(sled.SAMPLE, k, vocab, 0.0, case.logits, case.tokens, case.q, case.u_acc, case.u_smp, a, a.clone(), ws)
+    with pytest.raises(sled.SledError):
+        sled.sled_accept(sled.SAMPLE, k, vocab, 1.0, case.logits, case.tokens, None, case.u_acc, case.u_smp, a, a.clone(), ws)
+    with pytest.raises(sled.SledError):
+        sled.sled_accept(sled.SAMPLE, k, vocab, 1.0, case.logits, case.tokens, case.q, case.u_acc, case.u_smp, a, a.clone(),
+                         ws[:256])

@@ -195,3 +195,22 @@ def test_round_points_only_touch_storage_tensors():
     b = O.prefill(oracle_model(shape, w, "bf16"), toks)["logits"]
     err = np.abs(a - b).max() / np.abs(a).max()
     assert 1e-5 < err < 5e-2
+
+
+def test_rounded_softmax_numerators_are_reference_free():
+    """bf16 mode: rounding 2^(t - M) for a whole number M gives the same attention output for any
+    such M (scaling by a power of two commutes with rounding), and stays within bf16 precision of
+    the unrounded softmax."""
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((3, 4, 16)) * 2
+    K = rng.standard_normal((40, 2, 16))
+    V = rng.standard_normal((40, 2, 16))
+    exact = O.attention_rows(q, K, V, 37, 2, "exact")
+    rounded = O.attention_rows(q, K, V, 37, 2, "bf16")
+    assert 1e-6 < np.abs(exact - rounded).max() < 2e-2
+    # the same with every reference shifted by +3 whole units, written out by hand for one row
+    j, h, g = 1, 2, 1
+    s = (K[:39, g, :] @ q[j, h, :]) / math.sqrt(16) * O.LOG2E
+    p = np.exp2(s - (math.ceil(s.max()) + 3))
+    alt = (O.bf16_round(p) @ V[:39, g, :]) / p.sum()
+    assert np.abs(alt - rounded[j, h]).max() < 1e-15
