@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Throughput of the batched verification step on one MI355X.
+
+One step = sled_verify_batch + sled_accept + sled_kv_append (commit) over one ragged batch of
+synthetic requests, inputs resident in HBM.  Workload: Llama-3-8B-shaped decoder (bf16, random
+init), 16 requests, contexts uniform in [512, 2048], k uniform in [2, 8], greedy acceptance.
+
+Prints one JSON line: verified draft tokens/s (whole job), p50 step latency, the HBM roofline of
+the dominant kernel (the weight-streaming projection GEMM) and the CPU oracle timed on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--workload", default="llama8b_b16", choices=["llama8b_b16", "llama8b_hetero64", "tiny_bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=5, help="steps of the event-instrumented region")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2506_09397_amd import sled, synth
+    from paper_2506_09397_amd.runtime import Verifier
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    sled.lib()  # fails loudly if libsled.so has not been built
+    torch.cuda.set_device(0)
+
+    if args.workload == "llama8b_b16":
+        shape, kind = synth.SHAPES["llama8b"], "b16"
+    elif args.workload == "llama8b_hetero64":
+        shape, kind = synth.SHAPES["llama8b"], "hetero64"
+    else:
+        shape, kind = synth.SHAPES["tiny_bf16"], "b16"
+    batch = synth.draw_batch(kind, shape.vocab, seed=args.seed)
+    B, T, n_drafts = batch.B, batch.T, int(sum(batch.k))
+    total_steps = args.warmup + args.steps + args.profile_steps + 2
+    ctx_budget = sum(batch.ctx_len) + B * (shape.k_max + 1) * (total_steps + 1)
+    n_pages = ctx_budget // 16 + 2 * B + 8
+    weights = synth.SynthWeights(shape, seed=args.seed, device="cuda")
+    v = Verifier(shape, weights, n_pages, B, B, ctx_budget)
+    reqs = [v.open() for _ in range(B)]
+    KV = []
+    for i in range(B):
+        K, V = synth.context_kv(shape, batch.ctx_len[i], seed=args.seed, req=i, device="cuda")
+        v.append_context([reqs[i]], [K], [V])
+        KV.append((K, V) if i < 2 else None)
+        del K, V
+    tokens = torch.from_numpy(batch.tokens).cuda()
+    torch.cuda.synchronize()
+
+    def step():
+        logits = v.verify(reqs, batch.k, tokens)
+        a, t = v.accept(sled.GREEDY, batch.k, logits, tokens)
+        v.commit(reqs, a)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for s in range(args.steps):
+        step()
+        ev[s + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    lat = sorted(ev[s].elapsed_time(ev[s + 1]) for s in range(args.steps))
+    p50, p90 = lat[len(lat) // 2], lat[min(len(lat) - 1, int(len(lat) * 0.9))]
+    value = n_drafts * args.steps / (t1 - t0)
+
+    # context actually held after the timed region (greedy on random tokens accepts ~0 drafts, so it
+    # grew by about one token per step); used for the algorithmic K/V bytes
+    lens = v.lengths(reqs)
+    kv_bytes = sum(lens) * shape.kv_bytes_per_token()
+    weight_bytes = shape.streamed_params() * 2
+    logits_bytes = T * shape.vocab * 4
+
+    # event-instrumented region: per-class kernel time on the stream the kernels run on
+    sled.sled_profile_enable(v.model, True)
+    for _ in range(args.profile_steps):
+        step()
+    ms, n = sled.sled_profile_read(v.model)
+    sled.sled_profile_enable(v.model, False)
+    proj_ms = ms[sled.PROF_PROJ] / args.profile_steps
+    proj_launches = n[sled.PROF_PROJ] // args.profile_steps
+    achieved = weight_bytes / (proj_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "gemm_bf16_kernel (projection GEMMs, weight stream)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": None,
+        "launches_per_step": proj_launches, "avg_launch_us": round(proj_ms * 1e3 / max(proj_launches, 1), 2),
+        "bytes_per_launch": round(weight_bytes / max(proj_launches, 1)),
+    }
+    step_bytes = weight_bytes + kv_bytes + logits_bytes
+    breakdown = {
+        "proj_ms": round(proj_ms, 4), "attn_ms": round(ms[sled.PROF_ATTN] / args.profile_steps, 4),
+        "rows_ms": round(ms[sled.PROF_ROWS] / args.profile_steps, 4),
+        "attn_GBps": round(kv_bytes / max(ms[sled.PROF_ATTN] / args.profile_steps, 1e-9) / 1e6, 1),
+        "step_bytes": step_bytes, "step_hbm_frac": round(step_bytes / (p50 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, weights, batch, KV, args)
+
+    out = {
+        "metric": "verified draft tokens/sec per batched verify step", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "p50_ms": round(p50, 4), "p90_ms": round(p90, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {shape.n_layers} layers d={shape.d_model} Hq/Hkv={shape.n_q_heads}/"
+                               f"{shape.n_kv_heads} F={shape.d_ffn} V={shape.vocab}, B={B}, T={T} packed rows, "
+                               f"{n_drafts} draft tokens, {sum(lens)} context tokens, greedy acceptance, seed {args.seed}"},
+        "roofline": roofline, "breakdown": breakdown, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    v.destroy()
+
+
+def cpu_baseline(shape, weights, batch, KV, args):
+    """The oracle as it stands, on a bounded sample: the first 2 requests of the batch through the
+    first 2 layers plus final norm and LM head; layer time is scaled to the full depth and request
+    time to the full batch by rows."""
+    import numpy as np
+    from oracle import sled_oracle as O
+    from oracle.harness import oracle_model
+    from paper_2506_09397_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n_req, n_lay = 2, 2
+    om = oracle_model(shape, weights, n_layers=n_lay)
+    offs = batch.row_offsets()
+    reqs = []
+    for i in range(n_req):
+        K, V = KV[i]
+        reqs.append({"tokens": batch.tokens[offs[i]: offs[i + 1]], "K": synth.as_f64(K[:n_lay]), "V": synth.as_f64(V[:n_lay])})
+    om.weights.embed(); om.weights.final()
+    for l in range(n_lay):
+        om.weights.layer(l)          # widen to float64 outside the timed part
+    rows = sum(len(r["tokens"]) for r in reqs)
+    t0 = time.perf_counter()
+    res = O.verify_batch(om, reqs)
+    t_all = time.perf_counter() - t0
+    # time of the head alone, to scale only the layer part with depth
+    om0 = oracle_model(shape, weights, n_layers=0)
+    om0.weights._c = om.weights._c
+    reqs0 = [{"tokens": r["tokens"], "K": r["K"][:0], "V": r["V"][:0]} for r in reqs]
+    t0 = time.perf_counter()
+    O.verify_batch(om0, reqs0)
+    t_head = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    logits = np.concatenate([r["logits"] for r in res], axis=0).astype(np.float32).astype(np.float64)
+    O.accept_batch("greedy", batch.k[:n_req], logits, batch.tokens[: offs[n_req]])
+    t_acc = time.perf_counter() - t0
+    t_layers = max(t_all - t_head, 0.0)
+    est = (t_layers * shape.n_layers / n_lay + t_head + t_acc) * batch.T / rows
+    return {"value": round(sum(batch.k) / est, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_req} of {batch.B} requests ({rows} of {batch.T} rows), first {n_lay} of {shape.n_layers} "
+                      f"layers + LM head + greedy acceptance, {t_all + t_acc:.1f} s measured, scaled by depth and rows "
+                      f"to {est:.1f} s per step"}
+
+
+if __name__ == "__main__":
+    main()

@@ -195,6 +195,22 @@ SLED_API int sled_accept(int mode, int B, const int* k /*host*/, int vocab, floa
                 int32_t* accept_len /*dev out*/, int32_t* out_token /*dev out*/,
                 void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
+/* ---- kernel timing (measurement aid) ---------------------------------------------- */
+
+/* Kernel classes of one verification step. */
+#define SLED_PROF_PROJ  0   /* projection GEMMs: QKV, O, gate/up, down, LM head (weight stream)    */
+#define SLED_PROF_ATTN  1   /* verify attention over the paged K/V cache (K/V stream) + its merge  */
+#define SLED_PROF_ROWS  2   /* row operators: embedding, split-K reduce, RMSNorm, rotary, K/V store */
+#define SLED_PROF_N     3
+
+/* With on != 0, every following sled_verify_batch on this model brackets each kernel launch with
+ * HIP events on the caller's stream (this costs a few microseconds per launch: never leave it on
+ * in a throughput run).  sled_profile_read waits for `stream`, adds up the elapsed time and the
+ * number of launches of each class since the last read, writes them to ms[SLED_PROF_N] and
+ * launches[SLED_PROF_N] (host out) and starts over.  Errors: SLED_EINVAL, SLED_EHIP. */
+SLED_API int sled_profile_enable(sled_model* m, int on);
+SLED_API int sled_profile_read(sled_model* m, void* stream, float* ms /*host out*/, int* launches /*host out*/);
+
 /* ---- errors ---------------------------------------------------------------------- */
 SLED_API const char* sled_strerror(int code);
 SLED_API const char* sled_last_error(void);   /* message of the last failing call on this thread */

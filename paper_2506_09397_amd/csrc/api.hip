@@ -100,6 +100,12 @@ extern "C" int sled_model_create(const sled_shape* shape, sled_model** out) {
 
 extern "C" int sled_model_destroy(sled_model* m) {
     if (!m) return SLED_OK;
+    (void)hipDeviceSynchronize();
+    for (auto& sp : m->prof_spans) {
+        (void)hipEventDestroy(sp.e0);
+        (void)hipEventDestroy(sp.e1);
+    }
+    for (hipEvent_t e : m->prof_free) (void)hipEventDestroy(e);
     for (void* p : m->allocs) (void)hipFree(p);
     delete m;
     return SLED_OK;
@@ -130,6 +136,61 @@ extern "C" int sled_model_load(sled_model* m, int tensor_id, int layer, const vo
         case SLED_T_LM_HEAD: return sled_launch_pack_rows(s.dtype, src, m->lm_head, s.vocab, d, 0, 1, st);
         default: SLED_FAIL(SLED_EINVAL, "sled_model_load: unknown tensor id %d", tensor_id);
     }
+}
+
+// ------------------------------------------------------------------------------------------ timing
+static int prof_event(sled_model* m, hipEvent_t* out) {
+    if (!m->prof_free.empty()) {
+        *out = m->prof_free.back();
+        m->prof_free.pop_back();
+        return SLED_OK;
+    }
+    SLED_HIP(hipEventCreate(out));
+    return SLED_OK;
+}
+
+// brackets one launch (or a short group of launches of the same class) with events
+struct prof_scope {
+    sled_model* m;
+    hipStream_t st;
+    sled_model::prof_span sp;
+    bool live;
+    prof_scope(sled_model* m_, int cls, hipStream_t st_) : m(m_), st(st_), live(false) {
+        if (!m->prof_on) return;
+        sp.cls = cls;
+        if (prof_event(m, &sp.e0) != SLED_OK || prof_event(m, &sp.e1) != SLED_OK) return;
+        live = hipEventRecord(sp.e0, st) == hipSuccess;
+    }
+    ~prof_scope() {
+        if (!live) return;
+        (void)hipEventRecord(sp.e1, st);
+        m->prof_spans.push_back(sp);
+    }
+};
+
+extern "C" int sled_profile_enable(sled_model* m, int on) {
+    if (!m) SLED_FAIL(SLED_EINVAL, "sled_profile_enable: null model");
+    m->prof_on = on != 0;
+    return SLED_OK;
+}
+
+extern "C" int sled_profile_read(sled_model* m, void* stream, float* ms, int* launches) {
+    if (!m || !ms || !launches) SLED_FAIL(SLED_EINVAL, "sled_profile_read: null argument");
+    SLED_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    for (int c = 0; c < SLED_PROF_N; c++) {
+        ms[c] = 0.f;
+        launches[c] = 0;
+    }
+    for (auto& sp : m->prof_spans) {
+        float t = 0.f;
+        SLED_HIP(hipEventElapsedTime(&t, sp.e0, sp.e1));
+        ms[sp.cls] += t;
+        launches[sp.cls] += 1;
+        m->prof_free.push_back(sp.e0);
+        m->prof_free.push_back(sp.e1);
+    }
+    m->prof_spans.clear();
+    return SLED_OK;
 }
 
 // ------------------------------------------------------------------------------------------ pool
@@ -385,7 +446,7 @@ int gemm_split(const sled_model* m, int T, int N, int K) { return sled_gemm_pick
 
 ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     const sled_shape& s = m->s;
-    const size_t T_alloc = align_up(T, 128), T_pad = align_up(T, 16);
+    const size_t T_alloc = align_up(T + 64, 128), T_pad = align_up(T, 16);  // row blocks of the GEMMs may overhang
     const size_t d = s.d_model, F = s.d_ffn, HD = (size_t)s.n_q_heads * s.head_dim;
     ws_plan w;
     size_t off = 0;
@@ -538,27 +599,35 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
         if ((rc = (x)) != SLED_OK) return rc; \
     } while (0)
 
-    SLED_TRY(sled_launch_rope_table(m, p, meta, cs, st));
-    SLED_TRY(sled_launch_embed_norm(m, tokens, T, h, xa, m->layers[0].g_attn, st));
+// a launch inside a timing scope of class c
+#define SLED_RUN(c, x)                     \
+    do {                                   \
+        prof_scope _ps(m, (c), st);        \
+        SLED_TRY(x);                       \
+    } while (0)
+
+    SLED_RUN(SLED_PROF_ROWS, sled_launch_rope_table(m, p, meta, cs, st));
+    SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, m->layers[0].g_attn, st));
     for (int l = 0; l < s.n_layers; l++) {
         const sled_layer_weights& w = m->layers[l];
-        SLED_TRY(sled_launch_gemm(m, xa, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, sp_qkv, partial, nullptr, 0, st));
-        SLED_TRY(sled_launch_qkv_rope_store(m, p, meta, l, partial, sp_qkv, T_pad, cs, qb, st));
-        SLED_TRY(sled_launch_attention(m, p, meta, l, qb, part_o, part_ml, xo, QT, st));
-        SLED_TRY(sled_launch_gemm(m, xo, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, sp_o, partial, nullptr, 0, st));
-        SLED_TRY(sled_launch_residual_norm(m, partial, sp_o, T, T_pad, h, xa, w.g_mlp, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, sp_qkv, partial, nullptr, 0, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, meta, l, partial, sp_qkv, T_pad, cs, qb, st));
+        SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, part_o, part_ml, xo, QT, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, sp_o, partial, nullptr, 0, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, sp_o, T, T_pad, h, xa, w.g_mlp, st));
         if (s.dtype == SLED_BF16) {
-            SLED_TRY(sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, 1, nullptr, xf, F, st));
+            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, 1, nullptr, xf, F, st));
         } else {
-            SLED_TRY(sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, 1, partial, nullptr, 0, st));
-            SLED_TRY(sled_launch_swiglu_f32(partial, T, F, static_cast<float*>(xf), st));
+            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, 1, partial, nullptr, 0, st));
+            SLED_RUN(SLED_PROF_ROWS, sled_launch_swiglu_f32(partial, T, F, static_cast<float*>(xf), st));
         }
-        SLED_TRY(sled_launch_gemm(m, xf, w.w_down, T, T_pad, d, F, SLED_EPI_PARTIAL, sp_dn, partial, nullptr, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xf, w.w_down, T, T_pad, d, F, SLED_EPI_PARTIAL, sp_dn, partial, nullptr, 0, st));
         const float* next_gain = (l + 1 < s.n_layers) ? m->layers[l + 1].g_attn : m->g_final;
-        SLED_TRY(sled_launch_residual_norm(m, partial, sp_dn, T, T_pad, h, xa, next_gain, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, sp_dn, T, T_pad, h, xa, next_gain, st));
     }
-    SLED_TRY(sled_launch_gemm(m, xa, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, 1, logits, nullptr, 0, st));
+    SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, 1, logits, nullptr, 0, st));
     SLED_TRY(stage_release(sl, st));
+#undef SLED_RUN
 #undef SLED_TRY
 
     for (int i = 0; i < B; i++) p->reqs[req_ids[i]].staged = k[i] + 1;

@@ -198,41 +198,37 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
     }
 }
 
-// merge the work items of (request b, kv head g) in ascending page order; write bf16 output in
-// operand order for the O projection: X[t = row0 + j][col = (g*G + hh)*D + d]
-__global__ __launch_bounds__(256) void attn_combine_bf16(sled_step_meta meta, int QT16, int Hq, int Hkv,
-                                                         const float* __restrict__ part_o,
-                                                         const float* __restrict__ part_ml, bf16_t* __restrict__ X) {
+// merge the work items of (request b, kv head g) in ascending page order, one wavefront per query
+// row; write bf16 output in operand order for the O projection:
+// X[t = row0 + j][col = (g*G + hh)*D + d]
+__global__ __launch_bounds__(64) void attn_combine_bf16(sled_step_meta meta, int QT16, int Hq, int Hkv,
+                                                        const float* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml, bf16_t* __restrict__ X) {
     constexpr int D = 128;
     const int b = blockIdx.x / Hkv, g = blockIdx.x - b * Hkv;
+    const int r = blockIdx.y;
     const int G = Hq / Hkv;
-    const int rows = G * (meta.k[b] + 1);
+    if (r >= G * (meta.k[b] + 1)) return;
     const int row0 = meta.cu_rows[b];
     const int w0 = meta.cu_work[blockIdx.x], w1 = meta.cu_work[blockIdx.x + 1];
     const int Kdim = Hq * D;
-    for (int e = threadIdx.x; e < rows * (D / 4); e += 256) {
-        const int r = e / (D / 4), d4 = (e - r * (D / 4)) * 4;
-        float M = NEG_BIG;
-        for (int w = w0; w < w1; w++) M = fmaxf(M, part_ml[((size_t)w * 2 + 0) * QT16 + r]);
-        float lsum = 0.f;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int w = w0; w < w1; w++) {
-            const float f = exp2f(part_ml[((size_t)w * 2 + 0) * QT16 + r] - M);
-            lsum += part_ml[((size_t)w * 2 + 1) * QT16 + r] * f;
-            const float4 ov = *reinterpret_cast<const float4*>(part_o + ((size_t)w * QT16 + r) * D + d4);
-            acc.x += ov.x * f;
-            acc.y += ov.y * f;
-            acc.z += ov.z * f;
-            acc.w += ov.w * f;
-        }
-        const float inv = 1.0f / lsum;
-        const int j = r / G, hh = r - j * G;
-        const int t = row0 + j, col = (g * G + hh) * D + d4;
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
-        pk.y = (uint32_t)f32_to_bf16(acc.z * inv) | ((uint32_t)f32_to_bf16(acc.w * inv) << 16);
-        *reinterpret_cast<uint2*>(X + frag_offset(t, col, Kdim)) = pk;
+    const int d2 = threadIdx.x * 2;
+    float M = NEG_BIG;
+    for (int w = w0; w < w1; w++) M = fmaxf(M, part_ml[((size_t)w * 2 + 0) * QT16 + r]);
+    float lsum = 0.f;
+    float2 acc = make_float2(0.f, 0.f);
+    for (int w = w0; w < w1; w++) {
+        const float f = exp2f(part_ml[((size_t)w * 2 + 0) * QT16 + r] - M);
+        lsum += part_ml[((size_t)w * 2 + 1) * QT16 + r] * f;
+        const float2 ov = *reinterpret_cast<const float2*>(part_o + ((size_t)w * QT16 + r) * D + d2);
+        acc.x += ov.x * f;
+        acc.y += ov.y * f;
     }
+    const float inv = 1.0f / lsum;
+    const int j = r / G, hh = r - j * G;
+    const int t = row0 + j, col = (g * G + hh) * D + d2;
+    const uint32_t pk = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
+    *reinterpret_cast<uint32_t*>(X + frag_offset(t, col, Kdim)) = pk;
 }
 
 // fp32 models: one wavefront per (packed row t, query head h); lanes stride over the keys
@@ -312,7 +308,7 @@ int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_
         }
 #undef SLED_ATTN_CASE
         SLED_LAUNCH_CHECK();
-        hipLaunchKernelGGL(attn_combine_bf16, dim3(meta.B * s.n_kv_heads), dim3(256), 0, st, meta, QT * 16, s.n_q_heads,
+        hipLaunchKernelGGL(attn_combine_bf16, dim3(meta.B * s.n_kv_heads, QT * 16), dim3(64), 0, st, meta, QT * 16, s.n_q_heads,
                            s.n_kv_heads, part_o, part_ml, static_cast<bf16_t*>(X_out));
         SLED_LAUNCH_CHECK();
         return SLED_OK;

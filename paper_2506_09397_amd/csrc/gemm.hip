@@ -20,7 +20,8 @@
 
 namespace {
 
-constexpr int KC = 4;  // k-steps (of 32) per pipeline stage
+constexpr int KC = 2;    // k-steps (of 32) per pipeline stage
+constexpr int NBUF = 4;  // weight register buffers: the stage in use + 3 stages in flight
 
 template <int MT, int NW, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, const bf16_t* __restrict__ Wp,
@@ -47,66 +48,77 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         nt_ok[a] = (nt0 + a) < NT;
-        wbase[a] = Wp + ((size_t)(nt_ok[a] ? nt0 + a : 0) * KS) * 512 + lane * 8;
+        wbase[a] = Wp + ((size_t)(nt_ok[a] ? nt0 + a : 0) * KS + ks_begin) * 512 + lane * 8;
     }
 
-    bf16x8_t wreg[2][NW][KC];
-    uint4 xreg[MT];
+    // One stage of activations is MT*KC KiB: MT*KC*64 16-byte pieces shared out over 256 threads.
+    constexpr int XPIECES = (MT * KC * 64 + 255) / 256;
+    bf16x8_t wreg[NBUF][NW][KC];
+    uint4 xreg[XPIECES];
 
-    auto load_w = [&](int buf, int ks0) {
+    auto load_w = [&](int buf, int stage) {
 #pragma unroll
         for (int a = 0; a < NW; a++)
 #pragma unroll
             for (int c = 0; c < KC; c++)
-                wreg[buf][a][c] = *reinterpret_cast<const bf16x8_t*>(wbase[a] + (size_t)(ks0 + c) * 512);
+                wreg[buf][a][c] = *reinterpret_cast<const bf16x8_t*>(wbase[a] + (size_t)(stage * KC + c) * 512);
     };
-    auto load_x = [&](int ks0) {
+    // piece e of a stage: row tile e / (KC*64), then KC*512 contiguous elements of that tile's k range
+    auto load_x = [&](int stage) {
 #pragma unroll
-        for (int b = 0; b < MT; b++)
-            xreg[b] = *reinterpret_cast<const uint4*>(Xp + ((size_t)(mt_base + b) * KS + ks0) * 512 + tid * 8);
+        for (int i = 0; i < XPIECES; i++) {
+            const int e = i * 256 + tid;
+            if (MT * KC * 64 % 256 == 0 || e < MT * KC * 64) {
+                const int b = e / (KC * 64), r = e - b * (KC * 64);
+                xreg[i] = *reinterpret_cast<const uint4*>(Xp + ((size_t)(mt_base + b) * KS + ks_begin + stage * KC) * 512 + r * 8);
+            }
+        }
     };
     auto store_x = [&](int buf) {
 #pragma unroll
-        for (int b = 0; b < MT; b++)
-            *reinterpret_cast<uint4*>(xs + ((size_t)(buf * MT + b) * KC) * 512 + tid * 8) = xreg[b];
+        for (int i = 0; i < XPIECES; i++) {
+            const int e = i * 256 + tid;
+            if (MT * KC * 64 % 256 == 0 || e < MT * KC * 64)
+                *reinterpret_cast<uint4*>(xs + (size_t)buf * (MT * KC * 512) + (size_t)e * 8) = xreg[i];
+        }
     };
-    auto compute = [&](int buf) {
+    auto compute = [&](int xbuf, int wbuf) {
 #pragma unroll
         for (int c = 0; c < KC; c++) {
 #pragma unroll
             for (int b = 0; b < MT; b++) {
                 bf16x8_t xf =
-                    *reinterpret_cast<const bf16x8_t*>(xs + ((size_t)((buf * MT + b) * KC + c)) * 512 + lane * 8);
+                    *reinterpret_cast<const bf16x8_t*>(xs + ((size_t)((xbuf * MT + b) * KC + c)) * 512 + lane * 8);
 #pragma unroll
                 for (int a = 0; a < NW; a++)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[buf][a][c], xf, acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[wbuf][a][c], xf, acc[a][b], 0, 0, 0);
             }
         }
     };
 
     if (n_stage > 0) {
-        load_x(ks_begin);
-        load_w(0, ks_begin);
+        // prologue: activations of stage 0 first (they are waited for first), then NBUF-1 weight stages
+        load_x(0);
+#pragma unroll
+        for (int u = 0; u < NBUF - 1; u++)
+            if (u < n_stage) load_w(u, u);
         store_x(0);
         __syncthreads();
-        for (int s = 0; s < n_stage; s += 2) {
-            // even stage: compute from buffer 0, prefetch into buffer 1
-            if (s + 1 < n_stage) {
-                load_x(ks_begin + (s + 1) * KC);
-                load_w(1, ks_begin + (s + 1) * KC);
+        for (int s0 = 0; s0 < n_stage; s0 += NBUF) {
+#pragma unroll
+            for (int u = 0; u < NBUF; u++) {
+                const int s = s0 + u;
+                if (s < n_stage) {
+                    // Loads are issued oldest-needed first: the activation loads of the next stage are
+                    // waited for at the end of this stage, the weight loads three stages later, so the
+                    // wait on the former leaves the latter in flight.
+                    if (s + 1 < n_stage) load_x(s + 1);
+                    if (s + NBUF - 1 < n_stage) load_w((u + NBUF - 1) % NBUF, s + NBUF - 1);
+                    compute(u & 1, u);
+                    if (s + 1 < n_stage) store_x((u + 1) & 1);
+                    __syncthreads();
+                }
             }
-            compute(0);
-            if (s + 1 < n_stage) store_x(1);
-            __syncthreads();
-            if (s + 1 >= n_stage) break;
-            // odd stage
-            if (s + 2 < n_stage) {
-                load_x(ks_begin + (s + 2) * KC);
-                load_w(0, ks_begin + (s + 2) * KC);
-            }
-            compute(1);
-            if (s + 2 < n_stage) store_x(0);
-            __syncthreads();
         }
     }
 
@@ -217,8 +229,9 @@ int sled_launch_gemm(const sled_model* m, const void* X, const void* W, int T, i
         if (KS % split_k || (KS / split_k) % KC) SLED_FAIL(SLED_EINVAL, "gemm: bad split %d for K=%d", split_k, K);
         const int kps = KS / split_k;
         const int mt_total = T_pad / 16;
-        // rows are processed in blocks of MT tiles; pick the smallest MT in {2,4,6,8} covering them
-        int MT = mt_total <= 2 ? 2 : mt_total <= 4 ? 4 : mt_total <= 6 ? 6 : 8;
+        // rows are processed in blocks of at most 8 tiles (128 rows), evenly sized
+        const int zb = (mt_total + 7) / 8;
+        int MT = (mt_total + zb - 1) / zb;
         const int zblocks = (mt_total + MT - 1) / MT;
         const bool wide = ((NT + 7) / 8) * split_k >= 512;  // enough workgroups even with two tiles per wavefront
         dim3 grid(wide ? (NT + 7) / 8 : (NT + 3) / 4, split_k, zblocks);
@@ -231,9 +244,13 @@ int sled_launch_gemm(const sled_model* m, const void* X, const void* W, int T, i
         return wide ? launch_bf16<M_, 2>(epilogue, grid, lds, st, Xb, Wb, NT, KS, kps, T, T_pad, N, out_f32, oa, F_act) \
                     : launch_bf16<M_, 1>(epilogue, grid, lds, st, Xb, Wb, NT, KS, kps, T, T_pad, N, out_f32, oa, F_act);
         switch (MT) {
+            SLED_GEMM_CASE(1)
             SLED_GEMM_CASE(2)
+            SLED_GEMM_CASE(3)
             SLED_GEMM_CASE(4)
+            SLED_GEMM_CASE(5)
             SLED_GEMM_CASE(6)
+            SLED_GEMM_CASE(7)
             default:
                 SLED_GEMM_CASE(8)
         }

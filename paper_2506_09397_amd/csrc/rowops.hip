@@ -9,12 +9,17 @@
 
 namespace {
 
-__device__ inline float block_sum_256(float x, float* sh /*[4]*/) {
+// sum over the workgroup (blockDim.x a multiple of 64, at most 1024); every thread gets the result;
+// the order of additions is fixed
+__device__ inline float block_sum(float x, float* sh /*[16]*/) {
     for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = x;
     __syncthreads();
-    return sh[0] + sh[1] + sh[2] + sh[3];
+    float t = 0.f;
+    const int nw = blockDim.x >> 6;
+    for (int i = 0; i < nw; i++) t += sh[i];
+    return t;
 }
 
 // store 8 consecutive normalised activations of row t starting at column c0
@@ -36,7 +41,7 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restrict__ tokens, const void* __restrict__ E,
                                                          int V, int d, float eps, const float* __restrict__ gain,
                                                          float* __restrict__ h, void* __restrict__ X) {
-    __shared__ float sh[4];
+    __shared__ float sh[16];
     const int t = blockIdx.x;
     int tok = tokens[t];
     tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restri
             ss += v[i] * v[i];
         }
     }
-    const float tot = block_sum_256(ss, sh);
+    const float tot = block_sum(ss, sh);
     const float r = 1.0f / sqrtf(tot / (float)d + eps);
     for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
         float v[8];
@@ -70,13 +75,13 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restri
 
 // h[t,:] += sum_s partial[s][t][:]  (s ascending);  X[t,:] = rmsnorm(h) * gain
 template <bool BF16>
-__global__ __launch_bounds__(256) void residual_norm_kernel(const float* __restrict__ partial, int n_split, int T_pad,
+__global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __restrict__ partial, int n_split, int T_pad,
                                                             int d, float eps, const float* __restrict__ gain,
                                                             float* __restrict__ h, void* __restrict__ X) {
-    __shared__ float sh[4];
+    __shared__ float sh[16];
     const int t = blockIdx.x;
     float ss = 0.f;
-    for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
+    for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
         float4 a = *reinterpret_cast<const float4*>(h + (size_t)t * d + c);
         for (int s = 0; s < n_split; s++) {
             float4 p = *reinterpret_cast<const float4*>(partial + ((size_t)s * T_pad + t) * d + c);
@@ -88,9 +93,9 @@ __global__ __launch_bounds__(256) void residual_norm_kernel(const float* __restr
         *reinterpret_cast<float4*>(h + (size_t)t * d + c) = a;
         ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
-    const float tot = block_sum_256(ss, sh);
+    const float tot = block_sum(ss, sh);
     const float r = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+    for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
         float v[8];
         for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
         store_act8<BF16>(X, t, c, d, v);
@@ -110,15 +115,15 @@ __global__ void rope_table_kernel(sled_step_meta meta, const int32_t* __restrict
     }
 }
 
-// Reduce the QKV partial sums of row t, rotate q and k, write q to Q[T, Hq, D] and k, v into the
-// request's page slot for position L + j.
+// Reduce the QKV partial sums of one head of row t (blockIdx = (t, head), heads ordered q, k, v),
+// rotate q and k, write q to Q[T, Hq, D] and k, v into the request's page slot for position L + j.
 template <bool BF16>
-__global__ __launch_bounds__(256) void qkv_rope_store_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev,
-                                                             const float* __restrict__ partial, int n_split, int T_pad,
-                                                             int Hq, int Hkv, int D, const float2* __restrict__ cs,
-                                                             void* __restrict__ Q, void* __restrict__ k_pool,
-                                                             void* __restrict__ v_pool, int64_t n_pages, int layer) {
-    const int t = blockIdx.x;
+__global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev,
+                                                            const float* __restrict__ partial, int n_split, int T_pad,
+                                                            int Hq, int Hkv, int D, const float2* __restrict__ cs,
+                                                            void* __restrict__ Q, void* __restrict__ k_pool,
+                                                            void* __restrict__ v_pool, int64_t n_pages, int layer) {
+    const int t = blockIdx.x, head = blockIdx.y;
     const int b = meta.row_req[t];
     const int pos = len_dev[meta.req_id[b]] + meta.row_j[t];
     const int page = meta.pages[meta.cu_pages[b] + (pos >> 4)];
@@ -131,54 +136,55 @@ __global__ __launch_bounds__(256) void qkv_rope_store_kernel(sled_step_meta meta
         for (int s = 0; s < n_split; s++) a += partial[((size_t)s * T_pad + t) * n_qkv + col];
         return a;
     };
-    // rotary pairs of q and k heads
-    const int n_pairs = (Hq + Hkv) * half;
-    for (int e = threadIdx.x; e < n_pairs; e += 256) {
-        const int head = e / half, i = e - head * half;
-        const int c1 = head * D + i, c2 = c1 + half;
-        const float x1 = fetch(c1), x2 = fetch(c2);
-        const float2 sc = cs[(size_t)t * half + i];
-        const float y1 = x1 * sc.x - x2 * sc.y;
-        const float y2 = x2 * sc.x + x1 * sc.y;
-        if (head < Hq) {
-            if (BF16) {
-                bf16_t* q = static_cast<bf16_t*>(Q) + ((size_t)t * Hq + head) * D;
-                q[i] = f32_to_bf16(y1);
-                q[i + half] = f32_to_bf16(y2);
+    if (head < Hq + Hkv) {
+        for (int i = threadIdx.x; i < half; i += 64) {
+            const int c1 = head * D + i, c2 = c1 + half;
+            const float x1 = fetch(c1), x2 = fetch(c2);
+            const float2 sc = cs[(size_t)t * half + i];
+            const float y1 = x1 * sc.x - x2 * sc.y;
+            const float y2 = x2 * sc.x + x1 * sc.y;
+            if (head < Hq) {
+                if (BF16) {
+                    bf16_t* q = static_cast<bf16_t*>(Q) + ((size_t)t * Hq + head) * D;
+                    q[i] = f32_to_bf16(y1);
+                    q[i + half] = f32_to_bf16(y2);
+                } else {
+                    float* q = static_cast<float*>(Q) + ((size_t)t * Hq + head) * D;
+                    q[i] = y1;
+                    q[i + half] = y2;
+                }
             } else {
-                float* q = static_cast<float*>(Q) + ((size_t)t * Hq + head) * D;
-                q[i] = y1;
-                q[i + half] = y2;
-            }
-        } else {
-            const int g = head - Hq;
-            const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
-            if (BF16) {
-                // K page-head block in operand order: element (slot, dd) at
-                //   (dd/32)*512 + (((dd%32)/8)*16 + slot)*8 + dd%8
-                bf16_t* kp = static_cast<bf16_t*>(k_pool) + base;
-                const int d1 = i, d2 = i + half;
-                kp[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) << 4) + slot) * 8 + (d1 & 7)] = f32_to_bf16(y1);
-                kp[(d2 >> 5) * 512 + ((((d2 & 31) >> 3) << 4) + slot) * 8 + (d2 & 7)] = f32_to_bf16(y2);
-            } else {
-                float* kp = static_cast<float*>(k_pool) + base + (size_t)slot * D;
-                kp[i] = y1;
-                kp[i + half] = y2;
+                const int g = head - Hq;
+                const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
+                if (BF16) {
+                    // K page-head block in operand order: element (slot, dd) at
+                    //   (dd/32)*512 + (((dd%32)/8)*16 + slot)*8 + dd%8
+                    bf16_t* kp = static_cast<bf16_t*>(k_pool) + base;
+                    const int d1 = i, d2 = i + half;
+                    kp[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) << 4) + slot) * 8 + (d1 & 7)] = f32_to_bf16(y1);
+                    kp[(d2 >> 5) * 512 + ((((d2 & 31) >> 3) << 4) + slot) * 8 + (d2 & 7)] = f32_to_bf16(y2);
+                } else {
+                    float* kp = static_cast<float*>(k_pool) + base + (size_t)slot * D;
+                    kp[i] = y1;
+                    kp[i + half] = y2;
+                }
             }
         }
-    }
-    // v heads: no rotation
-    for (int e = threadIdx.x; e < Hkv * D; e += 256) {
-        const int g = e / D, dd = e - g * D;
-        const float v = fetch((Hq + Hkv) * D + e);
+    } else {
+        // v head: no rotation
+        const int g = head - Hq - Hkv;
         const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
-        if (BF16) {
-            // V page-head block: element (slot, dd) at (((dd/16)/2)*64 + (slot/4)*16 + dd%16)*8 + ((dd/16)%2)*4 + slot%4
-            const int dt = dd >> 4;
-            static_cast<bf16_t*>(v_pool)[base + ((size_t)((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15))) * 8 + (dt & 1) * 4 +
-                                         (slot & 3)] = f32_to_bf16(v);
-        } else {
-            static_cast<float*>(v_pool)[base + (size_t)slot * D + dd] = v;
+        for (int dd = threadIdx.x; dd < D; dd += 64) {
+            const float v = fetch((Hq + Hkv) * D + g * D + dd);
+            if (BF16) {
+                // V page-head block: element (slot, dd) at
+                //   (((dd/16)/2)*64 + (slot/4)*16 + dd%16)*8 + ((dd/16)%2)*4 + slot%4
+                const int dt = dd >> 4;
+                static_cast<bf16_t*>(v_pool)[base + ((size_t)((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15))) * 8 +
+                                             (dt & 1) * 4 + (slot & 3)] = f32_to_bf16(v);
+            } else {
+                static_cast<float*>(v_pool)[base + (size_t)slot * D + dd] = v;
+            }
         }
     }
 }
@@ -300,11 +306,13 @@ int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, fl
 
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
                               const float* gain, hipStream_t st) {
+    // one float4 per thread per pass: short rows get small workgroups
+    const int bs = m->s.d_model >= 4096 ? 1024 : m->s.d_model >= 2048 ? 512 : 256;
     if (m->s.dtype == SLED_BF16)
-        hipLaunchKernelGGL(residual_norm_kernel<true>, dim3(T), dim3(256), 0, st, partial, n_split, T_pad, m->s.d_model,
+        hipLaunchKernelGGL(residual_norm_kernel<true>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
                            m->s.rms_eps, gain, h, X);
     else
-        hipLaunchKernelGGL(residual_norm_kernel<false>, dim3(T), dim3(256), 0, st, partial, n_split, T_pad, m->s.d_model,
+        hipLaunchKernelGGL(residual_norm_kernel<false>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
                            m->s.rms_eps, gain, h, X);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
@@ -320,12 +328,13 @@ int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled
 
 int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
                                const float* partial, int n_split, int T_pad, const float* cs, void* Q, hipStream_t st) {
+    const dim3 grid(meta.T, m->s.n_q_heads + 2 * m->s.n_kv_heads);
     if (m->s.dtype == SLED_BF16)
-        hipLaunchKernelGGL(qkv_rope_store_kernel<true>, dim3(meta.T), dim3(256), 0, st, meta, p->len_dev, partial, n_split,
+        hipLaunchKernelGGL(qkv_rope_store_kernel<true>, grid, dim3(64), 0, st, meta, p->len_dev, partial, n_split,
                            T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q,
                            p->k_pool, p->v_pool, p->n_pages, layer);
     else
-        hipLaunchKernelGGL(qkv_rope_store_kernel<false>, dim3(meta.T), dim3(256), 0, st, meta, p->len_dev, partial, n_split,
+        hipLaunchKernelGGL(qkv_rope_store_kernel<false>, grid, dim3(64), 0, st, meta, p->len_dev, partial, n_split,
                            T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q,
                            p->k_pool, p->v_pool, p->n_pages, layer);
     SLED_LAUNCH_CHECK();

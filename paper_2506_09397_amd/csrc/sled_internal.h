@@ -93,6 +93,14 @@ struct sled_model {
     float* g_final;
     std::vector<sled_layer_weights> layers;
     std::vector<void*> allocs;
+    // kernel timing (sled_profile_enable): one (class, start event, end event) per launch
+    struct prof_span {
+        int cls;
+        hipEvent_t e0, e1;
+    };
+    bool prof_on = false;
+    std::vector<prof_span> prof_spans;     // recorded since the last read
+    std::vector<hipEvent_t> prof_free;     // events ready for reuse
 };
 
 struct sled_request {

@@ -30,8 +30,10 @@ EXPORTS = [
     "sled_model_create", "sled_model_load", "sled_model_destroy",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
     "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch",
-    "sled_accept_workspace_bytes", "sled_accept", "sled_strerror", "sled_last_error",
+    "sled_accept_workspace_bytes", "sled_accept", "sled_profile_enable", "sled_profile_read",
+    "sled_strerror", "sled_last_error",
 ]
+PROF_PROJ, PROF_ATTN, PROF_ROWS, PROF_N = 0, 1, 2, 3
 
 
 class SledError(RuntimeError):
@@ -73,6 +75,8 @@ def lib() -> C.CDLL:
     L.sled_accept_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     L.sled_accept_workspace_bytes.restype = C.c_size_t
     L.sled_accept.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.sled_profile_enable.argtypes = [vp, C.c_int]
+    L.sled_profile_read.argtypes = [vp, vp, C.POINTER(C.c_float), ip]
     L.sled_strerror.argtypes = [C.c_int]
     L.sled_strerror.restype = C.c_char_p
     L.sled_last_error.restype = C.c_char_p
@@ -185,6 +189,17 @@ def sled_accept(mode: int, k: Sequence[int], vocab: int, temperature: float, log
     _check(lib().sled_accept(mode, len(k), _ints(k), vocab, float(temperature), _ptr(logits), _ptr(tokens), _ptr(draft_q),
                              _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token), _ptr(workspace),
                              workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sled_profile_enable(model: int, on: bool) -> None:
+    _check(lib().sled_profile_enable(model, 1 if on else 0))
+
+
+def sled_profile_read(model: int):
+    ms = (C.c_float * PROF_N)()
+    n = (C.c_int * PROF_N)()
+    _check(lib().sled_profile_read(model, _stream(), ms, n))
+    return list(ms), list(n)
 
 
 # ---------------------------------------------------------------------------------------- helpers

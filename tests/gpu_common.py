@@ -8,7 +8,7 @@ import torch
 from oracle import sled_oracle as O
 from paper_2506_09397_amd import sled, synth
 from paper_2506_09397_amd.runtime import Verifier
-from helpers import oracle_model
+from helpers import oracle_model, oracle_requests  # noqa: F401
 
 # Decisions whose oracle margin is below these bounds may legitimately differ by float32 round-off
 # of exp() in the row sums (accept test) or by ~1e-16 relative round-off of the float64 prefix sums
@@ -61,10 +61,3 @@ def build_verifier(shape: synth.ModelShape, weights_seed: int, n_pages: int, max
     w = synth.SynthWeights(shape, seed=weights_seed, device="cuda", std=std, gain_jitter=gain_jitter)
     v = Verifier(shape, w, n_pages, max_requests, B_max, ctx_tokens_max)
     return v, w
-
-
-def oracle_requests(batch: synth.Batch, K_list, V_list):
-    reqs, offs = [], batch.row_offsets()
-    for i in range(batch.B):
-        reqs.append({"tokens": batch.tokens[offs[i]: offs[i + 1]], "K": synth.as_f64(K_list[i]), "V": synth.as_f64(V_list[i])})
-    return reqs

@@ -1,0 +1,93 @@
+"""GPU parity at the real shapes: Llama-3-8B-shaped decoder (bf16, random init N(0, 0.02)), batch of 16
+requests with contexts uniform in [512, 2048] and k uniform in [2, 8] -- the configuration bench.py times.
+
+The oracle cannot pin these values to anything outside itself (random weights have no published
+outputs): parity here rests on the oracle's own pins plus element-wise agreement with it.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sled_oracle as O
+from paper_2506_09397_amd import sled, synth
+from gpu_common import build_verifier
+from helpers import oracle_model, oracle_requests
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+def _setup(shape, batch, seed=0):
+    B = batch.B
+    ctx_budget = sum(batch.ctx_len) + 9 * B
+    v, w = build_verifier(shape, seed, n_pages=ctx_budget // 16 + 2 * B + 8, max_requests=B, B_max=B,
+                          ctx_tokens_max=ctx_budget)
+    reqs, KV = [], []
+    for i in range(B):
+        K, V = synth.context_kv(shape, batch.ctx_len[i], seed=seed, req=i, device="cuda")
+        reqs.append(v.open())
+        v.append_context([reqs[i]], [K], [V])
+        KV.append((K.cpu(), V.cpu()))
+    return v, w, reqs, KV
+
+
+def test_llama8b_two_layers_all_logits():
+    """Every layer shape of the 8B model (d 4096, 32/8 heads, FFN 14336, vocab 128256) at depth 2:
+    all T x V logits against the oracle."""
+    shape = synth.scaled_shape(synth.SHAPES["llama8b"], n_layers=2)
+    batch = synth.draw_batch("b16", shape.vocab, seed=0)
+    v, w, reqs, KV = _setup(shape, batch)
+    tokens = torch.from_numpy(batch.tokens).cuda()
+    got = v.verify(reqs, batch.k, tokens).cpu().numpy()
+    oreqs = oracle_requests(batch, [a for a, _ in KV], [b for _, b in KV])
+    t0 = time.time()
+    want = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w, "bf16"), oreqs)], axis=0)
+    t1 = time.time()
+    exact = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w, "exact"), oreqs)], axis=0)
+    err, err_exact = np.abs(got - want).max(), np.abs(got - exact).max()
+    row_err = np.abs(got - want).max(axis=1)
+    print(f"8B shape, 2 layers, T={batch.T}: max |logit error| {err:.3e} (median row {np.median(row_err):.1e}); "
+          f"vs unrounded oracle {err_exact:.3e}; logit std {want.std():.3f}; oracle {t1 - t0:.1f} s")
+    assert err < TOL_BF16
+    assert err_exact < TOL_BF16
+    # greedy acceptance chained on the logits, where the oracle's top-2 gap is clear of the error
+    a, t = v.accept(sled.GREEDY, batch.k, v.logits[: batch.T], tokens)
+    acc = O.accept_batch("greedy", batch.k, want.astype(np.float32).astype(np.float64), batch.tokens)
+    a, t = a.cpu().numpy(), t.cpu().numpy()
+    n = 0
+    for i, r in enumerate(acc):
+        if r["margin"] > 4 * err:
+            assert (a[i], t[i]) == (r["accept_len"], r["out_token"])
+            n += 1
+    assert n >= batch.B // 2
+    v.destroy()
+
+
+def test_llama8b_full_depth_sampled_requests():
+    """All 32 layers, the batch of 16 as benchmarked; the oracle scores two of the requests
+    (requests are independent, so their rows are a sample of the batch's outputs)."""
+    shape = synth.SHAPES["llama8b"]
+    batch = synth.draw_batch("b16", shape.vocab, seed=0)
+    v, w, reqs, KV = _setup(shape, batch)
+    tokens = torch.from_numpy(batch.tokens).cuda()
+    got = v.verify(reqs, batch.k, tokens).cpu().numpy()
+    assert np.isfinite(got).all()
+    offs = batch.row_offsets()
+    sample = [int(np.argmax(batch.ctx_len)), int(np.argmin(batch.ctx_len))]
+    oreqs = [{"tokens": batch.tokens[offs[i]: offs[i + 1]], "K": synth.as_f64(KV[i][0]), "V": synth.as_f64(KV[i][1])}
+             for i in sample]
+    t0 = time.time()
+    res = O.verify_batch(oracle_model(shape, w, "bf16", cache=False), oreqs)
+    t1 = time.time()
+    errs = []
+    for i, r in zip(sample, res):
+        e = np.abs(got[offs[i]: offs[i + 1]] - r["logits"]).max()
+        errs.append(e)
+        print(f"8B, 32 layers, request {i} (L={batch.ctx_len[i]}, k={batch.k[i]}): max |logit error| {e:.3e}, "
+              f"logit std {r['logits'].std():.3f}")
+    print(f"oracle time for {len(sample)} requests: {t1 - t0:.1f} s")
+    assert max(errs) < TOL_BF16
+    v.destroy()
