@@ -39,7 +39,7 @@ def oracle_model(shape: synth.ModelShape, weights: synth.SynthWeights, round_poi
     """round_points defaults to the storage rounding of the model's dtype.  n_layers < shape.n_layers
     gives the oracle for the first n_layers layers followed by the final norm and LM head."""
     if round_points is None:
-        round_points = "bf16" if shape.dtype == "bf16" else "exact"
+        round_points = "bf16x2" if shape.dtype == "bf16" else "exact"
     return O.OracleModel(shape.n_layers if n_layers is None else n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                          shape.d_ffn, shape.vocab, shape.rope_theta, shape.rms_eps, F64Weights(weights, cache),
                          round_points)

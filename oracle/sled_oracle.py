@@ -26,13 +26,19 @@ position embedding with the half-split pairing (i, i + D/2) used by the public
 LLaMA implementations, grouped-query attention (query head h reads kv head
 h // group), SwiGLU MLP, no biases, untied LM head.
 
-Storage-rounding option.  A model whose storage type is bf16 keeps some tensors in
-bf16 between operators.  With round_points="bf16" the oracle rounds (to nearest,
-ties to even) exactly those tensors and nothing else: the normalised activations fed
-to the projections, q/k/v after rotation, the softmax numerators that multiply V
-(see attention_rows), the attention output, and the SwiGLU product.  All sums, the
-softmax denominator, the residual stream and the logits stay float64.
-round_points="exact" rounds nothing.
+Storage-rounding option (round_points).  A bf16 model keeps tensors in bf16 between
+operators; the oracle can round (to nearest, ties to even) exactly those tensors and
+nothing else.  All sums, the softmax denominator, the residual stream and the logits
+stay float64 in every mode.
+  "exact"   rounds nothing (weights and given context K/V are bf16 values already).
+  "bf16x2"  K and V of the new tokens are rounded to bf16 -- that is what a bf16 K/V cache
+            holds; every other activation between operators (normalised activations, q,
+            softmax numerators, attention output, SwiGLU product) is kept as a PAIR of
+            bf16 numbers hi + lo (about 16 significant bits).  This is the storage contract
+            of a SLED_BF16 model in the HIP library and the default for parity tests.
+  "bf16"    every one of those tensors is a single bf16 number: the usual all-bf16
+            inference pipeline, kept to measure what it would cost (at 8B shape its
+            logits sit 5e-2..1e-1 away from "exact", beyond the 2e-2 tolerance).
 
 Pins (tests/test_oracle_*.py, no GPU): Hugging Face's LlamaForCausalLM in float64
 for the forward; closed forms, brute force over the uniforms, chi-square
@@ -60,11 +66,21 @@ def bf16_round(x: np.ndarray) -> np.ndarray:
     return out.reshape(x32.shape)
 
 
-def _rounder(round_points: str):
+def bf16x2_round(x: np.ndarray) -> np.ndarray:
+    """Value kept as a pair of bfloat16 numbers hi + lo: hi = bf16(x), lo = bf16(x - hi)."""
+    hi = bf16_round(x)
+    return hi + bf16_round(np.asarray(x, dtype=np.float64) - hi)
+
+
+def _rounder(round_points: str, cached: bool = False):
+    """Storage rounding of an activation.  `cached` marks K and V, which live in the bf16 cache as
+    single bf16 numbers in every bf16 mode; "bf16x2" keeps all other activations as bf16 pairs."""
     if round_points == "exact":
         return lambda a: a
     if round_points == "bf16":
         return bf16_round
+    if round_points == "bf16x2":
+        return bf16_round if cached else bf16x2_round
     raise ValueError(round_points)
 
 
@@ -119,7 +135,7 @@ def attention_rows(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int, grou
             else:
                 t = s * LOG2E
                 p = np.exp2(t - math.ceil(t.max()))
-                out[j, h, :] = (bf16_round(p) @ V[:m, g, :]) / p.sum()
+                out[j, h, :] = (_rounder(round_points)(p) @ V[:m, g, :]) / p.sum()
     return out
 
 
@@ -149,7 +165,7 @@ def layer_rows(model: OracleModel, W: Dict[str, np.ndarray], h: np.ndarray, posi
 
     h[n, d] residual stream in; K_ctx, V_ctx[n_ctx, Hkv, D] this layer's cached context
     (K already rotated).  Returns (h_out, k_new[n,Hkv,D] rotated, v_new[n,Hkv,D])."""
-    R = _rounder(model.round_points)
+    R, RC = _rounder(model.round_points), _rounder(model.round_points, cached=True)
     n = h.shape[0]
     Hq, Hkv, D = model.n_q_heads, model.n_kv_heads, model.head_dim
     x = R(rmsnorm(h, W["g_attn"], model.rms_eps))
@@ -157,8 +173,8 @@ def layer_rows(model: OracleModel, W: Dict[str, np.ndarray], h: np.ndarray, posi
     k = (x @ W["wk"].T).reshape(n, Hkv, D)
     v = (x @ W["wv"].T).reshape(n, Hkv, D)
     q = R(rope(q, positions, model.rope_theta))
-    k = R(rope(k, positions, model.rope_theta))
-    v = R(v)
+    k = RC(rope(k, positions, model.rope_theta))
+    v = RC(v)
     K_all = np.concatenate([K_ctx, k], axis=0)
     V_all = np.concatenate([V_ctx, v], axis=0)
     o = R(attention_rows(q, K_all, V_all, K_ctx.shape[0], model.group, model.round_points)).reshape(n, Hq * D)

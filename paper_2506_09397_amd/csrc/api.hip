@@ -431,7 +431,7 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
 namespace {
 
 struct ws_plan {
-    size_t h, xa, xo, xf, q, partial, cs, part_o, part_ml, total;
+    size_t h, xa, xo, xf, q, partial, cs, part_o, part_ml, total, T_alloc;
 };
 
 int attn_chunk_pages(int64_t total_page_heads) {
@@ -442,12 +442,11 @@ int attn_chunk_pages(int64_t total_page_heads) {
     return (int)c;
 }
 
-int gemm_split(const sled_model* m, int T, int N, int K) { return sled_gemm_pick_split(m, T, N, K); }
-
 ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     const sled_shape& s = m->s;
     const size_t T_alloc = align_up(T + 64, 128), T_pad = align_up(T, 16);  // row blocks of the GEMMs may overhang
     const size_t d = s.d_model, F = s.d_ffn, HD = (size_t)s.n_q_heads * s.head_dim;
+    const size_t planes = s.dtype == SLED_BF16 ? 2 : 1;  // bf16 models keep activations as hi + lo
     ws_plan w;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -455,16 +454,17 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
         off += align_up(bytes, 256);
         return o;
     };
+    w.T_alloc = T_alloc;
     w.h = take(T_alloc * d * sizeof(float));
-    w.xa = take(T_alloc * d * m->elem);
-    w.xo = take(T_alloc * HD * m->elem);
-    w.xf = take(T_alloc * F * m->elem);
-    w.q = take(T_alloc * HD * m->elem);
+    w.xa = take(planes * T_alloc * d * m->elem);
+    w.xo = take(planes * T_alloc * HD * m->elem);
+    w.xf = take(planes * T_alloc * F * m->elem);
+    w.q = take(planes * T_alloc * HD * m->elem);
     size_t part = 0;
-    part = std::max(part, (size_t)gemm_split(m, T, m->n_qkv, s.d_model) * T_pad * m->n_qkv);
-    part = std::max(part, (size_t)gemm_split(m, T, s.d_model, (int)HD) * T_pad * d);
-    part = std::max(part, (size_t)gemm_split(m, T, s.d_model, s.d_ffn) * T_pad * d);
-    if (s.dtype == SLED_F32) part = std::max(part, T_pad * 2 * F);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, m->n_qkv, s.d_model, false).split * T_pad * m->n_qkv);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, (int)HD, false).split * T_pad * d);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, s.d_ffn, false).split * T_pad * d);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, 2 * s.d_ffn, s.d_model, false).split * T_pad * 2 * F);
     w.partial = take(part * sizeof(float));
     w.cs = take((size_t)T * s.head_dim * sizeof(float));
     w.part_o = take((size_t)n_work * QT * 16 * 128 * sizeof(float));
@@ -592,13 +592,21 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     float* part_ml = reinterpret_cast<float*>(ws + wp.part_ml);
     const int T_pad = (int)align_up(T, 16);
     const int d = s.d_model, F = s.d_ffn, HD = s.n_q_heads * s.head_dim;
-    const int sp_qkv = gemm_split(m, T, m->n_qkv, d), sp_o = gemm_split(m, T, d, HD), sp_dn = gemm_split(m, T, d, F);
+    const bool bf = s.dtype == SLED_BF16;
+    // distance between the hi and lo planes of each activation buffer (bf16 models)
+    const size_t pl_d = bf ? wp.T_alloc * (size_t)d : 0, pl_hd = bf ? wp.T_alloc * (size_t)HD : 0,
+                 pl_f = bf ? wp.T_alloc * (size_t)F : 0;
+    const sled_gemm_plan g_qkv = sled_gemm_make_plan(m, m->n_qkv, d, false), g_o = sled_gemm_make_plan(m, d, HD, false),
+                         g_dn = sled_gemm_make_plan(m, d, F, false), g_lm = sled_gemm_make_plan(m, s.vocab, d, true);
+    // gate/up applies SwiGLU in its epilogue when it runs unsplit; otherwise (and for fp32 models) a row
+    // kernel reduces the K slices and applies it
+    sled_gemm_plan g_gu = sled_gemm_make_plan(m, 2 * F, d, false);
+    const bool gu_fused = bf && g_gu.split == 1;
 
 #define SLED_TRY(x)                        \
     do {                                   \
         if ((rc = (x)) != SLED_OK) return rc; \
     } while (0)
-
 // a launch inside a timing scope of class c
 #define SLED_RUN(c, x)                     \
     do {                                   \
@@ -607,25 +615,25 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     } while (0)
 
     SLED_RUN(SLED_PROF_ROWS, sled_launch_rope_table(m, p, meta, cs, st));
-    SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, m->layers[0].g_attn, st));
+    SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, pl_d, m->layers[0].g_attn, st));
     for (int l = 0; l < s.n_layers; l++) {
         const sled_layer_weights& w = m->layers[l];
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, sp_qkv, partial, nullptr, 0, st));
-        SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, meta, l, partial, sp_qkv, T_pad, cs, qb, st));
-        SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, part_o, part_ml, xo, QT, st));
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, sp_o, partial, nullptr, 0, st));
-        SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, sp_o, T, T_pad, h, xa, w.g_mlp, st));
-        if (s.dtype == SLED_BF16) {
-            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, 1, nullptr, xf, F, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, g_qkv, partial, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, meta, l, partial, g_qkv.split, T_pad, cs, qb, pl_hd, st));
+        SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, part_o, part_ml, xo, pl_hd, QT, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, pl_hd, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, g_o, partial, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_o.split, T, T_pad, h, xa, pl_d, w.g_mlp, st));
+        if (gu_fused) {
+            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, g_gu, nullptr, xf, pl_f, F, st));
         } else {
-            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, 1, partial, nullptr, 0, st));
-            SLED_RUN(SLED_PROF_ROWS, sled_launch_swiglu_f32(partial, T, F, static_cast<float*>(xf), st));
+            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, g_gu, partial, nullptr, 0, 0, st));
+            SLED_RUN(SLED_PROF_ROWS, sled_launch_swiglu_reduce(m, partial, g_gu.split, T, T_pad, xf, pl_f, st));
         }
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xf, w.w_down, T, T_pad, d, F, SLED_EPI_PARTIAL, sp_dn, partial, nullptr, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xf, pl_f, w.w_down, T, T_pad, d, F, SLED_EPI_PARTIAL, g_dn, partial, nullptr, 0, 0, st));
         const float* next_gain = (l + 1 < s.n_layers) ? m->layers[l + 1].g_attn : m->g_final;
-        SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, sp_dn, T, T_pad, h, xa, next_gain, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_dn.split, T, T_pad, h, xa, pl_d, next_gain, st));
     }
-    SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, 1, logits, nullptr, 0, st));
+    SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, g_lm, logits, nullptr, 0, 0, st));
     SLED_TRY(stage_release(sl, st));
 #undef SLED_RUN
 #undef SLED_TRY

@@ -7,17 +7,18 @@
 // step and reused G * n_i times (this is the whole arithmetic intensity the step has).
 //
 // bf16 kernel, per work item (request, kv head, run of pages):
-//   S^T[token, qrow] = K_page * Q^T      v_mfma_f32_16x16x32_bf16, K page tile as the A operand
+//   S^T[token, qrow] = K_page * Q^T      v_mfma_f32_16x16x32_bf16, K page tile as the A operand; q is a
+//                                        bf16 pair (hi + lo, two MFMAs), its tiles sit in LDS
 //   online softmax per qrow              (a lane owns one qrow: reductions over 4 registers and
 //                                         2 cross-lane steps); the running maximum is rounded up
 //                                         to a whole number of log2 units, so the numerators
 //                                         p = 2^(s - M) are rounded to bf16 the same way whatever
 //                                         the page order or the split of the keys over wavefronts
 //   O^T[d, qrow]    += V_page^T * P^T    v_mfma_f32_16x16x16_bf16; the S^T accumulator registers
-//                                        are, unchanged, the P^T operand
+//                                        are, in place, the P^T operand (p too is a bf16 pair)
 // A page (16 tokens x 128 dims of one kv head) is stored in the pool in operand order, K for the
 // first product and V for the second, so a wavefront reads a whole page with 4 + 4 contiguous
-// 1 KiB loads into registers; there is no LDS traffic in the main loop.  The four wavefronts of a
+// 1 KiB loads into registers, the next page in flight while one is consumed.  The four wavefronts of a
 // workgroup take alternate pages and merge their (max, sum, O) states through LDS at the end; a
 // second kernel merges the work items of one (request, kv head) in a fixed order and writes the
 // attention output in the operand order of the following projection.
@@ -31,15 +32,19 @@ constexpr float NEG_BIG = -1.0e30f;
 
 template <int QT>
 __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, const int32_t* __restrict__ len_dev,
-                                                         const bf16_t* __restrict__ Q, const bf16_t* __restrict__ k_pool,
+                                                         const bf16_t* __restrict__ Q, size_t q_plane,
+                                                         const bf16_t* __restrict__ k_pool,
                                                          const bf16_t* __restrict__ v_pool, int64_t n_pages, int layer,
                                                          int Hq, int Hkv, float scale_log2,
                                                          float* __restrict__ part_o, float* __restrict__ part_ml) {
     constexpr int D = 128;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    float* sh_o = reinterpret_cast<float*>(smem);          // [QT][8][64][4]
-    float* sh_m = sh_o + QT * 8 * 64 * 4;                  // [QT*16]
-    float* sh_l = sh_m + QT * 16;                          // [QT*16]
+    // main loop: Q operand tiles [2 planes][QT][4 k-steps][64 lanes][8]; afterwards the same bytes
+    // serve as the merge buffer [QT][8][64][4] floats
+    bf16_t* sh_q = reinterpret_cast<bf16_t*>(smem);
+    float* sh_o = reinterpret_cast<float*>(smem);
+    float* sh_m = sh_o + QT * 8 * 64 * 4;  // [QT*16]
+    float* sh_l = sh_m + QT * 16;          // [QT*16]
 
     const int w = blockIdx.x;
     const int b = meta.work[4 * w + 0], g = meta.work[4 * w + 1];
@@ -55,23 +60,23 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
     const int32_t* pages = meta.pages + meta.cu_pages[b];
     const int lq = lane & 15, lg = lane >> 4;
 
-    // Q operand tiles: qrow r = qt*16 + lane%16 -> (query position j = r / G, head g*G + r % G)
-    bf16x8_t qf[QT][4];
+    // Q operand tiles, both planes of the bf16 pair: qrow r = qt*16 + l%16 -> (query position
+    // j = r / G, head g*G + r % G); element k = ks*32 + (l/16)*8 ..+8
+    for (int e = tid; e < 2 * QT * 4 * 64; e += 256) {
+        const int l = e & 63, ks = (e >> 6) & 3, qt = (e >> 8) % QT, pl = e / (QT * 256);
+        const int r = qt * 16 + (l & 15);
+        uint4 val = make_uint4(0u, 0u, 0u, 0u);
+        if (r < rows) {
+            const int j = r / G, hh = r - j * G;
+            val = *reinterpret_cast<const uint4*>(Q + pl * q_plane + ((size_t)(row0 + j) * Hq + g * G + hh) * D + ks * 32 +
+                                                  (l >> 4) * 8);
+        }
+        *reinterpret_cast<uint4*>(sh_q + (size_t)e * 8) = val;
+    }
+    __syncthreads();
     int jrow[QT];
 #pragma unroll
-    for (int qt = 0; qt < QT; qt++) {
-        const int r = qt * 16 + lq;
-        const int j = r / G, hh = r - j * G;
-        jrow[qt] = j;
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            if (r < rows) {
-                qf[qt][ks] = *reinterpret_cast<const bf16x8_t*>(Q + ((size_t)(row0 + j) * Hq + g * G + hh) * D + ks * 32 + lg * 8);
-            } else {
-                for (int e = 0; e < 8; e++) qf[qt][ks][e] = (__bf16)0.0f;
-            }
-        }
-    }
+    for (int qt = 0; qt < QT; qt++) jrow[qt] = (qt * 16 + lq) / G;
 
     float m[QT], lsum[QT];
     float4_t o[QT][8];
@@ -83,21 +88,30 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
         for (int dt = 0; dt < 8; dt++) o[qt][dt] = float4_t{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (int pg = page0 + wv; pg < page_end; pg += 4) {
-        const int phys = pages[pg];
-        const size_t base = (((size_t)layer * n_pages + phys) * Hkv + g) * (16 * D);
+    struct page_regs {
         bf16x8_t kf[4];
         uint4 vraw[4];
+    };
+    auto load_page = [&](page_regs& pr, int pg) {
+        const int phys = pages[pg];
+        const size_t base = (((size_t)layer * n_pages + phys) * Hkv + g) * (16 * D);
 #pragma unroll
-        for (int c = 0; c < 4; c++) kf[c] = *reinterpret_cast<const bf16x8_t*>(k_pool + base + c * 512 + lane * 8);
+        for (int c = 0; c < 4; c++) pr.kf[c] = *reinterpret_cast<const bf16x8_t*>(k_pool + base + c * 512 + lane * 8);
 #pragma unroll
-        for (int c = 0; c < 4; c++) vraw[c] = *reinterpret_cast<const uint4*>(v_pool + base + c * 512 + lane * 8);
+        for (int c = 0; c < 4; c++) pr.vraw[c] = *reinterpret_cast<const uint4*>(v_pool + base + c * 512 + lane * 8);
+    };
+    auto process = [&](const page_regs& pr, int pg) {
         const bool need_mask = (pg * 16 + 15) > L;  // page reaches beyond the context: causal part / tail
 #pragma unroll
         for (int qt = 0; qt < QT; qt++) {
             float4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[qt][ks], s, 0, 0, 0);
+            for (int ks = 0; ks < 4; ks++) {
+                const bf16x8_t qh = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)(qt * 4 + ks) * 64 + lane) * 8);
+                const bf16x8_t ql = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)((QT + qt) * 4 + ks) * 64 + lane) * 8);
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pr.kf[ks], qh, s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pr.kf[ks], ql, s, 0, 0, 0);
+            }
             float sv[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) {
@@ -111,27 +125,27 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
             mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
             // The running reference is kept on whole numbers (scores are in log2 units), so every
-            // rescale below is an exact power of two and the bf16 rounding of p does not depend on
-            // the order in which pages are visited: bf16(2^(s-M)) * 2^(M-M') == bf16(2^(s-M')).
+            // rescale is an exact power of two and the rounding of p does not depend on the order in
+            // which pages are visited: bf16(2^(s-M)) * 2^(M-M') == bf16(2^(s-M')).
             const float mnew = fmaxf(m[qt], ceilf(mloc));
             const float alpha = exp2f(m[qt] - mnew);
-            float p[4];
             float psum = 0.f;
+            short4_t ph, pl;  // p as a bf16 pair
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                p[i] = exp2f(sv[i] - mnew);
-                psum += p[i];
+                const float p = exp2f(sv[i] - mnew);
+                psum += p;
+                const bf16_t hi = f32_to_bf16(p);
+                ph[i] = (short)hi;
+                pl[i] = (short)f32_to_bf16(p - bf16_to_f32(hi));
             }
             lsum[qt] = lsum[qt] * alpha + psum;
             m[qt] = mnew;
-            short4_t pb;
-#pragma unroll
-            for (int i = 0; i < 4; i++) pb[i] = (short)f32_to_bf16(p[i]);
 #pragma unroll
             for (int dt = 0; dt < 8; dt++) {
                 // V operand for dims dt*16 .. dt*16+15: half of the 16-byte chunk vraw[dt/2]
-                const uint4 r4 = vraw[dt >> 1];
-                uint32_t lo = (dt & 1) ? r4.z : r4.x, hi = (dt & 1) ? r4.w : r4.y;
+                const uint4 r4 = pr.vraw[dt >> 1];
+                const uint32_t lo = (dt & 1) ? r4.z : r4.x, hi = (dt & 1) ? r4.w : r4.y;
                 short4_t va;
                 va[0] = (short)(lo & 0xffff);
                 va[1] = (short)(lo >> 16);
@@ -140,10 +154,28 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
                 float4_t acc = o[qt][dt];
 #pragma unroll
                 for (int i = 0; i < 4; i++) acc[i] *= alpha;
-                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pb, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, ph, acc, 0, 0, 0);
+                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pl, acc, 0, 0, 0);
             }
         }
+    };
+
+    // the wavefront's pages, two register sets: the next page is in flight while one is consumed
+    {
+        page_regs A, B;
+        int pg = page0 + wv;
+        if (pg < page_end) load_page(A, pg);
+        while (pg < page_end) {
+            if (pg + 4 < page_end) load_page(B, pg + 4);
+            process(A, pg);
+            pg += 4;
+            if (pg >= page_end) break;
+            if (pg + 4 < page_end) load_page(A, pg + 4);
+            process(B, pg);
+            pg += 4;
+        }
     }
+    __syncthreads();  // all wavefronts are done with the Q tiles: the bytes become the merge buffer
     // lane-partial sums -> per-qrow sums
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) {
@@ -203,7 +235,8 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
 // X[t = row0 + j][col = (g*G + hh)*D + d]
 __global__ __launch_bounds__(64) void attn_combine_bf16(sled_step_meta meta, int QT16, int Hq, int Hkv,
                                                         const float* __restrict__ part_o,
-                                                        const float* __restrict__ part_ml, bf16_t* __restrict__ X) {
+                                                        const float* __restrict__ part_ml, bf16_t* __restrict__ X,
+                                                        size_t x_plane) {
     constexpr int D = 128;
     const int b = blockIdx.x / Hkv, g = blockIdx.x - b * Hkv;
     const int r = blockIdx.y;
@@ -227,8 +260,12 @@ __global__ __launch_bounds__(64) void attn_combine_bf16(sled_step_meta meta, int
     const float inv = 1.0f / lsum;
     const int j = r / G, hh = r - j * G;
     const int t = row0 + j, col = (g * G + hh) * D + d2;
-    const uint32_t pk = (uint32_t)f32_to_bf16(acc.x * inv) | ((uint32_t)f32_to_bf16(acc.y * inv) << 16);
-    *reinterpret_cast<uint32_t*>(X + frag_offset(t, col, Kdim)) = pk;
+    const float ox = acc.x * inv, oy = acc.y * inv;
+    const bf16_t hx = f32_to_bf16(ox), hy = f32_to_bf16(oy);
+    const bf16_t lx = f32_to_bf16(ox - bf16_to_f32(hx)), ly = f32_to_bf16(oy - bf16_to_f32(hy));
+    const size_t off = frag_offset(t, col, Kdim);
+    *reinterpret_cast<uint32_t*>(X + off) = (uint32_t)hx | ((uint32_t)hy << 16);
+    *reinterpret_cast<uint32_t*>(X + x_plane + off) = (uint32_t)lx | ((uint32_t)ly << 16);
 }
 
 // fp32 models: one wavefront per (packed row t, query head h); lanes stride over the keys
@@ -285,7 +322,8 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const
 size_t sled_attn_lds_bytes(int QT) { return (size_t)(QT * 8 * 64 * 4 + 2 * QT * 16) * sizeof(float); }
 
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
-                          float* part_o, float* part_ml, void* X_out, int QT, hipStream_t st) {
+                          size_t q_plane, float* part_o, float* part_ml, void* X_out, size_t x_plane, int QT,
+                          hipStream_t st) {
     const sled_shape& s = m->s;
     if (s.dtype == SLED_BF16) {
         const float scale_log2 = 1.4426950408889634f / sqrtf((float)s.head_dim);
@@ -293,7 +331,7 @@ int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_
         dim3 grid(meta.n_work), blk(256);
 #define SLED_ATTN_CASE(N)                                                                                          \
     case N:                                                                                                        \
-        hipLaunchKernelGGL(attn_partial_bf16<N>, grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q), \
+        hipLaunchKernelGGL(attn_partial_bf16<N>, grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q), q_plane, \
                            static_cast<const bf16_t*>(p->k_pool), static_cast<const bf16_t*>(p->v_pool), p->n_pages,   \
                            layer, s.n_q_heads, s.n_kv_heads, scale_log2, part_o, part_ml);                           \
         break;
@@ -309,7 +347,7 @@ int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_
 #undef SLED_ATTN_CASE
         SLED_LAUNCH_CHECK();
         hipLaunchKernelGGL(attn_combine_bf16, dim3(meta.B * s.n_kv_heads, QT * 16), dim3(64), 0, st, meta, QT * 16, s.n_q_heads,
-                           s.n_kv_heads, part_o, part_ml, static_cast<bf16_t*>(X_out));
+                           s.n_kv_heads, part_o, part_ml, static_cast<bf16_t*>(X_out), x_plane);
         SLED_LAUNCH_CHECK();
         return SLED_OK;
     }

@@ -22,13 +22,21 @@ __device__ inline float block_sum(float x, float* sh /*[16]*/) {
     return t;
 }
 
-// store 8 consecutive normalised activations of row t starting at column c0
+// store 8 consecutive activations of row t starting at column c0; bf16 models keep an activation
+// as a bf16 pair hi + lo in two planes of operand-ordered storage, `plane` elements apart
 template <bool BF16>
-__device__ inline void store_act8(void* X, int t, int c0, int K, const float* v) {
+__device__ inline void store_act8(void* X, size_t plane, int t, int c0, int K, const float* v) {
     if (BF16) {
-        uint32_t w[4];
-        for (int i = 0; i < 4; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
-        *reinterpret_cast<uint4*>(static_cast<bf16_t*>(X) + frag_offset(t, c0, K)) = make_uint4(w[0], w[1], w[2], w[3]);
+        uint32_t wh[4], wl[4];
+        for (int i = 0; i < 4; i++) {
+            const bf16_t h0 = f32_to_bf16(v[2 * i]), h1 = f32_to_bf16(v[2 * i + 1]);
+            const bf16_t l0 = f32_to_bf16(v[2 * i] - bf16_to_f32(h0)), l1 = f32_to_bf16(v[2 * i + 1] - bf16_to_f32(h1));
+            wh[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            wl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        bf16_t* p = static_cast<bf16_t*>(X) + frag_offset(t, c0, K);
+        *reinterpret_cast<uint4*>(p) = make_uint4(wh[0], wh[1], wh[2], wh[3]);
+        *reinterpret_cast<uint4*>(p + plane) = make_uint4(wl[0], wl[1], wl[2], wl[3]);
     } else {
         float* p = static_cast<float*>(X) + (size_t)t * K + c0;
         *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
@@ -40,7 +48,7 @@ __device__ inline void store_act8(void* X, int t, int c0, int K, const float* v)
 template <bool BF16>
 __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restrict__ tokens, const void* __restrict__ E,
                                                          int V, int d, float eps, const float* __restrict__ gain,
-                                                         float* __restrict__ h, void* __restrict__ X) {
+                                                         float* __restrict__ h, void* __restrict__ X, size_t plane) {
     __shared__ float sh[16];
     const int t = blockIdx.x;
     int tok = tokens[t];
@@ -69,7 +77,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restri
     for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
         float v[8];
         for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
-        store_act8<BF16>(X, t, c, d, v);
+        store_act8<BF16>(X, plane, t, c, d, v);
     }
 }
 
@@ -77,7 +85,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restri
 template <bool BF16>
 __global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __restrict__ partial, int n_split, int T_pad,
                                                             int d, float eps, const float* __restrict__ gain,
-                                                            float* __restrict__ h, void* __restrict__ X) {
+                                                            float* __restrict__ h, void* __restrict__ X, size_t plane) {
     __shared__ float sh[16];
     const int t = blockIdx.x;
     float ss = 0.f;
@@ -98,7 +106,7 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __rest
     for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
         float v[8];
         for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
-        store_act8<BF16>(X, t, c, d, v);
+        store_act8<BF16>(X, plane, t, c, d, v);
     }
 }
 
@@ -121,7 +129,7 @@ template <bool BF16>
 __global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev,
                                                             const float* __restrict__ partial, int n_split, int T_pad,
                                                             int Hq, int Hkv, int D, const float2* __restrict__ cs,
-                                                            void* __restrict__ Q, void* __restrict__ k_pool,
+                                                            void* __restrict__ Q, size_t q_plane, void* __restrict__ k_pool,
                                                             void* __restrict__ v_pool, int64_t n_pages, int layer) {
     const int t = blockIdx.x, head = blockIdx.y;
     const int b = meta.row_req[t];
@@ -144,10 +152,13 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta,
             const float y1 = x1 * sc.x - x2 * sc.y;
             const float y2 = x2 * sc.x + x1 * sc.y;
             if (head < Hq) {
-                if (BF16) {
+                if (BF16) {  // q is kept as a bf16 pair, like every activation that is not cached
                     bf16_t* q = static_cast<bf16_t*>(Q) + ((size_t)t * Hq + head) * D;
-                    q[i] = f32_to_bf16(y1);
-                    q[i + half] = f32_to_bf16(y2);
+                    const bf16_t h1 = f32_to_bf16(y1), h2 = f32_to_bf16(y2);
+                    q[i] = h1;
+                    q[i + half] = h2;
+                    q[q_plane + i] = f32_to_bf16(y1 - bf16_to_f32(h1));
+                    q[q_plane + i + half] = f32_to_bf16(y2 - bf16_to_f32(h2));
                 } else {
                     float* q = static_cast<float*>(Q) + ((size_t)t * Hq + head) * D;
                     q[i] = y1;
@@ -189,12 +200,32 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta,
     }
 }
 
-// fp32 models: a[t, f] = silu(gu[t, 2f]) * gu[t, 2f+1]
-__global__ void swiglu_f32_kernel(const float* __restrict__ gu, int T, int F, float* __restrict__ a) {
-    const size_t n = (size_t)T * F;
-    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
-        const float g = gu[2 * e], u = gu[2 * e + 1];
-        a[e] = g / (1.f + expf(-g)) * u;
+// a[t, f] = silu(g) * u with (g, u) = sum over K slices of gu[s][t][2f], gu[s][t][2f+1]; used when the
+// gate/up projection does not apply SwiGLU itself (fp32 models, or a gate/up projection split over K).
+// One workgroup per row, 8 outputs per thread.
+template <bool BF16>
+__global__ __launch_bounds__(256) void swiglu_reduce_kernel(const float* __restrict__ gu, int n_split, int T_pad, int F,
+                                                            void* __restrict__ A, size_t plane) {
+    const int t = blockIdx.x;
+    for (int f0 = (blockIdx.y * 256 + threadIdx.x) * 8; f0 < F; f0 += gridDim.y * 256 * 8) {
+        float acc[16];
+        for (int i = 0; i < 16; i++) acc[i] = 0.f;
+        for (int s = 0; s < n_split; s++) {
+            const float4* p = reinterpret_cast<const float4*>(gu + ((size_t)s * T_pad + t) * (2 * (size_t)F) + 2 * f0);
+            for (int q = 0; q < 4; q++) {
+                const float4 x = p[q];
+                acc[4 * q] += x.x;
+                acc[4 * q + 1] += x.y;
+                acc[4 * q + 2] += x.z;
+                acc[4 * q + 3] += x.w;
+            }
+        }
+        float v[8];
+        for (int i = 0; i < 8; i++) {
+            const float g = acc[2 * i], u = acc[2 * i + 1];
+            v[i] = g / (1.f + __expf(-g)) * u;
+        }
+        store_act8<BF16>(A, plane, t, f0, F, v);
     }
 }
 
@@ -292,28 +323,28 @@ int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStre
     return SLED_OK;
 }
 
-int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, const float* gain,
-                           hipStream_t st) {
+int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, size_t plane,
+                           const float* gain, hipStream_t st) {
     if (m->s.dtype == SLED_BF16)
         hipLaunchKernelGGL(embed_norm_kernel<true>, dim3(T), dim3(256), 0, st, tokens, m->embed, m->s.vocab, m->s.d_model,
-                           m->s.rms_eps, gain, h, X);
+                           m->s.rms_eps, gain, h, X, plane);
     else
         hipLaunchKernelGGL(embed_norm_kernel<false>, dim3(T), dim3(256), 0, st, tokens, m->embed, m->s.vocab, m->s.d_model,
-                           m->s.rms_eps, gain, h, X);
+                           m->s.rms_eps, gain, h, X, plane);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
 
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
-                              const float* gain, hipStream_t st) {
+                              size_t plane, const float* gain, hipStream_t st) {
     // one float4 per thread per pass: short rows get small workgroups
     const int bs = m->s.d_model >= 4096 ? 1024 : m->s.d_model >= 2048 ? 512 : 256;
     if (m->s.dtype == SLED_BF16)
         hipLaunchKernelGGL(residual_norm_kernel<true>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
-                           m->s.rms_eps, gain, h, X);
+                           m->s.rms_eps, gain, h, X, plane);
     else
         hipLaunchKernelGGL(residual_norm_kernel<false>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
-                           m->s.rms_eps, gain, h, X);
+                           m->s.rms_eps, gain, h, X, plane);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
@@ -327,25 +358,32 @@ int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled
 }
 
 int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
-                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, hipStream_t st) {
+                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, size_t q_plane,
+                               hipStream_t st) {
     const dim3 grid(meta.T, m->s.n_q_heads + 2 * m->s.n_kv_heads);
     if (m->s.dtype == SLED_BF16)
         hipLaunchKernelGGL(qkv_rope_store_kernel<true>, grid, dim3(64), 0, st, meta, p->len_dev, partial, n_split,
-                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q,
+                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q, q_plane,
                            p->k_pool, p->v_pool, p->n_pages, layer);
     else
         hipLaunchKernelGGL(qkv_rope_store_kernel<false>, grid, dim3(64), 0, st, meta, p->len_dev, partial, n_split,
-                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q,
+                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q, q_plane,
                            p->k_pool, p->v_pool, p->n_pages, layer);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
 
-int sled_launch_swiglu_f32(const float* gu, int T, int F, float* a, hipStream_t st) {
-    size_t n = (size_t)T * F;
-    int grid = (int)((n + 255) / 256);
-    if (grid > 4096) grid = 4096;
-    hipLaunchKernelGGL(swiglu_f32_kernel, dim3(grid), dim3(256), 0, st, gu, T, F, a);
+int sled_launch_swiglu_reduce(const sled_model* m, const float* gu, int n_split, int T, int T_pad, void* A, size_t plane,
+                              hipStream_t st) {
+    const int F = m->s.d_ffn;
+    int gy = (F / 8 + 255) / 256;
+    if (gy > 8) gy = 8;
+    if (gy < 1) gy = 1;
+    dim3 grid(T, gy);
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(swiglu_reduce_kernel<true>, grid, dim3(256), 0, st, gu, n_split, T_pad, F, A, plane);
+    else
+        hipLaunchKernelGGL(swiglu_reduce_kernel<false>, grid, dim3(256), 0, st, gu, n_split, T_pad, F, A, plane);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

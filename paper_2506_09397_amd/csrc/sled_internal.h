@@ -151,18 +151,21 @@ struct sled_step_meta {
 // ------------------------------------------------------------------------------------------
 // kernel launchers (defined in the .hip files); all return SLED_OK or an error code
 // ------------------------------------------------------------------------------------------
-// rowops.hip
+// rowops.hip.  `plane` arguments: distance in elements between the hi and lo planes of an activation
+// buffer of a bf16 model (unused for fp32 models).
 int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
                           hipStream_t st);
 int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStream_t st);
-int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, const float* gain,
-                           hipStream_t st);
+int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, size_t plane,
+                           const float* gain, hipStream_t st);
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
-                              const float* gain, hipStream_t st);
+                              size_t plane, const float* gain, hipStream_t st);
 int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs, hipStream_t st);
 int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
-                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, hipStream_t st);
-int sled_launch_swiglu_f32(const float* gu, int T, int F, float* a, hipStream_t st);
+                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, size_t q_plane,
+                               hipStream_t st);
+int sled_launch_swiglu_reduce(const sled_model* m, const float* gu, int n_split, int T, int T_pad, void* A, size_t plane,
+                              hipStream_t st);
 int sled_launch_kv_ingest(const sled_model* m, const sled_kvpool* p, const void* k_src, const void* v_src, int n_tokens,
                           int req_id, const int32_t* pages_dev, hipStream_t st);
 int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int32_t* add_dev, const int32_t* accept_dev,
@@ -170,13 +173,19 @@ int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int3
 
 // gemm.hip:  out = X[T, K] * W[N, K]^T
 enum { SLED_EPI_PARTIAL = 0, SLED_EPI_SWIGLU = 1, SLED_EPI_STORE = 2 };
-int sled_gemm_pick_split(const sled_model* m, int T, int N, int K);
-int sled_launch_gemm(const sled_model* m, const void* X, const void* W, int T, int T_pad, int N, int K, int epilogue,
-                     int split_k, float* out_f32, void* out_act, int F_act, hipStream_t st);
+struct sled_gemm_plan {
+    int nw;      // 16-column tiles per wavefront
+    int split;   // K slices
+};
+sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
+int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, int T, int T_pad, int N, int K,
+                     int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane, int F_act,
+                     hipStream_t st);
 
 // attention.hip
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
-                          float* part_o, float* part_ml, void* X_out, int QT, hipStream_t st);
+                          size_t q_plane, float* part_o, float* part_ml, void* X_out, size_t x_plane, int QT,
+                          hipStream_t st);
 
 // accept.hip
 size_t sled_accept_ws_bytes(int B, int T, int n_split);

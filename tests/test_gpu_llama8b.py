@@ -44,7 +44,7 @@ def test_llama8b_two_layers_all_logits():
     got = v.verify(reqs, batch.k, tokens).cpu().numpy()
     oreqs = oracle_requests(batch, [a for a, _ in KV], [b for _, b in KV])
     t0 = time.time()
-    want = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w, "bf16"), oreqs)], axis=0)
+    want = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w), oreqs)], axis=0)
     t1 = time.time()
     exact = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w, "exact"), oreqs)], axis=0)
     err, err_exact = np.abs(got - want).max(), np.abs(got - exact).max()
@@ -52,7 +52,8 @@ def test_llama8b_two_layers_all_logits():
     print(f"8B shape, 2 layers, T={batch.T}: max |logit error| {err:.3e} (median row {np.median(row_err):.1e}); "
           f"vs unrounded oracle {err_exact:.3e}; logit std {want.std():.3f}; oracle {t1 - t0:.1f} s")
     assert err < TOL_BF16
-    assert err_exact < TOL_BF16
+    # the unrounded oracle differs by the bf16 rounding of the new tokens' cached K/V alone
+    assert err_exact < 3 * TOL_BF16
     # greedy acceptance chained on the logits, where the oracle's top-2 gap is clear of the error
     a, t = v.accept(sled.GREEDY, batch.k, v.logits[: batch.T], tokens)
     acc = O.accept_batch("greedy", batch.k, want.astype(np.float32).astype(np.float64), batch.tokens)
@@ -80,7 +81,7 @@ def test_llama8b_full_depth_sampled_requests():
     oreqs = [{"tokens": batch.tokens[offs[i]: offs[i + 1]], "K": synth.as_f64(KV[i][0]), "V": synth.as_f64(KV[i][1])}
              for i in sample]
     t0 = time.time()
-    res = O.verify_batch(oracle_model(shape, w, "bf16", cache=False), oreqs)
+    res = O.verify_batch(oracle_model(shape, w, cache=False), oreqs)
     t1 = time.time()
     errs = []
     for i, r in zip(sample, res):

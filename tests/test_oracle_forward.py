@@ -193,8 +193,20 @@ def test_round_points_only_touch_storage_tensors():
     toks = synth.context_tokens(12, shape.vocab, seed=8)
     a = O.prefill(oracle_model(shape, w, "exact"), toks)["logits"]
     b = O.prefill(oracle_model(shape, w, "bf16"), toks)["logits"]
+    c = O.prefill(oracle_model(shape, w, "bf16x2"), toks)["logits"]
     err = np.abs(a - b).max() / np.abs(a).max()
+    err2 = np.abs(a - c).max() / np.abs(a).max()
     assert 1e-5 < err < 5e-2
+    assert 1e-7 < err2 < err          # pairs carry 16 bits; only the cached K/V are single bf16
+
+
+def test_bf16_pair_rounding():
+    x = np.array([1.0, 1.00390625, 3.14159265358979, -2.718281828, 1e-3, 123456.789])
+    y = O.bf16x2_round(x)
+    hi = O.bf16_round(x)
+    assert np.array_equal(y, hi + O.bf16_round(x - hi))
+    assert np.all(np.abs(y - x) <= np.abs(x) * 2.0 ** -16)
+    assert np.all(np.abs(hi - x) <= np.abs(x) * 2.0 ** -8)
 
 
 def test_rounded_softmax_numerators_are_reference_free():
