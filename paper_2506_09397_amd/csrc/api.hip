@@ -58,7 +58,8 @@ extern "C" int sled_model_create(const sled_shape* shape, sled_model** out) {
     const int G = s.n_q_heads / s.n_kv_heads;
     if (s.dtype == SLED_BF16) {
         if (s.head_dim != 128) SLED_FAIL(SLED_EINVAL, "bf16 models need head_dim 128");
-        if (s.d_model % 128 || s.d_ffn % 128) SLED_FAIL(SLED_EINVAL, "bf16 models need d_model and d_ffn multiples of 128");
+        if (s.d_model % 256 || s.d_ffn % 256 || (s.n_q_heads * s.head_dim) % 256)
+            SLED_FAIL(SLED_EINVAL, "bf16 models need d_model, d_ffn and n_q_heads*head_dim multiples of 256");
         if (s.vocab % 16) SLED_FAIL(SLED_EINVAL, "bf16 models need vocab a multiple of 16");
         if (G * (s.k_max + 1) > 80) SLED_FAIL(SLED_EINVAL, "(n_q_heads/n_kv_heads)*(k_max+1) must be <= 80");
     } else if (s.dtype == SLED_F32) {

@@ -11,8 +11,12 @@
 //     that way by the producing kernel): a single bf16 rounding of every activation costs more
 //     accuracy than the 2e-2 logit tolerance allows at 8B scale, while in this HBM-bound regime
 //     the MFMA pipes are mostly idle, so each weight tile is multiplied with both planes.
-//     They are small and shared by all wavefronts of a workgroup: staged through LDS, double
-//     buffered.
+//     They are small and shared by all wavefronts of a workgroup: a fifth "producer" wavefront
+//     streams them from L2 into a ring of three LDS buffers with direct-to-LDS loads, two stages
+//     ahead, while the four "consumer" wavefronts stream weights and do the arithmetic.  The split
+//     matters because vector-memory loads retire in order under one counter: a wavefront that
+//     issued both kinds could not wait for its activation loads without also draining its weight
+//     prefetch.
 //   - Each wavefront owns NW 16-column tiles of the output for all rows of its block (MT 16-row
 //     tiles): an activation tile read from LDS is reused for NW weight tiles.
 //   - Split-K over blockIdx.y gives every CU work on the narrow projections; partial sums go to a
@@ -29,24 +33,62 @@
 
 namespace {
 
-constexpr int KC = 2;      // k-steps (of 32) per pipeline stage
 constexpr int PLANES = 2;  // activation planes: hi, lo
+constexpr int NXB = 3;     // LDS ring: the stage being read, the next one (landed), the one after (in flight)
+constexpr int NBUF = 4;    // weight register buffers: the stage in use + 3 stages in flight
 
-template <int MT, int NW, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
+// s_waitcnt vmcnt(n) alone: expcnt and lgkmcnt fields at their no-wait values
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
+template <int MT, int NW, int KC, int EPI>
+__global__ __launch_bounds__(320) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
                                                         const bf16_t* __restrict__ Wp, int NT, int KS, int ks_per_split,
                                                         int T, int T_pad, int N, float* __restrict__ out,
                                                         bf16_t* __restrict__ out_act, size_t act_plane, int F_act) {
-    constexpr int NBUF = NW >= 4 ? 3 : 4;  // weight register buffers: the stage in use + the stages in flight
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* xs = reinterpret_cast<bf16_t*>(smem);  // [2][PLANES][MT][KC][512]
+    bf16_t* xs = reinterpret_cast<bf16_t*>(smem);  // [NXB][PLANES][MT][KC][512]
+    constexpr int STAGE_TILES = PLANES * MT * KC;  // 1 KiB operand tiles per stage
+    constexpr int STAGE_ELEMS = STAGE_TILES * 512;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int nt0 = (blockIdx.x * 4 + wv) * NW;
     const int ks_begin = blockIdx.y * ks_per_split;
-    const int ks_end = min(KS, ks_begin + ks_per_split);
-    const int n_stage = (ks_end - ks_begin) / KC;
-    const int mt_base = blockIdx.z * MT;  // first 16-row tile handled by this block
+    const int n_stage = ks_per_split / KC;  // a positive multiple of NBUF (the host picks K slices accordingly)
+    const int mt_base = blockIdx.z * MT;    // first 16-row tile handled by this block
 
+    if (wv == 4) {
+        // ---- producer wavefront: activations L2 -> LDS, two stages ahead of the consumers -------
+        // One direct-to-LDS load moves a whole operand tile: lane l's 16 bytes land at base + 16*l.
+        auto dma = [&](int buf, int stage) {
+#pragma unroll
+            for (int i = 0; i < STAGE_TILES; i++) {
+                const int pl = i / (MT * KC), rem = i - pl * (MT * KC);
+                const int b = rem / KC, c = rem - b * KC;
+                const bf16_t* g = Xp + pl * x_plane + ((size_t)(mt_base + b) * KS + ks_begin + stage * KC + c) * 512 + lane * 8;
+                bf16_t* l = xs + (size_t)buf * STAGE_ELEMS + (size_t)i * 512;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                                 (__attribute__((address_space(3))) void*)l, 16, 0, 0);
+            }
+        };
+        dma(0, 0);
+        dma(1, 1);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(STAGE_TILES));  // stage 0 has landed, stage 1 may be in flight
+        __builtin_amdgcn_s_barrier();
+        int buf = 2;
+        for (int s = 0; s < n_stage; s++) {
+            // buffer `buf` held stage s-1: its readers passed the previous barrier
+            if (s + 2 < n_stage) {
+                dma(buf, s + 2);
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(STAGE_TILES));  // loads retire in order: stage s+1 has landed
+            } else {
+                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            }
+            __builtin_amdgcn_s_barrier();  // publishes stage s+1, and says stage s has been consumed
+            buf = buf == NXB - 1 ? 0 : buf + 1;
+        }
+        return;
+    }
+
+    // ---- consumer wavefronts: weights HBM -> registers, MFMA ---------------------------------------
+    const int nt0 = (blockIdx.x * 4 + wv) * NW;
     float4_t acc[NW][MT];
 #pragma unroll
     for (int a = 0; a < NW; a++)
@@ -60,14 +102,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         nt_ok[a] = (nt0 + a) < NT;
         wbase[a] = Wp + ((size_t)(nt_ok[a] ? nt0 + a : 0) * KS + ks_begin) * 512 + lane * 8;
     }
-
-    // One stage of activations is PLANES*MT*KC KiB = PLANES*MT*KC*64 16-byte pieces over 256 threads.
-    constexpr int STAGE_PIECES = PLANES * MT * KC * 64;
-    constexpr int XPIECES = (STAGE_PIECES + 255) / 256;
-    constexpr int STAGE_ELEMS = PLANES * MT * KC * 512;
     bf16x8_t wreg[NBUF][NW][KC];
-    uint4 xreg[XPIECES];
-
     auto load_w = [&](int buf, int stage) {
 #pragma unroll
         for (int a = 0; a < NW; a++)
@@ -75,34 +110,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
             for (int c = 0; c < KC; c++)
                 wreg[buf][a][c] = *reinterpret_cast<const bf16x8_t*>(wbase[a] + (size_t)(stage * KC + c) * 512);
     };
-    // piece e of a stage: plane e / (MT*KC*64), row tile, then KC*512 contiguous elements of that
-    // tile's k range; LDS keeps the same order
-    auto load_x = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < XPIECES; i++) {
-            const int e = i * 256 + tid;
-            if (STAGE_PIECES % 256 == 0 || e < STAGE_PIECES) {
-                const int pl = e / (MT * KC * 64), rem = e - pl * (MT * KC * 64);
-                const int b = rem / (KC * 64), r = rem - b * (KC * 64);
-                xreg[i] = *reinterpret_cast<const uint4*>(Xp + pl * x_plane +
-                                                          ((size_t)(mt_base + b) * KS + ks_begin + stage * KC) * 512 + r * 8);
-            }
-        }
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < XPIECES; i++) {
-            const int e = i * 256 + tid;
-            if (STAGE_PIECES % 256 == 0 || e < STAGE_PIECES)
-                *reinterpret_cast<uint4*>(xs + (size_t)buf * STAGE_ELEMS + (size_t)e * 8) = xreg[i];
-        }
-    };
-    auto compute = [&](int xbuf, int wbuf) {
+    auto compute = [&](const bf16_t* xb, int wbuf) {
 #pragma unroll
         for (int c = 0; c < KC; c++) {
 #pragma unroll
             for (int b = 0; b < MT; b++) {
-                const bf16_t* xp = xs + (size_t)xbuf * STAGE_ELEMS + ((size_t)(b * KC + c)) * 512 + lane * 8;
+                const bf16_t* xp = xb + ((size_t)(b * KC + c)) * 512 + lane * 8;
                 const bf16x8_t xhi = *reinterpret_cast<const bf16x8_t*>(xp);
                 const bf16x8_t xlo = *reinterpret_cast<const bf16x8_t*>(xp + MT * KC * 512);
 #pragma unroll
@@ -114,31 +127,36 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         }
     };
 
-    if (n_stage > 0) {
-        // prologue: activations of stage 0 first (they are waited for first), then NBUF-1 weight stages
-        load_x(0);
 #pragma unroll
-        for (int u = 0; u < NBUF - 1; u++)
-            if (u < n_stage) load_w(u, u);
-        store_x(0);
-        __syncthreads();
-        constexpr int UNROLL = (NBUF % 2) ? 2 * NBUF : NBUF;  // LDS parity and register buffer both compile-time
-        for (int s0 = 0; s0 < n_stage; s0 += UNROLL) {
+    for (int u = 0; u < NBUF - 1; u++) load_w(u, u);
+    __builtin_amdgcn_s_barrier();  // stage 0 of the activations is in LDS
+    int xbuf = 0;
+    // NBUF stages per trip so that the weight register buffer is a compile-time index.  The only
+    // vector-memory operations of these wavefronts are the weight loads, so the compiler's own wait
+    // before a stage's arithmetic leaves the three later stages in flight.
+    // All trips but the last prefetch unconditionally; the last one has nothing left to fetch after
+    // its first stage.  Keeping run-time conditions out of the trips matters: the compiler sizes
+    // each wait for the path with the fewest loads outstanding.
+    int s0 = 0;
+    for (; s0 + NBUF < n_stage; s0 += NBUF) {
 #pragma unroll
-            for (int u = 0; u < UNROLL; u++) {
-                const int s = s0 + u;
-                if (s < n_stage) {
-                    // Loads are issued oldest-needed first: the activation loads of the next stage are
-                    // waited for at the end of this stage, the weight loads NBUF-1 stages later, so the
-                    // wait on the former leaves the latter in flight.
-                    if (s + 1 < n_stage) load_x(s + 1);
-                    if (s + NBUF - 1 < n_stage) load_w((u + NBUF - 1) % NBUF, s + NBUF - 1);
-                    compute(u & 1, u % NBUF);
-                    if (s + 1 < n_stage) store_x((u + 1) & 1);
-                    __syncthreads();
-                }
-            }
+        for (int u = 0; u < NBUF; u++) {
+            load_w((u + NBUF - 1) % NBUF, s0 + u + NBUF - 1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(xs + (size_t)xbuf * STAGE_ELEMS, u);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            xbuf = xbuf == NXB - 1 ? 0 : xbuf + 1;
         }
+    }
+#pragma unroll
+    for (int u = 0; u < NBUF; u++) {
+        if (u == 0) load_w(NBUF - 1, s0 + NBUF - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(xs + (size_t)xbuf * STAGE_ELEMS, u);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        xbuf = xbuf == NXB - 1 ? 0 : xbuf + 1;
     }
 
     // epilogue: lane holds rows (tokens) mt*16 + lane%16, columns nt*16 + (lane/16)*4 + 0..3
@@ -209,42 +227,64 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
         }
 }
 
-template <int MT, int NW>
-int launch_bf16(int epi, dim3 grid, size_t lds, hipStream_t st, const bf16_t* X, size_t x_plane, const bf16_t* W, int NT,
-                int KS, int kps, int T, int T_pad, int N, float* out, bf16_t* out_act, size_t act_plane, int F_act) {
-    switch (epi) {
-        case SLED_EPI_PARTIAL:
-            hipLaunchKernelGGL((gemm_bf16_kernel<MT, NW, SLED_EPI_PARTIAL>), grid, dim3(256), lds, st, X, x_plane, W, NT, KS,
-                               kps, T, T_pad, N, out, out_act, act_plane, F_act);
-            break;
-        case SLED_EPI_SWIGLU:
-            hipLaunchKernelGGL((gemm_bf16_kernel<MT, NW, SLED_EPI_SWIGLU>), grid, dim3(256), lds, st, X, x_plane, W, NT, KS,
-                               kps, T, T_pad, N, out, out_act, act_plane, F_act);
-            break;
-        default:
-            hipLaunchKernelGGL((gemm_bf16_kernel<MT, NW, SLED_EPI_STORE>), grid, dim3(256), lds, st, X, x_plane, W, NT, KS,
-                               kps, T, T_pad, N, out, out_act, act_plane, F_act);
-            break;
+struct gemm_args {
+    dim3 grid;
+    size_t lds;
+    hipStream_t st;
+    const bf16_t* X;
+    size_t x_plane;
+    const bf16_t* W;
+    int NT, KS, kps, T, T_pad, N;
+    float* out;
+    bf16_t* out_act;
+    size_t act_plane;
+    int F_act;
+};
+
+template <int MT, int NW, int KC, int EPI>
+int launch_one(const gemm_args& a) {
+    // more than 64 KiB of dynamic LDS has to be allowed once per kernel
+    static bool allowed = false;
+    auto kern = gemm_bf16_kernel<MT, NW, KC, EPI>;
+    if (!allowed) {
+        SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        allowed = true;
     }
+    hipLaunchKernelGGL(kern, a.grid, dim3(320), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.T, a.T_pad, a.N,
+                       a.out, a.out_act, a.act_plane, a.F_act);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
 
-template <int MT>
-int launch_bf16_nw(int nw, int epi, dim3 grid, size_t lds, hipStream_t st, const bf16_t* X, size_t x_plane, const bf16_t* W,
-                   int NT, int KS, int kps, int T, int T_pad, int N, float* out, bf16_t* out_act, size_t act_plane,
-                   int F_act) {
-    switch (nw) {
-        case 1: return launch_bf16<MT, 1>(epi, grid, lds, st, X, x_plane, W, NT, KS, kps, T, T_pad, N, out, out_act, act_plane, F_act);
-        case 2: return launch_bf16<MT, 2>(epi, grid, lds, st, X, x_plane, W, NT, KS, kps, T, T_pad, N, out, out_act, act_plane, F_act);
-        default: return launch_bf16<MT, 4>(epi, grid, lds, st, X, x_plane, W, NT, KS, kps, T, T_pad, N, out, out_act, act_plane, F_act);
+template <int MT, int NW, int KC>
+int launch_epi(int epi, const gemm_args& a) {
+    switch (epi) {
+        case SLED_EPI_PARTIAL: return launch_one<MT, NW, KC, SLED_EPI_PARTIAL>(a);
+        case SLED_EPI_SWIGLU: return launch_one<MT, NW, KC, SLED_EPI_SWIGLU>(a);
+        default: return launch_one<MT, NW, KC, SLED_EPI_STORE>(a);
     }
 }
 
-// tuning aid: SLED_GEMM_TUNE="N:K:nw:split;N:K:nw:split;..." overrides the plan of the projections
-// with those N and K (read once)
+template <int MT>
+int launch_cfg(int nw, int kc, int epi, const gemm_args& a) {
+    if (kc == 1) {
+        switch (nw) {
+            case 1: return launch_epi<MT, 1, 1>(epi, a);
+            case 2: return launch_epi<MT, 2, 1>(epi, a);
+            default: return launch_epi<MT, 4, 1>(epi, a);
+        }
+    }
+    switch (nw) {
+        case 1: return launch_epi<MT, 1, 2>(epi, a);
+        case 2: return launch_epi<MT, 2, 2>(epi, a);
+        default: return launch_epi<MT, 4, 2>(epi, a);
+    }
+}
+
+// tuning aid: SLED_GEMM_TUNE="N:K:nw:kc:split;..." overrides the plan of the projections with those
+// N and K (read once)
 struct tune_entry {
-    int N, K, nw, split;
+    int N, K, nw, kc, split;
 };
 const std::vector<tune_entry>& tune_table() {
     static std::vector<tune_entry> t = [] {
@@ -256,8 +296,9 @@ const std::vector<tune_entry>& tune_table() {
         while (pos < s.size()) {
             size_t end = s.find(';', pos);
             if (end == std::string::npos) end = s.size();
-            tune_entry te{0, 0, 0, 0};
-            if (sscanf(s.substr(pos, end - pos).c_str(), "%d:%d:%d:%d", &te.N, &te.K, &te.nw, &te.split) == 4) v.push_back(te);
+            tune_entry te{0, 0, 0, 0, 0};
+            if (sscanf(s.substr(pos, end - pos).c_str(), "%d:%d:%d:%d:%d", &te.N, &te.K, &te.nw, &te.kc, &te.split) == 5)
+                v.push_back(te);
             pos = end + 1;
         }
         return v;
@@ -267,23 +308,24 @@ const std::vector<tune_entry>& tune_table() {
 
 }  // namespace
 
-// Shape of the launch for a projection of N columns over K: NW 16-column tiles per wavefront and the
-// number of K slices.  More tiles per wavefront mean fewer LDS reads per weight byte; more slices
-// mean more workgroups (the chip wants at least one per CU) but more partial sums to reduce.
+// Shape of the launch for a projection of N columns over K: NW 16-column tiles per wavefront, KC
+// k-steps per pipeline stage and the number of K slices.  More tiles per wavefront mean fewer LDS
+// reads per weight byte; more slices mean more workgroups (the chip wants at least one per CU) but
+// more partial sums to reduce.  Each slice must hold a multiple of 4 stages.
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k) {
-    sled_gemm_plan p{1, 1};
+    sled_gemm_plan p{1, 1, 1};
     if (m->s.dtype != SLED_BF16) return p;
-    const int NT = N / 16, stages = K / (32 * KC);
-    auto legal_split = [&](int sp) { return sp >= 1 && stages % sp == 0 && (stages / sp) >= 4; };
+    const int NT = N / 16;
+    auto legal = [&](int kc, int sp) { return sp >= 1 && (K / 32) % (sp * kc * NBUF) == 0; };
     for (const auto& te : tune_table())
-        if (te.N == N && te.K == K && (te.nw == 1 || te.nw == 2 || te.nw == 4) && legal_split(te.split) &&
-            (!needs_full_k || te.split == 1))
-            return sled_gemm_plan{te.nw, te.split};
-    // default: two tiles per wavefront (128 columns per workgroup); split K until the chip is covered
+        if (te.N == N && te.K == K && (te.nw == 1 || te.nw == 2 || te.nw == 4) && (te.kc == 1 || te.kc == 2) &&
+            legal(te.kc, te.split) && (!needs_full_k || te.split == 1))
+            return sled_gemm_plan{te.nw, te.kc, te.split};
     p.nw = NT >= 4096 ? 4 : 2;
+    p.kc = 1;
     const int n_wg = (NT + 4 * p.nw - 1) / (4 * p.nw);
     if (!needs_full_k)
-        while (n_wg * p.split < 256 && legal_split(p.split * 2)) p.split *= 2;
+        while (n_wg * p.split < 256 && legal(p.kc, p.split * 2)) p.split *= 2;
     return p;
 }
 
@@ -291,35 +333,40 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
                      int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane, int F_act,
                      hipStream_t st) {
     if (m->s.dtype == SLED_BF16) {
-        if (N % 16 || K % (32 * KC) || T_pad % 16) SLED_FAIL(SLED_EINVAL, "gemm: unsupported shape N=%d K=%d T_pad=%d", N, K, T_pad);
-        const int NT = N / 16, KS = K / 32, split_k = plan.split;
-        if (KS % split_k || (KS / split_k) % KC) SLED_FAIL(SLED_EINVAL, "gemm: bad split %d for K=%d", split_k, K);
-        const int kps = KS / split_k;
+        const int NT = N / 16, KS = K / 32;
+        if (N % 16 || K % 32 || T_pad % 16 || KS % (plan.split * plan.kc * NBUF))
+            SLED_FAIL(SLED_EINVAL, "gemm: unsupported shape N=%d K=%d T_pad=%d split=%d kc=%d", N, K, T_pad, plan.split, plan.kc);
         const int mt_total = T_pad / 16;
         // rows are processed in blocks of at most 8 tiles (128 rows), evenly sized
         const int zb = (mt_total + 7) / 8;
         const int MT = (mt_total + zb - 1) / zb;
-        const int zblocks = (mt_total + MT - 1) / MT;
-        dim3 grid((NT + 4 * plan.nw - 1) / (4 * plan.nw), split_k, zblocks);
-        const size_t lds = (size_t)2 * PLANES * MT * KC * 512 * sizeof(bf16_t);
-        const bf16_t* Xb = static_cast<const bf16_t*>(X);
-        const bf16_t* Wb = static_cast<const bf16_t*>(W);
-        bf16_t* oa = static_cast<bf16_t*>(out_act);
-#define SLED_GEMM_CASE(M_) \
-    case M_:               \
-        return launch_bf16_nw<M_>(plan.nw, epilogue, grid, lds, st, Xb, x_plane, Wb, NT, KS, kps, T, T_pad, N, out_f32, oa, act_plane, F_act);
+        gemm_args a;
+        a.grid = dim3((NT + 4 * plan.nw - 1) / (4 * plan.nw), plan.split, (mt_total + MT - 1) / MT);
+        a.lds = (size_t)NXB * PLANES * MT * plan.kc * 512 * sizeof(bf16_t);
+        a.st = st;
+        a.X = static_cast<const bf16_t*>(X);
+        a.x_plane = x_plane;
+        a.W = static_cast<const bf16_t*>(W);
+        a.NT = NT;
+        a.KS = KS;
+        a.kps = KS / plan.split;
+        a.T = T;
+        a.T_pad = T_pad;
+        a.N = N;
+        a.out = out_f32;
+        a.out_act = static_cast<bf16_t*>(out_act);
+        a.act_plane = act_plane;
+        a.F_act = F_act;
         switch (MT) {
-            SLED_GEMM_CASE(1)
-            SLED_GEMM_CASE(2)
-            SLED_GEMM_CASE(3)
-            SLED_GEMM_CASE(4)
-            SLED_GEMM_CASE(5)
-            SLED_GEMM_CASE(6)
-            SLED_GEMM_CASE(7)
-            default:
-                SLED_GEMM_CASE(8)
+            case 1: return launch_cfg<1>(plan.nw, plan.kc, epilogue, a);
+            case 2: return launch_cfg<2>(plan.nw, plan.kc, epilogue, a);
+            case 3: return launch_cfg<3>(plan.nw, plan.kc, epilogue, a);
+            case 4: return launch_cfg<4>(plan.nw, plan.kc, epilogue, a);
+            case 5: return launch_cfg<5>(plan.nw, plan.kc, epilogue, a);
+            case 6: return launch_cfg<6>(plan.nw, plan.kc, epilogue, a);
+            case 7: return launch_cfg<7>(plan.nw, plan.kc, epilogue, a);
+            default: return launch_cfg<8>(plan.nw, plan.kc, epilogue, a);
         }
-#undef SLED_GEMM_CASE
     }
     // fp32: no split, plain store (partial buffer with one slice has the same layout)
     dim3 grid((N + 63) / 64, (T + 15) / 16);

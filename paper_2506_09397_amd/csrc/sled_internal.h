@@ -175,6 +175,7 @@ int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int3
 enum { SLED_EPI_PARTIAL = 0, SLED_EPI_SWIGLU = 1, SLED_EPI_STORE = 2 };
 struct sled_gemm_plan {
     int nw;      // 16-column tiles per wavefront
+    int kc;      // k-steps of 32 per pipeline stage
     int split;   // K slices
 };
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
