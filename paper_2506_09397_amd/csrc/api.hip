@@ -124,17 +124,17 @@ extern "C" int sled_model_load(sled_model* m, int tensor_id, int layer, const vo
         case SLED_T_EMBED:
             SLED_HIP(hipMemcpyAsync(m->embed, src, (size_t)s.vocab * d * m->elem, hipMemcpyDeviceToDevice, st));
             return SLED_OK;
-        case SLED_T_WQ: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, HD, d, 0, 1, st);
-        case SLED_T_WK: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, KD, d, HD, 1, st);
-        case SLED_T_WV: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, KD, d, HD + KD, 1, st);
-        case SLED_T_WO: return sled_launch_pack_rows(s.dtype, src, w->w_o, d, HD, 0, 1, st);
-        case SLED_T_WGATE: return sled_launch_pack_rows(s.dtype, src, w->w_gu, F, d, 0, 2, st);
-        case SLED_T_WUP: return sled_launch_pack_rows(s.dtype, src, w->w_gu, F, d, 1, 2, st);
-        case SLED_T_WDOWN: return sled_launch_pack_rows(s.dtype, src, w->w_down, d, F, 0, 1, st);
+        case SLED_T_WQ: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, HD, d, 0, 1, m->n_qkv, st);
+        case SLED_T_WK: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, KD, d, HD, 1, m->n_qkv, st);
+        case SLED_T_WV: return sled_launch_pack_rows(s.dtype, src, w->w_qkv, KD, d, HD + KD, 1, m->n_qkv, st);
+        case SLED_T_WO: return sled_launch_pack_rows(s.dtype, src, w->w_o, d, HD, 0, 1, d, st);
+        case SLED_T_WGATE: return sled_launch_pack_rows(s.dtype, src, w->w_gu, F, d, 0, 2, 2 * F, st);
+        case SLED_T_WUP: return sled_launch_pack_rows(s.dtype, src, w->w_gu, F, d, 1, 2, 2 * F, st);
+        case SLED_T_WDOWN: return sled_launch_pack_rows(s.dtype, src, w->w_down, d, F, 0, 1, d, st);
         case SLED_T_G_ATTN: return sled_launch_copy_gain(s.dtype, src, w->g_attn, d, st);
         case SLED_T_G_MLP: return sled_launch_copy_gain(s.dtype, src, w->g_mlp, d, st);
         case SLED_T_G_FINAL: return sled_launch_copy_gain(s.dtype, src, m->g_final, d, st);
-        case SLED_T_LM_HEAD: return sled_launch_pack_rows(s.dtype, src, m->lm_head, s.vocab, d, 0, 1, st);
+        case SLED_T_LM_HEAD: return sled_launch_pack_rows(s.dtype, src, m->lm_head, s.vocab, d, 0, 1, s.vocab, st);
         default: SLED_FAIL(SLED_EINVAL, "sled_model_load: unknown tensor id %d", tensor_id);
     }
 }
@@ -432,15 +432,30 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
 namespace {
 
 struct ws_plan {
-    size_t h, xa, xo, xf, q, partial, cs, part_o, part_ml, total, T_alloc;
+    size_t h, xa, xo, xf, q, partial, cs, part_o, part_ml, arrive, total, T_alloc;
 };
 
-int attn_chunk_pages(int64_t total_page_heads) {
-    // aim at about 1024 work items over the chip, never fewer than 4 pages per item
-    int64_t c = (total_page_heads + 1023) / 1024;
-    if (c < 4) c = 4;
-    c = (c + 3) / 4 * 4;  // four wavefronts share an item's pages
-    return (int)c;
+// Attention work list.  A work item is a run of pages of one (request, kv head), processed by one
+// workgroup; the chip wants about one item per CU (a multiple of 256 when there are more (request,
+// kv head) pairs than that), all of similar size.  Returns the largest number of pages an item may
+// hold so that the item count stays within that cap; each pair then splits its pages evenly.
+constexpr int ATTN_CUS = 256;
+int attn_item_cap(int B, int Hkv) { return ATTN_CUS * ((B * Hkv + ATTN_CUS - 1) / ATTN_CUS); }
+int attn_pages_per_item(const std::vector<int>& np, int Hkv) {
+    int64_t total = 0;
+    int longest = 1;
+    for (int n : np) {
+        total += n;
+        longest = std::max(longest, n);
+    }
+    const int cap = attn_item_cap((int)np.size(), Hkv);
+    int tgt = (int)std::max<int64_t>(8, (total * Hkv + cap - 1) / cap);
+    for (; tgt < longest; tgt++) {
+        int64_t items = 0;
+        for (int n : np) items += (int64_t)Hkv * ceil_div(n, tgt);
+        if (items <= cap) break;
+    }
+    return tgt;
 }
 
 ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
@@ -470,15 +485,15 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     w.cs = take((size_t)T * s.head_dim * sizeof(float));
     w.part_o = take((size_t)n_work * QT * 16 * 128 * sizeof(float));
     w.part_ml = take((size_t)n_work * 2 * QT * 16 * sizeof(float));
+    w.arrive = take((size_t)(n_work + 1) * sizeof(int32_t));  // one counter per (request, kv head): at most n_work
     w.total = off;
     return w;
 }
 
-// upper bound of the attention work list: every (request, kv head) rounds its page count up to a
-// whole chunk, and attn_chunk_pages keeps total_page_heads / chunk <= 1024
+// upper bound of the attention work list
 int max_work_items(const sled_model* m, int B, int64_t ctx_tokens) {
-    const int64_t page_heads = (ctx_tokens / 16 + 2 * (int64_t)B) * m->s.n_kv_heads;
-    return (int)std::min<int64_t>(page_heads, 1024 + 4) + B * m->s.n_kv_heads;
+    (void)ctx_tokens;
+    return attn_item_cap(B, m->s.n_kv_heads) + B * m->s.n_kv_heads;
 }
 
 }  // namespace
@@ -518,11 +533,14 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
         if ((rc = ensure_pages(p, req_ids[i], rq.len_ub + k[i] + 1)) != SLED_OK) return rc;
         total_pages += ceil_div(rq.len_ub + k[i] + 1, 16);
     }
-    const int chunk = attn_chunk_pages(total_pages * Hkv);
+    std::vector<int> np_all(B);
+    for (int i = 0; i < B; i++) np_all[i] = ceil_div(p->reqs[req_ids[i]].len_ub + k[i] + 1, 16);
+    const int tgt = attn_pages_per_item(np_all, Hkv);
     std::vector<int32_t> work;
     std::vector<int32_t> cu_work(B * Hkv + 1);
     for (int i = 0; i < B; i++) {
-        const int np = ceil_div(p->reqs[req_ids[i]].len_ub + k[i] + 1, 16);
+        const int np = np_all[i];
+        const int chunk = ceil_div(np, ceil_div(np, tgt));  // even split of this request's pages
         for (int g = 0; g < Hkv; g++) {
             cu_work[i * Hkv + g] = (int)(work.size() / 4);
             for (int p0 = 0; p0 < np; p0 += chunk) {
@@ -591,6 +609,7 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     float* cs = reinterpret_cast<float*>(ws + wp.cs);
     float* part_o = reinterpret_cast<float*>(ws + wp.part_o);
     float* part_ml = reinterpret_cast<float*>(ws + wp.part_ml);
+    int32_t* arrive = reinterpret_cast<int32_t*>(ws + wp.arrive);
     const int T_pad = (int)align_up(T, 16);
     const int d = s.d_model, F = s.d_ffn, HD = s.n_q_heads * s.head_dim;
     const bool bf = s.dtype == SLED_BF16;
@@ -615,13 +634,15 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
         SLED_TRY(x);                       \
     } while (0)
 
+    // arrival counters of the attention work items start at zero (each layer leaves them at zero)
+    SLED_RUN(SLED_PROF_ROWS, sled_launch_fill_i32(arrive, 0, (size_t)B * Hkv, st));
     SLED_RUN(SLED_PROF_ROWS, sled_launch_rope_table(m, p, meta, cs, st));
     SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, pl_d, m->layers[0].g_attn, st));
     for (int l = 0; l < s.n_layers; l++) {
         const sled_layer_weights& w = m->layers[l];
         SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, g_qkv, partial, nullptr, 0, 0, st));
         SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, meta, l, partial, g_qkv.split, T_pad, cs, qb, pl_hd, st));
-        SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, part_o, part_ml, xo, pl_hd, QT, st));
+        SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, part_o, part_ml, arrive, xo, pl_hd, QT, st));
         SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, pl_hd, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, g_o, partial, nullptr, 0, 0, st));
         SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_o.split, T, T_pad, h, xa, pl_d, w.g_mlp, st));
         if (gu_fused) {

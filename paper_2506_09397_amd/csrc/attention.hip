@@ -19,9 +19,10 @@
 // A page (16 tokens x 128 dims of one kv head) is stored in the pool in operand order, K for the
 // first product and V for the second, so a wavefront reads a whole page with 4 + 4 contiguous
 // 1 KiB loads into registers, the next page in flight while one is consumed.  The four wavefronts of a
-// workgroup take alternate pages and merge their (max, sum, O) states through LDS at the end; a
-// second kernel merges the work items of one (request, kv head) in a fixed order and writes the
-// attention output in the operand order of the following projection.
+// workgroup take alternate pages and merge their (max, sum, O) states through LDS at the end.  When a
+// (request, kv head) is split over several work items, each stores its state and the last one to
+// arrive (a device-scope counter) merges them in a fixed order; either way the output is written in
+// the operand order of the following projection, as a bf16 pair.
 //
 // fp32 kernel (fp32 models): one wavefront per (row, query head), lanes over keys.
 #include "sled_internal.h"
@@ -30,21 +31,25 @@ namespace {
 
 constexpr float NEG_BIG = -1.0e30f;
 
+constexpr int ATTN_WAVES = 4;  // wavefronts per workgroup: one per SIMD, each with the whole register file
+
+// LDS merge slots: floats per slot = O tile + max + sum
+__host__ __device__ constexpr int attn_slot_floats(int QT) { return QT * 8 * 64 * 4 + 2 * QT * 16; }
+__host__ __device__ constexpr int attn_slots(int QT) { return QT <= 5 ? 2 : 1; }
+
 template <int QT>
-__global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, const int32_t* __restrict__ len_dev,
-                                                         const bf16_t* __restrict__ Q, size_t q_plane,
-                                                         const bf16_t* __restrict__ k_pool,
-                                                         const bf16_t* __restrict__ v_pool, int64_t n_pages, int layer,
-                                                         int Hq, int Hkv, float scale_log2,
-                                                         float* __restrict__ part_o, float* __restrict__ part_ml) {
+__global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bf16_kernel(
+    sled_step_meta meta, const int32_t* __restrict__ len_dev, const bf16_t* __restrict__ Q, size_t q_plane,
+    const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int64_t n_pages, int layer, int Hq, int Hkv,
+    float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml, int32_t* __restrict__ arrive,
+    bf16_t* __restrict__ X, size_t x_plane) {
     constexpr int D = 128;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // main loop: Q operand tiles [2 planes][QT][4 k-steps][64 lanes][8]; afterwards the same bytes
-    // serve as the merge buffer [QT][8][64][4] floats
+    // main loop: Q operand tiles [2 planes][QT][4 k-steps][64 lanes][8] (the size of one O tile);
+    // afterwards the same bytes serve as merge slots
     bf16_t* sh_q = reinterpret_cast<bf16_t*>(smem);
-    float* sh_o = reinterpret_cast<float*>(smem);
-    float* sh_m = sh_o + QT * 8 * 64 * 4;  // [QT*16]
-    float* sh_l = sh_m + QT * 16;          // [QT*16]
+    float* sh_f = reinterpret_cast<float*>(smem);
+    __shared__ int sh_last;
 
     const int w = blockIdx.x;
     const int b = meta.work[4 * w + 0], g = meta.work[4 * w + 1];
@@ -62,7 +67,7 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
 
     // Q operand tiles, both planes of the bf16 pair: qrow r = qt*16 + l%16 -> (query position
     // j = r / G, head g*G + r % G); element k = ks*32 + (l/16)*8 ..+8
-    for (int e = tid; e < 2 * QT * 4 * 64; e += 256) {
+    for (int e = tid; e < 2 * QT * 4 * 64; e += 64 * ATTN_WAVES) {
         const int l = e & 63, ks = (e >> 6) & 3, qt = (e >> 8) % QT, pl = e / (QT * 256);
         const int r = qt * 16 + (l & 15);
         uint4 val = make_uint4(0u, 0u, 0u, 0u);
@@ -160,19 +165,17 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
         }
     };
 
-    // the wavefront's pages, two register sets: the next page is in flight while one is consumed
+    // the wavefront's pages, three register sets: two pages are in flight while one is consumed
     {
-        page_regs A, B;
+        page_regs cur, nxt, nxt2;
         int pg = page0 + wv;
-        if (pg < page_end) load_page(A, pg);
-        while (pg < page_end) {
-            if (pg + 4 < page_end) load_page(B, pg + 4);
-            process(A, pg);
-            pg += 4;
-            if (pg >= page_end) break;
-            if (pg + 4 < page_end) load_page(A, pg + 4);
-            process(B, pg);
-            pg += 4;
+        if (pg < page_end) load_page(cur, pg);
+        if (pg + ATTN_WAVES < page_end) load_page(nxt, pg + ATTN_WAVES);
+        for (; pg < page_end; pg += ATTN_WAVES) {
+            if (pg + 2 * ATTN_WAVES < page_end) load_page(nxt2, pg + 2 * ATTN_WAVES);
+            process(cur, pg);
+            cur = nxt;
+            nxt = nxt2;
         }
     }
     __syncthreads();  // all wavefronts are done with the Q tiles: the bytes become the merge buffer
@@ -182,90 +185,132 @@ __global__ __launch_bounds__(256) void attn_partial_bf16(sled_step_meta meta, co
         lsum[qt] += __shfl_xor(lsum[qt], 16);
         lsum[qt] += __shfl_xor(lsum[qt], 32);
     }
-    // merge wavefronts 1..3 into wavefront 0 through LDS, one after the other
-    for (int src = 1; src < 4; src++) {
-        if (wv == src) {
+    // merge the wavefronts' states pairwise through LDS: 4 -> 2 -> 1 (exact: every rescale is
+    // a power of two), at most attn_slots(QT) writers at a time
+    auto merge_from = [&](const float* slot) {
 #pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                if (lg == 0) {
-                    sh_m[qt * 16 + lq] = m[qt];
-                    sh_l[qt * 16 + lq] = lsum[qt];
-                }
+        for (int qt = 0; qt < QT; qt++) {
+            const float m2 = slot[QT * 2048 + qt * 16 + lq], l2 = slot[QT * 2048 + QT * 16 + qt * 16 + lq];
+            const float mnew = fmaxf(m[qt], m2);
+            const float a1 = exp2f(m[qt] - mnew), a2 = exp2f(m2 - mnew);
+            lsum[qt] = lsum[qt] * a1 + l2 * a2;
+            m[qt] = mnew;
 #pragma unroll
-                for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(sh_o + ((qt * 8 + dt) * 64 + lane) * 4) = o[qt][dt];
+            for (int dt = 0; dt < 8; dt++) {
+                const float4_t o2 = *reinterpret_cast<const float4_t*>(slot + ((qt * 8 + dt) * 64 + lane) * 4);
+#pragma unroll
+                for (int i = 0; i < 4; i++) o[qt][dt][i] = o[qt][dt][i] * a1 + o2[i] * a2;
             }
         }
-        __syncthreads();
+    };
+    auto store_to = [&](float* slot) {
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            if (lg == 0) {
+                slot[QT * 2048 + qt * 16 + lq] = m[qt];
+                slot[QT * 2048 + QT * 16 + qt * 16 + lq] = lsum[qt];
+            }
+#pragma unroll
+            for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(slot + ((qt * 8 + dt) * 64 + lane) * 4) = o[qt][dt];
+        }
+    };
+    constexpr int SLOTS = attn_slots(QT), SLOT_F = attn_slot_floats(QT);
+#pragma unroll
+    for (int half = ATTN_WAVES / 2; half >= 1; half >>= 1) {
+        for (int g0 = 0; g0 < half; g0 += SLOTS) {
+            // wavefronts half+g0 .. half+g0+SLOTS-1 hand their state to wavefronts g0 .. g0+SLOTS-1
+            if (wv >= half + g0 && wv < half + g0 + SLOTS && wv < 2 * half) store_to(sh_f + (size_t)(wv - half - g0) * SLOT_F);
+            __syncthreads();
+            if (wv >= g0 && wv < g0 + SLOTS && wv < half) merge_from(sh_f + (size_t)(wv - g0) * SLOT_F);
+            __syncthreads();
+        }
+    }
+
+    // Wavefront 0 now holds the state of work item w.  If the (request, kv head) has several work
+    // items, each stores its state; the one that arrives last merges them all in ascending order
+    // (so the result does not depend on which one that is) and writes the output.
+    const int bg = b * Hkv + g;
+    const int w0 = meta.cu_work[bg], w1 = meta.cu_work[bg + 1];
+    const bool single = (w1 - w0) == 1;
+    if (!single) {
         if (wv == 0) {
 #pragma unroll
             for (int qt = 0; qt < QT; qt++) {
-                const float m2 = sh_m[qt * 16 + lq], l2 = sh_l[qt * 16 + lq];
+                const int r = qt * 16 + lq;
+                if (lg == 0) {
+                    part_ml[((size_t)w * 2 + 0) * (QT * 16) + r] = m[qt];
+                    part_ml[((size_t)w * 2 + 1) * (QT * 16) + r] = lsum[qt];
+                }
+#pragma unroll
+                for (int dt = 0; dt < 8; dt++)
+                    *reinterpret_cast<float4_t*>(part_o + ((size_t)w * (QT * 16) + r) * D + dt * 16 + lg * 4) = o[qt][dt];
+            }
+            __threadfence();  // the stores above are visible device-wide before the arrival is counted
+            if (lane == 0) {
+                const int old = atomicAdd(&arrive[bg], 1);
+                const int last = old == (w1 - w0 - 1);
+                if (last) arrive[bg] = 0;  // ready for the next layer
+                sh_last = last;
+            }
+        }
+        __syncthreads();
+        if (!sh_last) return;
+        if (wv != 0) return;
+        __threadfence();  // see the other work items' stores
+#pragma unroll
+        for (int qt = 0; qt < QT; qt++) {
+            m[qt] = NEG_BIG;
+            lsum[qt] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 8; dt++) o[qt][dt] = float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+        for (int ww = w0; ww < w1; ww++) {
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++) {
+                const int r = qt * 16 + lq;
+                const float m2 = part_ml[((size_t)ww * 2 + 0) * (QT * 16) + r];
+                const float l2 = part_ml[((size_t)ww * 2 + 1) * (QT * 16) + r];
                 const float mnew = fmaxf(m[qt], m2);
                 const float a1 = exp2f(m[qt] - mnew), a2 = exp2f(m2 - mnew);
                 lsum[qt] = lsum[qt] * a1 + l2 * a2;
                 m[qt] = mnew;
 #pragma unroll
                 for (int dt = 0; dt < 8; dt++) {
-                    const float4_t o2 = *reinterpret_cast<const float4_t*>(sh_o + ((qt * 8 + dt) * 64 + lane) * 4);
+                    const float4_t o2 = *reinterpret_cast<const float4_t*>(part_o + ((size_t)ww * (QT * 16) + r) * D + dt * 16 + lg * 4);
 #pragma unroll
                     for (int i = 0; i < 4; i++) o[qt][dt][i] = o[qt][dt][i] * a1 + o2[i] * a2;
                 }
             }
         }
-        __syncthreads();
+    } else if (wv != 0) {
+        return;
     }
-    if (wv == 0) {
-        // partial state of work item w: rows qt*16 + lq, dims dt*16 + lg*4 + i
+    // normalise and write the attention output as a bf16 pair, in the operand order of the O
+    // projection: X[t = row0 + j][col = (g*G + hh)*D + d]; lane holds qrow lq, dims dt*16 + lg*4 + 0..3
+    const int Kdim = Hq * D;
 #pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            const int r = qt * 16 + lq;
-            if (lg == 0) {
-                part_ml[((size_t)w * 2 + 0) * (QT * 16) + r] = m[qt];
-                part_ml[((size_t)w * 2 + 1) * (QT * 16) + r] = lsum[qt];
+    for (int qt = 0; qt < QT; qt++) {
+        const int r = qt * 16 + lq;
+        if (r >= rows) continue;
+        const float inv = 1.0f / lsum[qt];
+        const int j = r / G, hh = r - j * G;
+        const int t = row0 + j;
+#pragma unroll
+        for (int dt = 0; dt < 8; dt++) {
+            const int col = (g * G + hh) * D + dt * 16 + lg * 4;
+            uint32_t hi2[2], lo2[2];
+#pragma unroll
+            for (int e = 0; e < 2; e++) {
+                const float x0 = o[qt][dt][2 * e] * inv, x1 = o[qt][dt][2 * e + 1] * inv;
+                const bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+                hi2[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                lo2[e] = (uint32_t)f32_to_bf16(x0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(x1 - bf16_to_f32(h1)) << 16);
             }
-#pragma unroll
-            for (int dt = 0; dt < 8; dt++)
-                *reinterpret_cast<float4_t*>(part_o + ((size_t)w * (QT * 16) + r) * D + dt * 16 + lg * 4) = o[qt][dt];
+            const size_t off = frag_offset(t, col, Kdim);
+            *reinterpret_cast<uint2*>(X + off) = make_uint2(hi2[0], hi2[1]);
+            *reinterpret_cast<uint2*>(X + x_plane + off) = make_uint2(lo2[0], lo2[1]);
         }
     }
-}
-
-// merge the work items of (request b, kv head g) in ascending page order, one wavefront per query
-// row; write bf16 output in operand order for the O projection:
-// X[t = row0 + j][col = (g*G + hh)*D + d]
-__global__ __launch_bounds__(64) void attn_combine_bf16(sled_step_meta meta, int QT16, int Hq, int Hkv,
-                                                        const float* __restrict__ part_o,
-                                                        const float* __restrict__ part_ml, bf16_t* __restrict__ X,
-                                                        size_t x_plane) {
-    constexpr int D = 128;
-    const int b = blockIdx.x / Hkv, g = blockIdx.x - b * Hkv;
-    const int r = blockIdx.y;
-    const int G = Hq / Hkv;
-    if (r >= G * (meta.k[b] + 1)) return;
-    const int row0 = meta.cu_rows[b];
-    const int w0 = meta.cu_work[blockIdx.x], w1 = meta.cu_work[blockIdx.x + 1];
-    const int Kdim = Hq * D;
-    const int d2 = threadIdx.x * 2;
-    float M = NEG_BIG;
-    for (int w = w0; w < w1; w++) M = fmaxf(M, part_ml[((size_t)w * 2 + 0) * QT16 + r]);
-    float lsum = 0.f;
-    float2 acc = make_float2(0.f, 0.f);
-    for (int w = w0; w < w1; w++) {
-        const float f = exp2f(part_ml[((size_t)w * 2 + 0) * QT16 + r] - M);
-        lsum += part_ml[((size_t)w * 2 + 1) * QT16 + r] * f;
-        const float2 ov = *reinterpret_cast<const float2*>(part_o + ((size_t)w * QT16 + r) * D + d2);
-        acc.x += ov.x * f;
-        acc.y += ov.y * f;
-    }
-    const float inv = 1.0f / lsum;
-    const int j = r / G, hh = r - j * G;
-    const int t = row0 + j, col = (g * G + hh) * D + d2;
-    const float ox = acc.x * inv, oy = acc.y * inv;
-    const bf16_t hx = f32_to_bf16(ox), hy = f32_to_bf16(oy);
-    const bf16_t lx = f32_to_bf16(ox - bf16_to_f32(hx)), ly = f32_to_bf16(oy - bf16_to_f32(hy));
-    const size_t off = frag_offset(t, col, Kdim);
-    *reinterpret_cast<uint32_t*>(X + off) = (uint32_t)hx | ((uint32_t)hy << 16);
-    *reinterpret_cast<uint32_t*>(X + x_plane + off) = (uint32_t)lx | ((uint32_t)ly << 16);
 }
 
 // fp32 models: one wavefront per (packed row t, query head h); lanes stride over the keys
@@ -319,22 +364,29 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const
 
 }  // namespace
 
-size_t sled_attn_lds_bytes(int QT) { return (size_t)(QT * 8 * 64 * 4 + 2 * QT * 16) * sizeof(float); }
+size_t sled_attn_lds_bytes(int QT) { return (size_t)attn_slots(QT) * attn_slot_floats(QT) * sizeof(float); }
 
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
-                          size_t q_plane, float* part_o, float* part_ml, void* X_out, size_t x_plane, int QT,
-                          hipStream_t st) {
+                          size_t q_plane, float* part_o, float* part_ml, int32_t* arrive, void* X_out, size_t x_plane,
+                          int QT, hipStream_t st) {
     const sled_shape& s = m->s;
     if (s.dtype == SLED_BF16) {
         const float scale_log2 = 1.4426950408889634f / sqrtf((float)s.head_dim);
         const size_t lds = sled_attn_lds_bytes(QT);
-        dim3 grid(meta.n_work), blk(256);
-#define SLED_ATTN_CASE(N)                                                                                          \
-    case N:                                                                                                        \
-        hipLaunchKernelGGL(attn_partial_bf16<N>, grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q), q_plane, \
-                           static_cast<const bf16_t*>(p->k_pool), static_cast<const bf16_t*>(p->v_pool), p->n_pages,   \
-                           layer, s.n_q_heads, s.n_kv_heads, scale_log2, part_o, part_ml);                           \
-        break;
+        dim3 grid(meta.n_work), blk(64 * ATTN_WAVES);
+#define SLED_ATTN_CASE(N)                                                                                            \
+    case N: {                                                                                                        \
+        static bool allowed = false;                                                                                 \
+        if (!allowed) {                                                                                              \
+            SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<N>),                          \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                     \
+            allowed = true;                                                                                          \
+        }                                                                                                            \
+        hipLaunchKernelGGL(attn_bf16_kernel<N>, grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q),  \
+                           q_plane, static_cast<const bf16_t*>(p->k_pool), static_cast<const bf16_t*>(p->v_pool),     \
+                           p->n_pages, layer, s.n_q_heads, s.n_kv_heads, scale_log2, part_o, part_ml, arrive,         \
+                           static_cast<bf16_t*>(X_out), x_plane);                                                    \
+    } break;
         switch (QT) {
             SLED_ATTN_CASE(1)
             SLED_ATTN_CASE(2)
@@ -345,9 +397,6 @@ int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_
                 SLED_FAIL(SLED_EINVAL, "attention: %d query-row tiles unsupported", QT);
         }
 #undef SLED_ATTN_CASE
-        SLED_LAUNCH_CHECK();
-        hipLaunchKernelGGL(attn_combine_bf16, dim3(meta.B * s.n_kv_heads, QT * 16), dim3(64), 0, st, meta, QT * 16, s.n_q_heads,
-                           s.n_kv_heads, part_o, part_ml, static_cast<bf16_t*>(X_out), x_plane);
         SLED_LAUNCH_CHECK();
         return SLED_OK;
     }

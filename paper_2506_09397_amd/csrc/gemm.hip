@@ -3,8 +3,8 @@
 // bf16 path (the one that matters): T is about 100-600 packed rows, so every weight byte is
 // used for only T multiply-adds and the kernel is a weight stream bounded by HBM; it is still a
 // dense contraction, so the arithmetic goes through v_mfma_f32_16x16x32_bf16.
-//   - Weights sit in HBM in MFMA operand order (see frag_offset): a wavefront fetches a 16-row x
-//     32-k tile with one contiguous 1 KiB load straight into registers, no LDS, no transpose, and
+//   - Weights sit in HBM in MFMA operand order, k-step-major (see wfrag_offset): a wavefront fetches
+//     a 16-row x 32-k tile with one contiguous 1 KiB load straight into registers, no LDS, no transpose, and
 //     keeps NBUF-1 pipeline stages of them in flight (HBM latency is covered by bytes in flight per
 //     wavefront, not by the number of wavefronts).
 //   - Activations are carried as bf16 PAIRS, x = hi + lo (two planes in operand order, written
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(320) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         nt_ok[a] = (nt0 + a) < NT;
-        wbase[a] = Wp + ((size_t)(nt_ok[a] ? nt0 + a : 0) * KS + ks_begin) * 512 + lane * 8;
+        wbase[a] = Wp + ((size_t)ks_begin * NT + (nt_ok[a] ? nt0 + a : 0)) * 512 + lane * 8;
     }
     bf16x8_t wreg[NBUF][NW][KC];
     auto load_w = [&](int buf, int stage) {
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(320) void gemm_bf16_kernel(const bf16_t* __restrict
         for (int a = 0; a < NW; a++)
 #pragma unroll
             for (int c = 0; c < KC; c++)
-                wreg[buf][a][c] = *reinterpret_cast<const bf16x8_t*>(wbase[a] + (size_t)(stage * KC + c) * 512);
+                wreg[buf][a][c] = *reinterpret_cast<const bf16x8_t*>(wbase[a] + (size_t)(stage * KC + c) * NT * 512);
     };
     auto compute = [&](const bf16_t* xb, int wbuf) {
 #pragma unroll
@@ -247,7 +247,7 @@ int launch_one(const gemm_args& a) {
     static bool allowed = false;
     auto kern = gemm_bf16_kernel<MT, NW, KC, EPI>;
     if (!allowed) {
-        SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
     }
     hipLaunchKernelGGL(kern, a.grid, dim3(320), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.T, a.T_pad, a.N,

@@ -4,7 +4,8 @@
 // K/V into the paged cache, SwiGLU for fp32 models, weight repacking at load time.
 //
 // Activations that feed a bf16 projection are written directly in MFMA operand order
-// (frag_offset), so the projection kernels never transpose anything.
+// (frag_offset), so the projection kernels never transpose anything.  Weights are repacked once, at
+// load time, into the k-step-major tile order of wfrag_offset.
 #include "sled_internal.h"
 
 namespace {
@@ -274,7 +275,7 @@ __global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t n) {
 // (bf16, operand order) or row-major (f32) matrix with K columns.
 template <bool BF16>
 __global__ void pack_rows_kernel(const void* __restrict__ src, void* __restrict__ dst, int rows, int K, int dst_row0,
-                                 int dst_row_stride) {
+                                 int dst_row_stride, int dst_row_tiles) {
     const size_t n8 = (size_t)rows * (K / 8);
     for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n8; e += (size_t)gridDim.x * blockDim.x) {
         const int r = (int)(e / (K / 8));
@@ -282,7 +283,7 @@ __global__ void pack_rows_kernel(const void* __restrict__ src, void* __restrict_
         const int dr = dst_row0 + r * dst_row_stride;
         if (BF16) {
             uint4 v = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(src) + (size_t)r * K + c);
-            *reinterpret_cast<uint4*>(static_cast<bf16_t*>(dst) + frag_offset(dr, c, K)) = v;
+            *reinterpret_cast<uint4*>(static_cast<bf16_t*>(dst) + wfrag_offset(dr, c, dst_row_tiles)) = v;
         } else {
             const float* s = static_cast<const float*>(src) + (size_t)r * K + c;
             float* d = static_cast<float*>(dst) + (size_t)dr * K + c;
@@ -301,15 +302,16 @@ __global__ void copy_gain_kernel(const void* __restrict__ src, float* __restrict
 }  // namespace
 
 int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
-                          hipStream_t st) {
+                          int dst_rows_total, hipStream_t st) {
+    const int dst_row_tiles = dst_rows_total / 16;
     const size_t n8 = (size_t)rows * (K / 8);
     int grid = (int)((n8 + 255) / 256);
     if (grid > 65535) grid = 65535;
     if (grid < 1) grid = 1;
     if (dtype == SLED_BF16)
-        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride);
+        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride, dst_row_tiles);
     else
-        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride);
+        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride, dst_row_tiles);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

@@ -72,6 +72,15 @@ __host__ __device__ inline size_t frag_offset(int r, int k, int K) {
     return ((size_t)rt * (K >> 5) + ks) * 512 + (size_t)(((kk >> 3) << 4) + rl) * 8 + (kk & 7);
 }
 
+// Weights use the same tiles, ordered k-step-major: tile (rt, ks) of a matrix with NT row tiles sits
+// at (ks * NT + rt) * 512.  All wavefronts of a projection advance through k together, so at any
+// moment the chip reads one contiguous window of NT KiB per k-step instead of thousands of streams
+// a whole matrix row apart -- DRAM pages stay open.
+__host__ __device__ inline size_t wfrag_offset(int r, int k, int NT) {
+    int rt = r >> 4, rl = r & 15, ks = k >> 5, kk = k & 31;
+    return ((size_t)ks * NT + rt) * 512 + (size_t)(((kk >> 3) << 4) + rl) * 8 + (kk & 7);
+}
+
 // ------------------------------------------------------------------------------------------
 // handles
 // ------------------------------------------------------------------------------------------
@@ -154,7 +163,7 @@ struct sled_step_meta {
 // rowops.hip.  `plane` arguments: distance in elements between the hi and lo planes of an activation
 // buffer of a bf16 model (unused for fp32 models).
 int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
-                          hipStream_t st);
+                          int dst_rows_total, hipStream_t st);
 int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStream_t st);
 int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, size_t plane,
                            const float* gain, hipStream_t st);
@@ -185,8 +194,9 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
 
 // attention.hip
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
-                          size_t q_plane, float* part_o, float* part_ml, void* X_out, size_t x_plane, int QT,
-                          hipStream_t st);
+                          size_t q_plane, float* part_o, float* part_ml, int32_t* arrive, void* X_out, size_t x_plane,
+                          int QT, hipStream_t st);
+int sled_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 
 // accept.hip
 size_t sled_accept_ws_bytes(int B, int T, int n_split);
