@@ -54,7 +54,8 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
     const int w = blockIdx.x;
     const int b = meta.work[4 * w + 0], g = meta.work[4 * w + 1];
     const int page0 = meta.work[4 * w + 2], npg = meta.work[4 * w + 3];
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: page ids are then fetched by scalar loads
     const int G = Hq / Hkv;
     const int L = len_dev[meta.req_id[b]];
     const int n = meta.k[b] + 1;
@@ -93,19 +94,42 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
         for (int dt = 0; dt < 8; dt++) o[qt][dt] = float4_t{0.f, 0.f, 0.f, 0.f};
     }
 
+    // K/V pages go from HBM straight into a private LDS ring of this wavefront (RING pages of 8 KiB:
+    // the one being consumed and the ones in flight) with direct-to-LDS loads: 4 + 4 loads of 1 KiB
+    // per page, lane l's 16 bytes landing at base + 16*l, i.e. the page keeps its operand order.
+    // The loads are issued from inline assembly and waited for by hand: they are the only
+    // vector-memory operations of the main loop, loads retire in order, so "at most 8*n
+    // outstanding" means every page but the last n issued has landed.
+    constexpr int RING = 3;
+    bf16_t* ring = sh_q + (size_t)QT * 4096 + (size_t)wv * RING * 4096;  // after the Q tiles
+    const unsigned ring_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring;
+    auto load_page = [&](int slot, int pg) {
+        // page ids come through the constant address space: uniform index, so a scalar load that does
+        // not enter the vector-memory count
+        const int phys = ((const __attribute__((address_space(4))) int32_t*)(uintptr_t)pages)[pg];
+        const size_t base = (((size_t)layer * n_pages + phys) * Hkv + g) * (16 * D);
+        const bf16_t* kg = k_pool + base + lane * 8;
+        const bf16_t* vg = v_pool + base + lane * 8;
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            const bf16_t* gp = (c < 4 ? kg : vg) + (c & 3) * 512;
+            const unsigned dst = __builtin_amdgcn_readfirstlane(ring_lds + (unsigned)(slot * 8192 + c * 1024));
+            asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gp), "s"(dst) : "memory");
+        }
+    };
     struct page_regs {
         bf16x8_t kf[4];
         uint4 vraw[4];
     };
-    auto load_page = [&](page_regs& pr, int pg) {
-        const int phys = pages[pg];
-        const size_t base = (((size_t)layer * n_pages + phys) * Hkv + g) * (16 * D);
+    auto process = [&](int slot, int pg) {
+        page_regs pr;
+        {
+            const bf16_t* pb = ring + (size_t)slot * 4096 + lane * 8;
 #pragma unroll
-        for (int c = 0; c < 4; c++) pr.kf[c] = *reinterpret_cast<const bf16x8_t*>(k_pool + base + c * 512 + lane * 8);
+            for (int c = 0; c < 4; c++) pr.kf[c] = *reinterpret_cast<const bf16x8_t*>(pb + c * 512);
 #pragma unroll
-        for (int c = 0; c < 4; c++) pr.vraw[c] = *reinterpret_cast<const uint4*>(v_pool + base + c * 512 + lane * 8);
-    };
-    auto process = [&](const page_regs& pr, int pg) {
+            for (int c = 0; c < 4; c++) pr.vraw[c] = *reinterpret_cast<const uint4*>(pb + 2048 + c * 512);
+        }
         const bool need_mask = (pg * 16 + 15) > L;  // page reaches beyond the context: causal part / tail
 #pragma unroll
         for (int qt = 0; qt < QT; qt++) {
@@ -165,17 +189,28 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
         }
     };
 
-    // the wavefront's pages, three register sets: two pages are in flight while one is consumed
+    // the wavefront's pages page0 + wv, + ATTN_WAVES, ...: two in flight while one is consumed
     {
-        page_regs cur, nxt, nxt2;
-        int pg = page0 + wv;
-        if (pg < page_end) load_page(cur, pg);
-        if (pg + ATTN_WAVES < page_end) load_page(nxt, pg + ATTN_WAVES);
-        for (; pg < page_end; pg += ATTN_WAVES) {
-            if (pg + 2 * ATTN_WAVES < page_end) load_page(nxt2, pg + 2 * ATTN_WAVES);
-            process(cur, pg);
-            cur = nxt;
-            nxt = nxt2;
+        const int first = page0 + wv;
+        const int n_my = first < page_end ? (page_end - first + ATTN_WAVES - 1) / ATTN_WAVES : 0;
+        if (n_my > 0) load_page(0, first);
+        if (n_my > 1) load_page(1, first + ATTN_WAVES);
+        int slot = 0, slot2 = 2;
+        for (int i = 0; i < n_my; i++) {
+            // slot2 held page i-1, whose LDS reads have been consumed by the arithmetic above
+            if (i + 2 < n_my) {
+                load_page(slot2, first + (i + 2) * ATTN_WAVES);
+                __builtin_amdgcn_s_waitcnt((16 & 15) | (7 << 4) | (15 << 8) | ((16 >> 4) << 14));  // vmcnt(16): page i has landed
+            } else if (i + 1 < n_my) {
+                __builtin_amdgcn_s_waitcnt(8 | (7 << 4) | (15 << 8));
+            } else {
+                __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+            }
+            asm volatile("" ::: "memory");
+            process(slot, first + i * ATTN_WAVES);
+            asm volatile("" ::: "memory");
+            slot = slot == RING - 1 ? 0 : slot + 1;
+            slot2 = slot2 == RING - 1 ? 0 : slot2 + 1;
         }
     }
     __syncthreads();  // all wavefronts are done with the Q tiles: the bytes become the merge buffer
@@ -364,7 +399,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const
 
 }  // namespace
 
-size_t sled_attn_lds_bytes(int QT) { return (size_t)attn_slots(QT) * attn_slot_floats(QT) * sizeof(float); }
+size_t sled_attn_lds_bytes(int QT) {
+    const size_t loop_bytes = (size_t)QT * 8192 + (size_t)ATTN_WAVES * 3 * 8192;  // Q tiles + per-wavefront page rings
+    const size_t merge_bytes = (size_t)attn_slots(QT) * attn_slot_floats(QT) * sizeof(float);
+    return loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
+}
 
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
                           size_t q_plane, float* part_o, float* part_ml, int32_t* arrive, void* X_out, size_t x_plane,
