@@ -97,7 +97,7 @@ typedef struct sled_shape {
 
 /* Allocates device storage for all weights of `shape` in the library's packed layout.
  * Supported: SLED_BF16 with head_dim 128, d_model, d_ffn and n_q_heads*head_dim multiples
- * of 256, vocab a multiple of 16, (n_q_heads/n_kv_heads)*(k_max+1) <= 80; SLED_F32 with head_dim 64 or 128.
+ * of 256, vocab a multiple of 32, (n_q_heads/n_kv_heads)*(k_max+1) <= 80; SLED_F32 with head_dim 64 or 128.
  * Errors: SLED_EINVAL (unsupported shape), SLED_ENOMEM. */
 SLED_API int sled_model_create(const sled_shape* shape /*host*/, sled_model** out);
 

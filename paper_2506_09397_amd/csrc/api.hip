@@ -60,7 +60,7 @@ extern "C" int sled_model_create(const sled_shape* shape, sled_model** out) {
         if (s.head_dim != 128) SLED_FAIL(SLED_EINVAL, "bf16 models need head_dim 128");
         if (s.d_model % 256 || s.d_ffn % 256 || (s.n_q_heads * s.head_dim) % 256)
             SLED_FAIL(SLED_EINVAL, "bf16 models need d_model, d_ffn and n_q_heads*head_dim multiples of 256");
-        if (s.vocab % 16) SLED_FAIL(SLED_EINVAL, "bf16 models need vocab a multiple of 16");
+        if (s.vocab % 32) SLED_FAIL(SLED_EINVAL, "bf16 models need vocab a multiple of 32");
         if (G * (s.k_max + 1) > 80) SLED_FAIL(SLED_EINVAL, "(n_q_heads/n_kv_heads)*(k_max+1) must be <= 80");
     } else if (s.dtype == SLED_F32) {
         if (s.head_dim != 64 && s.head_dim != 128) SLED_FAIL(SLED_EINVAL, "fp32 models need head_dim 64 or 128");
@@ -460,7 +460,7 @@ int attn_pages_per_item(const std::vector<int>& np, int Hkv) {
 
 ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     const sled_shape& s = m->s;
-    const size_t T_alloc = align_up(T + 64, 128), T_pad = align_up(T, 16);  // row blocks of the GEMMs may overhang
+    const size_t T_alloc = align_up(T + 64, 128), T_pad = align_up(T, 32);  // row blocks of the GEMMs may overhang
     const size_t d = s.d_model, F = s.d_ffn, HD = (size_t)s.n_q_heads * s.head_dim;
     const size_t planes = s.dtype == SLED_BF16 ? 2 : 1;  // bf16 models keep activations as hi + lo
     ws_plan w;
@@ -610,7 +610,7 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     float* part_o = reinterpret_cast<float*>(ws + wp.part_o);
     float* part_ml = reinterpret_cast<float*>(ws + wp.part_ml);
     int32_t* arrive = reinterpret_cast<int32_t*>(ws + wp.arrive);
-    const int T_pad = (int)align_up(T, 16);
+    const int T_pad = (int)align_up(T, 32);
     const int d = s.d_model, F = s.d_ffn, HD = s.n_q_heads * s.head_dim;
     const bool bf = s.dtype == SLED_BF16;
     // distance between the hi and lo planes of each activation buffer (bf16 models)

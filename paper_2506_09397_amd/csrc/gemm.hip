@@ -1,189 +1,304 @@
 // Projections of the verify step: out[T, N] = X[T, K] * W[N, K]^T over the packed rows of a batch.
 //
-// bf16 path (the one that matters): T is about 100-600 packed rows, so every weight byte is
-// used for only T multiply-adds and the kernel is a weight stream bounded by HBM; it is still a
-// dense contraction, so the arithmetic goes through v_mfma_f32_16x16x32_bf16.
-//   - Weights sit in HBM in MFMA operand order, k-step-major (see wfrag_offset): a wavefront fetches
-//     a 16-row x 32-k tile with one contiguous 1 KiB load straight into registers, no LDS, no transpose, and
-//     keeps NBUF-1 pipeline stages of them in flight (HBM latency is covered by bytes in flight per
-//     wavefront, not by the number of wavefronts).
+// bf16 path (the one that matters): T is about 100-600 packed rows, so every weight byte is used
+// for only T multiply-adds and the kernel is a weight stream bounded by HBM.  It is still a dense
+// contraction, so the arithmetic goes through v_mfma_f32_32x32x16_bf16 (the 16x16 shapes run at
+// about half its rate on gfx950, which would make them, not HBM, the bound).
+//   - Weights sit in HBM in MFMA operand order, k-step-major (see wfrag_offset): a wavefront
+//     fetches a 32-row x 16-k tile with one contiguous 1 KiB load straight into registers, no LDS,
+//     no transpose, and keeps three pipeline stages of them in flight.
 //   - Activations are carried as bf16 PAIRS, x = hi + lo (two planes in operand order, written
 //     that way by the producing kernel): a single bf16 rounding of every activation costs more
-//     accuracy than the 2e-2 logit tolerance allows at 8B scale, while in this HBM-bound regime
-//     the MFMA pipes are mostly idle, so each weight tile is multiplied with both planes.
-//     They are small and shared by all wavefronts of a workgroup: a fifth "producer" wavefront
-//     streams them from L2 into a ring of three LDS buffers with direct-to-LDS loads, two stages
-//     ahead, while the four "consumer" wavefronts stream weights and do the arithmetic.  The split
-//     matters because vector-memory loads retire in order under one counter: a wavefront that
-//     issued both kinds could not wait for its activation loads without also draining its weight
-//     prefetch.
-//   - Each wavefront owns NW 16-column tiles of the output for all rows of its block (MT 16-row
-//     tiles): an activation tile read from LDS is reused for NW weight tiles.
+//     accuracy than the 2e-2 logit tolerance allows at 8B scale, so each weight tile is multiplied
+//     with both planes.  All wavefronts of a workgroup need all of them: they go from L2 into a
+//     ring of five LDS stage buffers with direct-to-LDS loads, four stages ahead.
+//   - A workgroup is 8 wavefronts (two per SIMD), all alike: 2 column groups x 4 k-groups.  A stage
+//     is 4 k-steps of 16; k-group g works on the g-th of them for the 64 columns (two 32-column
+//     tiles) of its column group and all rows of the block (MT 32-row tiles), and the k-groups'
+//     sums are added through LDS at the end, in a fixed order.  This shape follows from three
+//     per-CU limits that all sit within a factor of two of the HBM time: one wavefront sustains
+//     only about 4-5 bytes per clock from L2, so the activation stream (twice the weight bytes per
+//     CU) has to be issued by all eight; ds_read_b128 runs at about 64 bytes per clock, so each
+//     activation tile read from LDS has to feed four MFMAs; and the MFMAs themselves need two
+//     wavefronts per SIMD to hide each other's waits.
+//   - Vector-memory loads retire in order under one counter, and the compiler cannot see that the
+//     two streams are independent (it drains the counter before any LDS read that might alias a
+//     direct-to-LDS load).  Both kinds of loads are therefore issued from inline assembly in a
+//     fixed order, and the waits are written by hand from that order.
 //   - Split-K over blockIdx.y gives every CU work on the narrow projections; partial sums go to a
 //     [split, T, N] fp32 buffer that the following row kernel reduces in a fixed order (no float
 //     atomics: results are reproducible run to run).
 //   - The weight tile is the A operand, the activation tile the B operand, so a lane ends up with
-//     4 consecutive output columns of one row: float4 stores, and gate/up pairs for SwiGLU in-lane.
+//     groups of 4 consecutive output columns of one row: float4 stores, and gate/up pairs for
+//     SwiGLU in-lane.
 //
 // fp32 path: plain LDS-tiled FMA kernel, used by fp32 models (correctness configuration).
 #include "sled_internal.h"
 
 #include <stdlib.h>
 #include <string.h>
+#include <algorithm>
+#include <type_traits>
 
 namespace {
 
-constexpr int PLANES = 2;  // activation planes: hi, lo
-constexpr int NXB = 3;     // LDS ring: the stage being read, the next one (landed), the one after (in flight)
-constexpr int NBUF = 4;    // weight register buffers: the stage in use + 3 stages in flight
+constexpr int PLANES = 2;    // activation planes: hi, lo
+constexpr int KG = 4;        // k-groups = k-steps of 16 per stage
+constexpr int CG = 2;        // column groups
+constexpr int NW = 2;        // 32-column tiles per wavefront
+constexpr int WAVES = KG * CG;
+constexpr int DEPTH = 3;     // weight stages in flight beyond the one in use
+constexpr int NBUF = DEPTH + 1;
+constexpr int AHEAD = DEPTH + 1;  // activation stages in flight beyond the one being read
+constexpr int NXB = AHEAD + 1;    // LDS ring
+constexpr int COLS_PER_WG = CG * NW * 32;
 
-// s_waitcnt vmcnt(n) alone: expcnt and lgkmcnt fields at their no-wait values
-constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float float16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4_t;
 
-template <int MT, int NW, int KC, int EPI>
-__global__ __launch_bounds__(320) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
-                                                        const bf16_t* __restrict__ Wp, int NT, int KS, int ks_per_split,
-                                                        int T, int T_pad, int N, float* __restrict__ out,
-                                                        bf16_t* __restrict__ out_act, size_t act_plane, int F_act) {
+// s_waitcnt vmcnt(N) tied to the registers the awaited loads write: the compiler sees the assembly
+// loads as complete when issued, so the data dependence has to run through the wait.
+template <int N>
+__device__ __forceinline__ void wait_loads(u32x4_t& a, u32x4_t& b) {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+
+// MT: 32-row tiles of activations per block.
+template <int MT, int EPI>
+__global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
+                                                               const bf16_t* __restrict__ Wp, int NT, int KS,
+                                                               int ks_per_split, int T, int T_pad, int N,
+                                                               float* __restrict__ out, bf16_t* __restrict__ out_act,
+                                                               size_t act_plane, int F_act) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t* xs = reinterpret_cast<bf16_t*>(smem);  // [NXB][PLANES][MT][KC][512]
-    constexpr int STAGE_TILES = PLANES * MT * KC;  // 1 KiB operand tiles per stage
-    constexpr int STAGE_ELEMS = STAGE_TILES * 512;
+    constexpr int STAGE_TILES = PLANES * MT * KG;  // 1 KiB operand tiles per stage, ordered [plane][row tile][k-step]
+    constexpr int MY_TILES = STAGE_TILES / WAVES;  // = MT: tiles of a stage this wavefront fetches
+    constexpr int PER_ITER = MY_TILES + NW;        // vector-memory instructions a wavefront issues per stage
+    constexpr unsigned STAGE_BYTES = STAGE_TILES * 1024;
+    static_assert(STAGE_TILES % WAVES == 0, "stage does not divide among the wavefronts");
+    static_assert(PER_ITER * DEPTH < 64, "too many loads in flight for the counter");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int cg = wv & (CG - 1), kgi = wv / CG;
     const int ks_begin = blockIdx.y * ks_per_split;
-    const int n_stage = ks_per_split / KC;  // a positive multiple of NBUF (the host picks K slices accordingly)
-    const int mt_base = blockIdx.z * MT;    // first 16-row tile handled by this block
+    const int n_stage = ks_per_split / KG;  // a positive multiple of NBUF (the host picks K slices accordingly)
+    const int mt_base = blockIdx.z * MT;    // first 32-row tile handled by this block
 
-    if (wv == 4) {
-        // ---- producer wavefront: activations L2 -> LDS, two stages ahead of the consumers -------
-        // One direct-to-LDS load moves a whole operand tile: lane l's 16 bytes land at base + 16*l.
-        auto dma = [&](int buf, int stage) {
+    // ---- activations: this wavefront's tiles of stage 0 and where they land in a stage buffer -----
+    const int row_lim = (T + 7) & ~7;
+    const bf16_t* xsrc[MY_TILES];
+    unsigned xdst[MY_TILES];
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;  // LDS byte address of the ring
 #pragma unroll
-            for (int i = 0; i < STAGE_TILES; i++) {
-                const int pl = i / (MT * KC), rem = i - pl * (MT * KC);
-                const int b = rem / KC, c = rem - b * KC;
-                const bf16_t* g = Xp + pl * x_plane + ((size_t)(mt_base + b) * KS + ks_begin + stage * KC + c) * 512 + lane * 8;
-                bf16_t* l = xs + (size_t)buf * STAGE_ELEMS + (size_t)i * 512;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                                 (__attribute__((address_space(3))) void*)l, 16, 0, 0);
-            }
-        };
-        dma(0, 0);
-        dma(1, 1);
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(STAGE_TILES));  // stage 0 has landed, stage 1 may be in flight
-        __builtin_amdgcn_s_barrier();
-        int buf = 2;
-        for (int s = 0; s < n_stage; s++) {
-            // buffer `buf` held stage s-1: its readers passed the previous barrier
-            if (s + 2 < n_stage) {
-                dma(buf, s + 2);
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(STAGE_TILES));  // loads retire in order: stage s+1 has landed
-            } else {
-                __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            }
-            __builtin_amdgcn_s_barrier();  // publishes stage s+1, and says stage s has been consumed
-            buf = buf == NXB - 1 ? 0 : buf + 1;
-        }
-        return;
+    for (int j = 0; j < MY_TILES; j++) {
+        const int i = j * WAVES + wv;
+        const int g = i % KG, pb = i / KG, pl = pb / MT, b = pb - pl * MT;
+        // Lanes whose row lies past the last token (rounded up to whole 128-byte lines of 8 rows) re-read
+        // the tile's first line instead: the fetch unit merges them into that line's request, so padding
+        // rows cost no L2 traffic.  What lands in their LDS bytes only reaches their own output rows.
+        const int row = (mt_base + b) * 32 + (lane & 31);
+        const int src_lane = row < row_lim ? lane : (lane & 32) + (lane & 7);
+        xsrc[j] = Xp + pl * x_plane + ((size_t)(mt_base + b) * KS + ks_begin + g) * 512 + src_lane * 8;
+        xdst[j] = lds_base + i * 1024;
     }
-
-    // ---- consumer wavefronts: weights HBM -> registers, MFMA ---------------------------------------
-    const int nt0 = (blockIdx.x * 4 + wv) * NW;
-    float4_t acc[NW][MT];
+    // one direct-to-LDS load moves a whole operand tile: lane l's 16 bytes land at m0 + 16*l
+    auto x_issue_one = [&](int buf, int stage, int j) {
+        const bf16_t* src = xsrc[j] + (size_t)stage * (KG * 512);
+        const unsigned dst = __builtin_amdgcn_readfirstlane(xdst[j] + (unsigned)buf * STAGE_BYTES);
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst) : "memory");
+    };
+    auto x_issue = [&](int buf, int stage) {
 #pragma unroll
-    for (int a = 0; a < NW; a++)
-#pragma unroll
-        for (int b = 0; b < MT; b++) acc[a][b] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < MY_TILES; j++) x_issue_one(buf, stage, j);
+    };
 
+    // ---- weights: NW tiles per stage, straight into registers ------------------------------------------
+    const int nt0 = (blockIdx.x * CG + cg) * NW;
     bool nt_ok[NW];
-    const bf16_t* wbase[NW];
+    const bf16_t* wsrc[NW];
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         nt_ok[a] = (nt0 + a) < NT;
-        wbase[a] = Wp + ((size_t)ks_begin * NT + (nt_ok[a] ? nt0 + a : 0)) * 512 + lane * 8;
+        wsrc[a] = Wp + ((size_t)(ks_begin + kgi) * NT + (nt_ok[a] ? nt0 + a : 0)) * 512 + lane * 8;
     }
-    bf16x8_t wreg[NBUF][NW][KC];
-    auto load_w = [&](int buf, int stage) {
-#pragma unroll
-        for (int a = 0; a < NW; a++)
-#pragma unroll
-            for (int c = 0; c < KC; c++)
-                wreg[buf][a][c] = *reinterpret_cast<const bf16x8_t*>(wbase[a] + (size_t)(stage * KC + c) * NT * 512);
+    u32x4_t wreg[NBUF][NW];
+    auto w_issue_one = [&](int buf, int stage, int a) {
+        const bf16_t* src = wsrc[a] + (size_t)stage * KG * NT * 512;
+        asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(wreg[buf][a]) : "v"(src) : "memory");
     };
-    auto compute = [&](const bf16_t* xb, int wbuf) {
+    auto w_issue = [&](int buf, int stage) {
 #pragma unroll
-        for (int c = 0; c < KC; c++) {
+        for (int a = 0; a < NW; a++) w_issue_one(buf, stage, a);
+    };
+
+    float16_t acc[NW][MT];
 #pragma unroll
-            for (int b = 0; b < MT; b++) {
-                const bf16_t* xp = xb + ((size_t)(b * KC + c)) * 512 + lane * 8;
-                const bf16x8_t xhi = *reinterpret_cast<const bf16x8_t*>(xp);
-                const bf16x8_t xlo = *reinterpret_cast<const bf16x8_t*>(xp + MT * KC * 512);
+    for (int a = 0; a < NW; a++)
 #pragma unroll
-                for (int a = 0; a < NW; a++) {
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[wbuf][a][c], xhi, acc[a][b], 0, 0, 0);
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[wbuf][a][c], xlo, acc[a][b], 0, 0, 0);
+        for (int b = 0; b < MT; b++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[a][b][e] = 0.f;
+
+    const bf16_t* xs = reinterpret_cast<const bf16_t*>(smem) + kgi * 512 + lane * 8;
+    struct xfrag {
+        bf16x8_t hi, lo;
+    };
+    auto read_x = [&](int xbuf, int b) {
+        const bf16_t* xb = xs + (size_t)xbuf * (STAGE_BYTES / 2);
+        xfrag f;
+        f.hi = *reinterpret_cast<const bf16x8_t*>(xb + (size_t)b * (KG * 512));
+        f.lo = *reinterpret_cast<const bf16x8_t*>(xb + (size_t)(MT + b) * (KG * 512));
+        return f;
+    };
+    auto mfma4 = [&](int b, const xfrag& f, const bf16x8_t& w0, const bf16x8_t& w1) {
+        acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, f.hi, acc[0][b], 0, 0, 0);
+        acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, f.hi, acc[1][b], 0, 0, 0);
+        acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0, f.lo, acc[0][b], 0, 0, 0);
+        acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1, f.lo, acc[1][b], 0, 0, 0);
+    };
+    // One stage ("iteration" s): arithmetic of stage s, and the loads of later stages.
+    //   - The iteration's PER_ITER loads (activations of stage s+AHEAD, then weights of stage
+    //     s+DEPTH, always in that order) leave first, right after the wait.
+    //   - LDS reads run one row tile ahead of the MFMAs that use them, and the first row tile of the
+    //     next stage is read before the last MFMAs of this one.  `cur` holds row tile 0 of the stage
+    //     on entry and row tile 0 of the next stage on exit.
+    //   - The barrier before the last row tile says two things: this wavefront's share of stage s+1
+    //     has landed (the wait at the top covers it), and its LDS reads of stage s are back, so that
+    //     buffer may be refilled.
+    // The wait at the top is for the weights of stage s and the activations of stage s+1, both issued
+    // DEPTH iterations earlier; AFTER is the number of loads issued since.
+    xfrag cur;
+    auto stage = [&](auto after_c, int xbuf, auto wbuf_c, bool more, int x_stage, int x_buf, int w_stage) {
+        constexpr int AFTER = decltype(after_c)::value, WBUF = decltype(wbuf_c)::value;
+        wait_loads<AFTER>(wreg[WBUF][0], wreg[WBUF][1]);
+        const bf16x8_t w0 = __builtin_bit_cast(bf16x8_t, wreg[WBUF][0]), w1 = __builtin_bit_cast(bf16x8_t, wreg[WBUF][1]);
+        auto issue = [&](int lo, int hi) {  // loads number lo .. hi-1 of this iteration
+#pragma unroll
+            for (int i = lo; i < hi; i++) {
+                if (i < MY_TILES) {
+                    if (x_stage >= 0) x_issue_one(x_buf, x_stage, i);
+                } else {
+                    if (w_stage >= 0) w_issue_one((WBUF + DEPTH) % NBUF, w_stage, i - MY_TILES);
                 }
             }
-        }
-    };
-
+        };
+        issue(0, PER_ITER);
 #pragma unroll
-    for (int u = 0; u < NBUF - 1; u++) load_w(u, u);
-    __builtin_amdgcn_s_barrier();  // stage 0 of the activations is in LDS
-    int xbuf = 0;
-    // NBUF stages per trip so that the weight register buffer is a compile-time index.  The only
-    // vector-memory operations of these wavefronts are the weight loads, so the compiler's own wait
-    // before a stage's arithmetic leaves the three later stages in flight.
-    // All trips but the last prefetch unconditionally; the last one has nothing left to fetch after
-    // its first stage.  Keeping run-time conditions out of the trips matters: the compiler sizes
-    // each wait for the path with the fewest loads outstanding.
-    int s0 = 0;
-    for (; s0 + NBUF < n_stage; s0 += NBUF) {
-#pragma unroll
-        for (int u = 0; u < NBUF; u++) {
-            load_w((u + NBUF - 1) % NBUF, s0 + u + NBUF - 1);
+        for (int b = 0; b + 1 < MT; b++) {
+            const xfrag nxt = read_x(xbuf, b + 1);
             __builtin_amdgcn_sched_barrier(0);
-            compute(xs + (size_t)xbuf * STAGE_ELEMS, u);
+            mfma4(b, cur, w0, w1);
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_barrier();
-            xbuf = xbuf == NXB - 1 ? 0 : xbuf + 1;
+            cur = nxt;
         }
-    }
-#pragma unroll
-    for (int u = 0; u < NBUF; u++) {
-        if (u == 0) load_w(NBUF - 1, s0 + NBUF - 1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(xs + (size_t)xbuf * STAGE_ELEMS, u);
-        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(7 << 4 | 3 << 14 | 15);  // lgkmcnt(0) only
         __builtin_amdgcn_s_barrier();
+        xfrag nxt = cur;
+        if (more) nxt = read_x(xbuf == NXB - 1 ? 0 : xbuf + 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma4(MT - 1, cur, w0, w1);
+        __builtin_amdgcn_sched_barrier(0);
+        cur = nxt;
+    };
+    using std::integral_constant;
+
+    // prologue: activations of stages 0..DEPTH and weights of stages 0..DEPTH-1, in iteration order
+    x_issue(0, 0);
+#pragma unroll
+    for (int u = 0; u < DEPTH; u++) {
+        x_issue(u + 1, u + 1);
+        w_issue(u, u);
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DEPTH * PER_ITER) : "memory");  // own tiles of stage 0
+    __builtin_amdgcn_s_barrier();                                           // everybody's
+    cur = read_x(0, 0);
+    int xbuf = 0, fbuf = AHEAD;  // buffer being read; buffer the next activations go to
+    int s0 = 0;
+    auto advance = [&]() {
         xbuf = xbuf == NXB - 1 ? 0 : xbuf + 1;
+        fbuf = fbuf == NXB - 1 ? 0 : fbuf + 1;
+    };
+    constexpr int STEADY = (DEPTH - 1) * PER_ITER;  // iterations s-DEPTH+1 .. s-1 have issued all their loads
+    static_assert(DEPTH == 3 && NBUF == 4, "the trips below are written for three stages in flight");
+    for (; s0 + NBUF < n_stage; s0 += NBUF) {
+        // buffer fbuf held stage s-1: every reader passed the barrier of the previous iteration
+        stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 0>{}, true, s0 + AHEAD, fbuf, s0 + DEPTH);
+        advance();
+        stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 1>{}, true, s0 + 1 + AHEAD, fbuf, s0 + 1 + DEPTH);
+        advance();
+        stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 2>{}, true, s0 + 2 + AHEAD, fbuf, s0 + 2 + DEPTH);
+        advance();
+        stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 3>{}, true, s0 + 3 + AHEAD, fbuf, s0 + 3 + DEPTH);
+        advance();
+    }
+    // last trip: only the weights of the last stage are left to fetch (in its first iteration)
+    stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 0>{}, true, -1, 0, s0 + DEPTH);
+    advance();
+    stage(integral_constant<int, PER_ITER + NW>{}, xbuf, integral_constant<int, 1>{}, true, -1, 0, -1);
+    advance();
+    stage(integral_constant<int, NW>{}, xbuf, integral_constant<int, 2>{}, true, -1, 0, -1);
+    advance();
+    stage(integral_constant<int, 0>{}, xbuf, integral_constant<int, 3>{}, false, -1, 0, -1);
+    __syncthreads();  // every stage has been consumed and no load is in flight: the ring is free
+
+    // ---- add the four k-groups' sums: (0 + 2) + (1 + 3), through LDS ------------------------------------
+    {
+        constexpr int PER_WAVE = NW * MT * 16 * 64;  // floats a wavefront parks
+        float* red = reinterpret_cast<float*>(smem);
+        auto park = [&](int slot) {
+#pragma unroll
+            for (int a = 0; a < NW; a++)
+#pragma unroll
+                for (int b = 0; b < MT; b++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) red[(size_t)slot * PER_WAVE + ((a * MT + b) * 16 + e) * 64 + lane] = acc[a][b][e];
+        };
+        auto take = [&](int slot) {
+#pragma unroll
+            for (int a = 0; a < NW; a++)
+#pragma unroll
+                for (int b = 0; b < MT; b++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) acc[a][b][e] += red[(size_t)slot * PER_WAVE + ((a * MT + b) * 16 + e) * 64 + lane];
+        };
+        if (kgi >= 2) park((kgi - 2) * CG + cg);
+        __syncthreads();
+        if (kgi >= 2) return;
+        take(kgi * CG + cg);
+        __syncthreads();
+        if (kgi == 1) park(cg);
+        __syncthreads();
+        if (kgi == 1) return;
+        take(cg);
     }
 
-    // epilogue: lane holds rows (tokens) mt*16 + lane%16, columns nt*16 + (lane/16)*4 + 0..3
-    const int col_in_tile = (lane >> 4) * 4;
+    // epilogue: lane holds row (token) mt*32 + lane%32 and, in registers 4q .. 4q+3, the columns
+    // nt*32 + 8q + (lane/32)*4 + 0..3
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         if (!nt_ok[a]) continue;
-        const int n = (nt0 + a) * 16 + col_in_tile;
 #pragma unroll
         for (int b = 0; b < MT; b++) {
-            const int tok = (mt_base + b) * 16 + (lane & 15);
-            if (EPI == SLED_EPI_PARTIAL) {
-                if (tok < T_pad)
-                    *reinterpret_cast<float4_t*>(out + ((size_t)blockIdx.y * T_pad + tok) * N + n) = acc[a][b];
-            } else if (EPI == SLED_EPI_STORE) {
-                if (tok < T) *reinterpret_cast<float4_t*>(out + (size_t)tok * N + n) = acc[a][b];
-            } else {  // SwiGLU: columns are (gate f, up f, gate f+1, up f+1)
-                if (tok < T_pad) {
-                    const int f = n >> 1;
-                    float g0 = acc[a][b][0], u0 = acc[a][b][1], g1 = acc[a][b][2], u1 = acc[a][b][3];
-                    float a0 = g0 / (1.f + __expf(-g0)) * u0;
-                    float a1 = g1 / (1.f + __expf(-g1)) * u1;
-                    const bf16_t h0 = f32_to_bf16(a0), h1 = f32_to_bf16(a1);
-                    const bf16_t l0 = f32_to_bf16(a0 - bf16_to_f32(h0)), l1 = f32_to_bf16(a1 - bf16_to_f32(h1));
-                    const size_t o = frag_offset(tok, f, F_act);
-                    *reinterpret_cast<uint32_t*>(out_act + o) = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                    *reinterpret_cast<uint32_t*>(out_act + act_plane + o) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+            const int tok = (mt_base + b) * 32 + (lane & 31);
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
+                const float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                if (EPI == SLED_EPI_PARTIAL) {
+                    if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)blockIdx.y * T_pad + tok) * N + n) = v;
+                } else if (EPI == SLED_EPI_STORE) {
+                    if (tok < T) *reinterpret_cast<float4_t*>(out + (size_t)tok * N + n) = v;
+                } else {  // SwiGLU: columns are (gate f, up f, gate f+1, up f+1)
+                    if (tok < T_pad) {
+                        const int f = n >> 1;
+                        const float a0 = v[0] / (1.f + __expf(-v[0])) * v[1];
+                        const float a1 = v[2] / (1.f + __expf(-v[2])) * v[3];
+                        const bf16_t h0 = f32_to_bf16(a0), h1 = f32_to_bf16(a1);
+                        const bf16_t l0 = f32_to_bf16(a0 - bf16_to_f32(h0)), l1 = f32_to_bf16(a1 - bf16_to_f32(h1));
+                        const size_t o = frag_offset(tok, f, F_act);
+                        *reinterpret_cast<uint32_t*>(out_act + o) = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                        *reinterpret_cast<uint32_t*>(out_act + act_plane + o) = (uint32_t)l0 | ((uint32_t)l1 << 16);
+                    }
                 }
             }
         }
@@ -241,50 +356,34 @@ struct gemm_args {
     int F_act;
 };
 
-template <int MT, int NW, int KC, int EPI>
+template <int MT, int EPI>
 int launch_one(const gemm_args& a) {
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
-    auto kern = gemm_bf16_kernel<MT, NW, KC, EPI>;
+    auto kern = gemm_bf16_kernel<MT, EPI>;
     if (!allowed) {
         SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
     }
-    hipLaunchKernelGGL(kern, a.grid, dim3(320), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.T, a.T_pad, a.N,
-                       a.out, a.out_act, a.act_plane, a.F_act);
+    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.T, a.T_pad,
+                       a.N, a.out, a.out_act, a.act_plane, a.F_act);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
 
-template <int MT, int NW, int KC>
+template <int MT>
 int launch_epi(int epi, const gemm_args& a) {
     switch (epi) {
-        case SLED_EPI_PARTIAL: return launch_one<MT, NW, KC, SLED_EPI_PARTIAL>(a);
-        case SLED_EPI_SWIGLU: return launch_one<MT, NW, KC, SLED_EPI_SWIGLU>(a);
-        default: return launch_one<MT, NW, KC, SLED_EPI_STORE>(a);
+        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL>(a);
+        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU>(a);
+        default: return launch_one<MT, SLED_EPI_STORE>(a);
     }
 }
 
-template <int MT>
-int launch_cfg(int nw, int kc, int epi, const gemm_args& a) {
-    if (kc == 1) {
-        switch (nw) {
-            case 1: return launch_epi<MT, 1, 1>(epi, a);
-            case 2: return launch_epi<MT, 2, 1>(epi, a);
-            default: return launch_epi<MT, 4, 1>(epi, a);
-        }
-    }
-    switch (nw) {
-        case 1: return launch_epi<MT, 1, 2>(epi, a);
-        case 2: return launch_epi<MT, 2, 2>(epi, a);
-        default: return launch_epi<MT, 4, 2>(epi, a);
-    }
-}
-
-// tuning aid: SLED_GEMM_TUNE="N:K:nw:kc:split;..." overrides the plan of the projections with those
-// N and K (read once)
+// tuning aid: SLED_GEMM_TUNE="N:K:split;..." overrides the number of K slices of the projections with
+// those N and K (read once)
 struct tune_entry {
-    int N, K, nw, kc, split;
+    int N, K, split;
 };
 const std::vector<tune_entry>& tune_table() {
     static std::vector<tune_entry> t = [] {
@@ -296,9 +395,8 @@ const std::vector<tune_entry>& tune_table() {
         while (pos < s.size()) {
             size_t end = s.find(';', pos);
             if (end == std::string::npos) end = s.size();
-            tune_entry te{0, 0, 0, 0, 0};
-            if (sscanf(s.substr(pos, end - pos).c_str(), "%d:%d:%d:%d:%d", &te.N, &te.K, &te.nw, &te.kc, &te.split) == 5)
-                v.push_back(te);
+            tune_entry te{0, 0, 0};
+            if (sscanf(s.substr(pos, end - pos).c_str(), "%d:%d:%d", &te.N, &te.K, &te.split) == 3) v.push_back(te);
             pos = end + 1;
         }
         return v;
@@ -308,24 +406,18 @@ const std::vector<tune_entry>& tune_table() {
 
 }  // namespace
 
-// Shape of the launch for a projection of N columns over K: NW 16-column tiles per wavefront, KC
-// k-steps per pipeline stage and the number of K slices.  More tiles per wavefront mean fewer LDS
-// reads per weight byte; more slices mean more workgroups (the chip wants at least one per CU) but
-// more partial sums to reduce.  Each slice must hold a multiple of 4 stages.
+// Number of K slices for a projection of N columns over K.  More slices mean more workgroups (the
+// chip wants at least one per CU) but more partial sums to reduce.  Each slice must hold a multiple
+// of 4 stages of 64 k.
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k) {
-    sled_gemm_plan p{1, 1, 1};
+    sled_gemm_plan p{1};
     if (m->s.dtype != SLED_BF16) return p;
-    const int NT = N / 16;
-    auto legal = [&](int kc, int sp) { return sp >= 1 && (K / 32) % (sp * kc * NBUF) == 0; };
+    auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * KG * NBUF) == 0; };
     for (const auto& te : tune_table())
-        if (te.N == N && te.K == K && (te.nw == 1 || te.nw == 2 || te.nw == 4) && (te.kc == 1 || te.kc == 2) &&
-            legal(te.kc, te.split) && (!needs_full_k || te.split == 1))
-            return sled_gemm_plan{te.nw, te.kc, te.split};
-    p.nw = NT >= 4096 ? 4 : 2;
-    p.kc = 1;
-    const int n_wg = (NT + 4 * p.nw - 1) / (4 * p.nw);
+        if (te.N == N && te.K == K && legal(te.split) && (!needs_full_k || te.split == 1)) return sled_gemm_plan{te.split};
+    const int n_wg = (N + COLS_PER_WG - 1) / COLS_PER_WG;
     if (!needs_full_k)
-        while (n_wg * p.split < 256 && legal(p.kc, p.split * 2)) p.split *= 2;
+        while (n_wg * p.split < 160 && legal(p.split * 2)) p.split *= 2;
     return p;
 }
 
@@ -333,16 +425,16 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
                      int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane, int F_act,
                      hipStream_t st) {
     if (m->s.dtype == SLED_BF16) {
-        const int NT = N / 16, KS = K / 32;
-        if (N % 16 || K % 32 || T_pad % 16 || KS % (plan.split * plan.kc * NBUF))
-            SLED_FAIL(SLED_EINVAL, "gemm: unsupported shape N=%d K=%d T_pad=%d split=%d kc=%d", N, K, T_pad, plan.split, plan.kc);
-        const int mt_total = T_pad / 16;
-        // rows are processed in blocks of at most 8 tiles (128 rows), evenly sized
-        const int zb = (mt_total + 7) / 8;
+        const int NT = N / 32, KS = K / 16;
+        if (N % 32 || K % 16 || T_pad % 32 || plan.split < 1 || KS % (plan.split * KG * NBUF))
+            SLED_FAIL(SLED_EINVAL, "gemm: unsupported shape N=%d K=%d T_pad=%d split=%d", N, K, T_pad, plan.split);
+        const int mt_total = T_pad / 32;
+        // rows are processed in blocks of at most 4 tiles (128 rows), evenly sized
+        const int zb = (mt_total + 3) / 4;
         const int MT = (mt_total + zb - 1) / zb;
         gemm_args a;
-        a.grid = dim3((NT + 4 * plan.nw - 1) / (4 * plan.nw), plan.split, (mt_total + MT - 1) / MT);
-        a.lds = (size_t)NXB * PLANES * MT * plan.kc * 512 * sizeof(bf16_t);
+        a.grid = dim3((NT + CG * NW - 1) / (CG * NW), plan.split, (mt_total + MT - 1) / MT);
+        a.lds = (size_t)NXB * PLANES * MT * KG * 1024;  // also holds the MT * 32 KiB of the final reduction
         a.st = st;
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;
@@ -358,14 +450,10 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.act_plane = act_plane;
         a.F_act = F_act;
         switch (MT) {
-            case 1: return launch_cfg<1>(plan.nw, plan.kc, epilogue, a);
-            case 2: return launch_cfg<2>(plan.nw, plan.kc, epilogue, a);
-            case 3: return launch_cfg<3>(plan.nw, plan.kc, epilogue, a);
-            case 4: return launch_cfg<4>(plan.nw, plan.kc, epilogue, a);
-            case 5: return launch_cfg<5>(plan.nw, plan.kc, epilogue, a);
-            case 6: return launch_cfg<6>(plan.nw, plan.kc, epilogue, a);
-            case 7: return launch_cfg<7>(plan.nw, plan.kc, epilogue, a);
-            default: return launch_cfg<8>(plan.nw, plan.kc, epilogue, a);
+            case 1: return launch_epi<1>(epilogue, a);
+            case 2: return launch_epi<2>(epilogue, a);
+            case 3: return launch_epi<3>(epilogue, a);
+            default: return launch_epi<4>(epilogue, a);
         }
     }
     // fp32: no split, plain store (partial buffer with one slice has the same layout)

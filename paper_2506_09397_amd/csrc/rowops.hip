@@ -303,7 +303,7 @@ __global__ void copy_gain_kernel(const void* __restrict__ src, float* __restrict
 
 int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
                           int dst_rows_total, hipStream_t st) {
-    const int dst_row_tiles = dst_rows_total / 16;
+    const int dst_row_tiles = dst_rows_total / 32;
     const size_t n8 = (size_t)rows * (K / 8);
     int grid = (int)((n8 + 255) / 256);
     if (grid > 65535) grid = 65535;

@@ -58,18 +58,19 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
 
 // ------------------------------------------------------------------------------------------
-// Packed operand layout for the bf16 MFMA kernels ("fragment order").
+// Packed operand layout for the bf16 projection kernels ("fragment order").
 //
 // A matrix M[R, K] (R = rows: output features of a weight, or tokens of an activation; K the
-// contraction axis) is stored as tiles of 16 rows x 32 k.  Tile (rt, ks) occupies 512
-// consecutive elements; inside it, lane l of a wavefront owns the 8 consecutive elements
-//     M[rt*16 + l%16][ks*32 + (l/16)*8 + j],  j = 0..7
-// which is exactly the operand register content of v_mfma_f32_16x16x32_bf16.  A wavefront
+// contraction axis) is stored as tiles of 32 rows x 16 k.  A tile occupies 512 consecutive
+// elements; inside it, lane l of a wavefront owns the 8 consecutive elements
+//     M[rt*32 + l%32][ks*16 + (l/32)*8 + j],  j = 0..7
+// which is exactly the operand register content of v_mfma_f32_32x32x16_bf16.  A wavefront
 // therefore loads one operand tile with a single fully coalesced 1 KiB access.
+// Activations order their tiles row-tile-major: tile (rt, ks) at (rt * K/16 + ks) * 512.
 // ------------------------------------------------------------------------------------------
 __host__ __device__ inline size_t frag_offset(int r, int k, int K) {
-    int rt = r >> 4, rl = r & 15, ks = k >> 5, kk = k & 31;
-    return ((size_t)rt * (K >> 5) + ks) * 512 + (size_t)(((kk >> 3) << 4) + rl) * 8 + (kk & 7);
+    int rt = r >> 5, rl = r & 31, ks = k >> 4, kk = k & 15;
+    return ((size_t)rt * (K >> 4) + ks) * 512 + (size_t)(((kk >> 3) << 5) + rl) * 8 + (kk & 7);
 }
 
 // Weights use the same tiles, ordered k-step-major: tile (rt, ks) of a matrix with NT row tiles sits
@@ -77,8 +78,8 @@ __host__ __device__ inline size_t frag_offset(int r, int k, int K) {
 // moment the chip reads one contiguous window of NT KiB per k-step instead of thousands of streams
 // a whole matrix row apart -- DRAM pages stay open.
 __host__ __device__ inline size_t wfrag_offset(int r, int k, int NT) {
-    int rt = r >> 4, rl = r & 15, ks = k >> 5, kk = k & 31;
-    return ((size_t)ks * NT + rt) * 512 + (size_t)(((kk >> 3) << 4) + rl) * 8 + (kk & 7);
+    int rt = r >> 5, rl = r & 31, ks = k >> 4, kk = k & 15;
+    return ((size_t)ks * NT + rt) * 512 + (size_t)(((kk >> 3) << 5) + rl) * 8 + (kk & 7);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -183,8 +184,6 @@ int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int3
 // gemm.hip:  out = X[T, K] * W[N, K]^T
 enum { SLED_EPI_PARTIAL = 0, SLED_EPI_SWIGLU = 1, SLED_EPI_STORE = 2 };
 struct sled_gemm_plan {
-    int nw;      // 16-column tiles per wavefront
-    int kc;      // k-steps of 32 per pipeline stage
     int split;   // K slices
 };
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
