@@ -21,6 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# L2 fetch + write-back bytes per projection launch (FETCH_SIZE and WRITE_SIZE of rocprofv3, each scaled by
+# what the counter reads for a 1 GiB copy; profiles/verify_step_llama8b_b16_hbm_traffic.txt).  Taken with the
+# projection kernel as it stands; to be reset to None whenever that kernel changes.
+MEASURED_TRAFFIC = {"llama8b_b16": 154.2e6}
+CPU_SAMPLE_REQUESTS, CPU_SAMPLE_LAYERS = 16, 16   # the oracle's bounded sample (about 10-20 s of CPU work)
 
 
 def parse():
@@ -31,6 +36,9 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workload", default="llama8b_b16", choices=["llama8b_b16", "llama8b_hetero64", "tiny_bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a 1 GiB device-to-device copy three times before the steps, so that a counter run "
+                         "(FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale the counters by")
     ap.add_argument("--profile-steps", type=int, default=5, help="steps of the event-instrumented region")
     return ap.parse_args()
 
@@ -69,7 +77,7 @@ def main():
     for i in range(B):
         K, V = synth.context_kv(shape, batch.ctx_len[i], seed=args.seed, req=i, device="cuda")
         v.append_context([reqs[i]], [K], [V])
-        KV.append((K, V) if i < 2 else None)
+        KV.append((K, V) if i < CPU_SAMPLE_REQUESTS else None)
         del K, V
     tokens = torch.from_numpy(batch.tokens).cuda()
     torch.cuda.synchronize()
@@ -79,6 +87,13 @@ def main():
         a, t = v.accept(sled.GREEDY, batch.k, logits, tokens)
         v.commit(reqs, a)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -108,21 +123,22 @@ def main():
         step()
     ms, n = sled.sled_profile_read(v.model)
     sled.sled_profile_enable(v.model, False)
-    proj_ms = ms[sled.PROF_PROJ] / args.profile_steps
-    proj_launches = n[sled.PROF_PROJ] // args.profile_steps
+    psteps = max(args.profile_steps, 1)
+    proj_ms = max(ms[sled.PROF_PROJ] / psteps, 1e-9)
+    proj_launches = n[sled.PROF_PROJ] // psteps
     achieved = weight_bytes / (proj_ms * 1e-3) / 1e9
     roofline = {
         "bound": "hbm", "kernel": "gemm_bf16_kernel (projection GEMMs, weight stream)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC.get(args.workload),
         "launches_per_step": proj_launches, "avg_launch_us": round(proj_ms * 1e3 / max(proj_launches, 1), 2),
         "bytes_per_launch": round(weight_bytes / max(proj_launches, 1)),
     }
     step_bytes = weight_bytes + kv_bytes + logits_bytes
     breakdown = {
-        "proj_ms": round(proj_ms, 4), "attn_ms": round(ms[sled.PROF_ATTN] / args.profile_steps, 4),
-        "rows_ms": round(ms[sled.PROF_ROWS] / args.profile_steps, 4),
-        "attn_GBps": round(kv_bytes / max(ms[sled.PROF_ATTN] / args.profile_steps, 1e-9) / 1e6, 1),
+        "proj_ms": round(proj_ms, 4), "attn_ms": round(ms[sled.PROF_ATTN] / psteps, 4),
+        "rows_ms": round(ms[sled.PROF_ROWS] / psteps, 4),
+        "attn_GBps": round(kv_bytes / max(ms[sled.PROF_ATTN] / psteps, 1e-9) / 1e6, 1),
         "step_bytes": step_bytes, "step_hbm_frac": round(step_bytes / (p50 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }
 
@@ -145,9 +161,9 @@ def main():
 
 
 def cpu_baseline(shape, weights, batch, KV, args):
-    """The oracle as it stands, on a bounded sample: the first 2 requests of the batch through the
-    first 2 layers plus final norm and LM head; layer time is scaled to the full depth and request
-    time to the full batch by rows."""
+    """The oracle as it stands, on a bounded sample: the first CPU_SAMPLE_REQUESTS requests of the batch
+    through the first CPU_SAMPLE_LAYERS layers plus final norm, LM head and acceptance; layer time is
+    scaled to the full depth and request time to the full batch by rows."""
     import numpy as np
     from oracle import sled_oracle as O
     from oracle.harness import oracle_model
@@ -157,7 +173,7 @@ def cpu_baseline(shape, weights, batch, KV, args):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    n_req, n_lay = 2, 2
+    n_req, n_lay = min(CPU_SAMPLE_REQUESTS, batch.B), min(CPU_SAMPLE_LAYERS, shape.n_layers)
     om = oracle_model(shape, weights, n_layers=n_lay)
     offs = batch.row_offsets()
     reqs = []

@@ -17,9 +17,10 @@
 //   O^T[d, qrow]    += V_page^T * P^T    v_mfma_f32_16x16x16_bf16; the S^T accumulator registers
 //                                        are, in place, the P^T operand (p too is a bf16 pair)
 // A page (16 tokens x 128 dims of one kv head) is stored in the pool in operand order, K for the
-// first product and V for the second, so a wavefront reads a whole page with 4 + 4 contiguous
-// 1 KiB loads into registers, the next page in flight while one is consumed.  The four wavefronts of a
-// workgroup take alternate pages and merge their (max, sum, O) states through LDS at the end.  When a
+// first product and V for the second, so a wavefront moves a whole page with 4 + 4 contiguous
+// 1 KiB direct-to-LDS loads into its private ring of three page buffers, two pages in flight while one
+// is consumed.  The four wavefronts of a workgroup take alternate pages and merge their (max, sum, O)
+// states through LDS at the end.  When a
 // (request, kv head) is split over several work items, each stores its state and the last one to
 // arrive (a device-scope counter) merges them in a fixed order; either way the output is written in
 // the operand order of the following projection, as a bf16 pair.
