@@ -84,6 +84,20 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
     int jrow[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) jrow[qt] = (qt * 16 + lq) / G;
+    // every wavefront keeps the whole Q operand in registers (one wavefront per SIMD owns the full
+    // register file): the main loop's LDS traffic is then the K/V pages alone
+    // (up to 48 query rows; larger tiles would spill and keep reading Q from LDS)
+    constexpr bool Q_IN_REGS = QT <= 3;
+    bf16x8_t qreg[2][Q_IN_REGS ? QT : 1][4];
+    if (Q_IN_REGS) {
+#pragma unroll
+        for (int pl = 0; pl < 2; pl++)
+#pragma unroll
+            for (int qt = 0; qt < QT; qt++)
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++)
+                    qreg[pl][qt][ks] = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)((pl * QT + qt) * 4 + ks) * 64 + lane) * 8);
+    }
 
     float m[QT], lsum[QT];
     float4_t o[QT][8];
@@ -137,8 +151,14 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
             float4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ks++) {
-                const bf16x8_t qh = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)(qt * 4 + ks) * 64 + lane) * 8);
-                const bf16x8_t ql = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)((QT + qt) * 4 + ks) * 64 + lane) * 8);
+                bf16x8_t qh, ql;
+                if (Q_IN_REGS) {
+                    qh = qreg[0][qt][ks];
+                    ql = qreg[1][qt][ks];
+                } else {
+                    qh = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)(qt * 4 + ks) * 64 + lane) * 8);
+                    ql = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)((QT + qt) * 4 + ks) * 64 + lane) * 8);
+                }
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pr.kf[ks], qh, s, 0, 0, 0);
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pr.kf[ks], ql, s, 0, 0, 0);
             }
@@ -158,19 +178,30 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
             // rescale is an exact power of two and the rounding of p does not depend on the order in
             // which pages are visited: bf16(2^(s-M)) * 2^(M-M') == bf16(2^(s-M')).
             const float mnew = fmaxf(m[qt], ceilf(mloc));
-            const float alpha = exp2f(m[qt] - mnew);
+            // the reference moves only on whole numbers, so after the first pages it rarely moves at all:
+            // the O accumulators are rescaled only when some row of the tile needs it (wave-uniform test)
+            const bool rescale = __builtin_amdgcn_ballot_w64(mnew != m[qt]) != 0ull;
+            // arguments are <= 0: the bare hardware exponential is enough (results below 2^-126 flush to 0)
+            const float alpha = __builtin_amdgcn_exp2f(m[qt] - mnew);
             float psum = 0.f;
             short4_t ph, pl;  // p as a bf16 pair
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const float p = exp2f(sv[i] - mnew);
+                const float p = __builtin_amdgcn_exp2f(sv[i] - mnew);
                 psum += p;
-                const bf16_t hi = f32_to_bf16(p);
-                ph[i] = (short)hi;
-                pl[i] = (short)f32_to_bf16(p - bf16_to_f32(hi));
+                const __bf16 hi = (__bf16)p;  // round to nearest even, in hardware
+                const __bf16 lo = (__bf16)(p - (float)hi);
+                ph[i] = __builtin_bit_cast(short, hi);
+                pl[i] = __builtin_bit_cast(short, lo);
             }
             lsum[qt] = lsum[qt] * alpha + psum;
             m[qt] = mnew;
+            if (rescale) {
+#pragma unroll
+                for (int dt = 0; dt < 8; dt++)
+#pragma unroll
+                    for (int i = 0; i < 4; i++) o[qt][dt][i] *= alpha;
+            }
 #pragma unroll
             for (int dt = 0; dt < 8; dt++) {
                 // V operand for dims dt*16 .. dt*16+15: half of the 16-byte chunk vraw[dt/2]
@@ -182,8 +213,6 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
                 va[2] = (short)(hi & 0xffff);
                 va[3] = (short)(hi >> 16);
                 float4_t acc = o[qt][dt];
-#pragma unroll
-                for (int i = 0; i < 4; i++) acc[i] *= alpha;
                 acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, ph, acc, 0, 0, 0);
                 o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pl, acc, 0, 0, 0);
             }
