@@ -68,9 +68,10 @@ __device__ __forceinline__ void wait_loads(u32x4_t& a, u32x4_t& b) {
 template <int MT, int EPI>
 __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
                                                                const bf16_t* __restrict__ Wp, int NT, int KS,
-                                                               int ks_per_split, int T, int T_pad, int N,
-                                                               float* __restrict__ out, bf16_t* __restrict__ out_act,
-                                                               size_t act_plane, int F_act) {
+                                                               int ks_per_split, int n_col, int n_split, int n_zb,
+                                                               int T, int T_pad, int N, float* __restrict__ out,
+                                                               bf16_t* __restrict__ out_act, size_t act_plane,
+                                                               int F_act) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int STAGE_TILES = PLANES * MT * KG;  // 1 KiB operand tiles per stage, ordered [plane][row tile][k-step]
     constexpr int MY_TILES = STAGE_TILES / WAVES;  // = MT: tiles of a stage this wavefront fetches
@@ -80,9 +81,23 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     static_assert(PER_ITER * DEPTH < 64, "too many loads in flight for the counter");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int cg = wv & (CG - 1), kgi = wv / CG;
-    const int ks_begin = blockIdx.y * ks_per_split;
+    // Workgroup -> (column block bx, K slice by, row block bz).  Workgroups go to the eight XCDs round
+    // robin by their linear index, and each XCD has its own L2.  The row blocks of one weight tile
+    // stream the same weight bytes, so they are given consecutive slots of ONE XCD: they run side by
+    // side there and all but the first find the weights in that L2 instead of fetching them from HBM
+    // again.  Weight tile t = by * n_col + bx lives on XCD t % 8.
+    int bx, by, bz;
+    {
+        const int w = blockIdx.x, xcd = w & 7, local = w >> 3;
+        bz = local % n_zb;
+        const int t = (local / n_zb) * 8 + xcd;
+        if (t >= n_col * n_split) return;  // the grid is rounded up to whole rounds of eight tiles
+        bx = t % n_col;
+        by = t / n_col;
+    }
+    const int ks_begin = by * ks_per_split;
     const int n_stage = ks_per_split / KG;  // a positive multiple of NBUF (the host picks K slices accordingly)
-    const int mt_base = blockIdx.z * MT;    // first 32-row tile handled by this block
+    const int mt_base = bz * MT;            // first 32-row tile handled by this block
 
     // ---- activations: this wavefront's tiles of stage 0 and where they land in a stage buffer -----
     const int row_lim = (T + 7) & ~7;
@@ -113,7 +128,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     };
 
     // ---- weights: NW tiles per stage, straight into registers ------------------------------------------
-    const int nt0 = (blockIdx.x * CG + cg) * NW;
+    const int nt0 = (bx * CG + cg) * NW;
     bool nt_ok[NW];
     const bf16_t* wsrc[NW];
 #pragma unroll
@@ -285,7 +300,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
                 const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
                 const float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
                 if (EPI == SLED_EPI_PARTIAL) {
-                    if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)blockIdx.y * T_pad + tok) * N + n) = v;
+                    if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)by * T_pad + tok) * N + n) = v;
                 } else if (EPI == SLED_EPI_STORE) {
                     if (tok < T) *reinterpret_cast<float4_t*>(out + (size_t)tok * N + n) = v;
                 } else {  // SwiGLU: columns are (gate f, up f, gate f+1, up f+1)
@@ -349,7 +364,7 @@ struct gemm_args {
     const bf16_t* X;
     size_t x_plane;
     const bf16_t* W;
-    int NT, KS, kps, T, T_pad, N;
+    int NT, KS, kps, n_col, n_split, n_zb, T, T_pad, N;
     float* out;
     bf16_t* out_act;
     size_t act_plane;
@@ -365,8 +380,8 @@ int launch_one(const gemm_args& a) {
         SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
     }
-    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.T, a.T_pad,
-                       a.N, a.out, a.out_act, a.act_plane, a.F_act);
+    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.n_col,
+                       a.n_split, a.n_zb, a.T, a.T_pad, a.N, a.out, a.out_act, a.act_plane, a.F_act);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
@@ -433,7 +448,10 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         const int zb = (mt_total + 3) / 4;
         const int MT = (mt_total + zb - 1) / zb;
         gemm_args a;
-        a.grid = dim3((NT + CG * NW - 1) / (CG * NW), plan.split, (mt_total + MT - 1) / MT);
+        a.n_col = (NT + CG * NW - 1) / (CG * NW);
+        a.n_split = plan.split;
+        a.n_zb = (mt_total + MT - 1) / MT;
+        a.grid = dim3((a.n_col * a.n_split + 7) / 8 * 8 * a.n_zb, 1, 1);
         a.lds = (size_t)NXB * PLANES * MT * KG * 1024;  // also holds the MT * 32 KiB of the final reduction
         a.st = st;
         a.X = static_cast<const bf16_t*>(X);

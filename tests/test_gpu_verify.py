@@ -127,7 +127,8 @@ BF16_CASES = [
     # ctx_len, k   (contexts off the page size, shorter than a page, empty; k from 0 to k_max)
     ([64, 64, 64, 64], [4, 4, 4, 4]),
     ([0, 5, 16, 17, 130, 257, 1000], [8, 0, 3, 8, 1, 7, 8]),
-    ([300] * 20, [2, 4, 6, 8] * 5),           # more than 128 packed rows: two row blocks in the GEMMs
+    ([300] * 20, [2, 4, 6, 8] * 5),           # 120 packed rows: one full row block of the projections
+    ([200, 40, 333] * 15, [8, 7, 8] * 15),    # 405 packed rows: four row blocks sharing each weight tile, the last one ragged
 ]
 
 
