@@ -34,7 +34,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--workload", default="llama8b_b16", choices=["llama8b_b16", "llama8b_hetero64", "tiny_bf16"])
+    ap.add_argument("--workload", default="llama8b_b16", choices=["llama8b_b16", "llama8b_hetero64", "llama70b_b32", "tiny_bf16"],
+                    help="llama8b_b16 is the headline configuration; hetero64 uses sampling acceptance over "
+                         "full-vocabulary draft probabilities, the others greedy")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy three times before the steps, so that a counter run "
@@ -63,6 +65,8 @@ def main():
         shape, kind = synth.SHAPES["llama8b"], "b16"
     elif args.workload == "llama8b_hetero64":
         shape, kind = synth.SHAPES["llama8b"], "hetero64"
+    elif args.workload == "llama70b_b32":
+        shape, kind = synth.SHAPES["llama70b"], "b32"
     else:
         shape, kind = synth.SHAPES["tiny_bf16"], "b16"
     batch = synth.draw_batch(kind, shape.vocab, seed=args.seed)
@@ -82,9 +86,19 @@ def main():
     tokens = torch.from_numpy(batch.tokens).cuda()
     torch.cuda.synchronize()
 
+    sampling = kind == "hetero64"
+    if sampling:
+        # draft probabilities softmax(target-shaped logits + N(0,1) noise) over the full vocabulary, uniforms
+        q = synth.draft_probs(n_drafts, shape.vocab, 1.0, seed=args.seed + 3, device="cuda", base_std=1.28)
+        u_acc = synth.uniforms(n_drafts, seed=args.seed + 4, device="cuda")
+        u_smp = synth.uniforms(B, seed=args.seed + 5, device="cuda")
+
     def step():
         logits = v.verify(reqs, batch.k, tokens)
-        a, t = v.accept(sled.GREEDY, batch.k, logits, tokens)
+        if sampling:
+            a, t = v.accept(sled.SAMPLE, batch.k, logits, tokens, q, u_acc, u_smp)
+        else:
+            a, t = v.accept(sled.GREEDY, batch.k, logits, tokens)
         v.commit(reqs, a)
 
     if args.copy_calibration:
@@ -153,7 +167,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers d={shape.d_model} Hq/Hkv={shape.n_q_heads}/"
                                f"{shape.n_kv_heads} F={shape.d_ffn} V={shape.vocab}, B={B}, T={T} packed rows, "
-                               f"{n_drafts} draft tokens, {sum(lens)} context tokens, greedy acceptance, seed {args.seed}"},
+                               f"{n_drafts} draft tokens, {sum(lens)} context tokens, {'sampling' if sampling else 'greedy'} acceptance, "
+                               f"seed {args.seed}"},
         "roofline": roofline, "breakdown": breakdown, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -173,7 +188,9 @@ def cpu_baseline(shape, weights, batch, KV, args):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    n_req, n_lay = min(CPU_SAMPLE_REQUESTS, batch.B), min(CPU_SAMPLE_LAYERS, shape.n_layers)
+    n_req = min(CPU_SAMPLE_REQUESTS, batch.B)
+    # the oracle widens the sampled layers to float64: keep that under about 40 GB of host memory
+    n_lay = max(1, min(CPU_SAMPLE_LAYERS, shape.n_layers, int(40e9 // (shape.layer_params() * 8))))
     om = oracle_model(shape, weights, n_layers=n_lay)
     offs = batch.row_offsets()
     reqs = []
