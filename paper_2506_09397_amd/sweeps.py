@@ -1,0 +1,117 @@
+"""Measurement sweeps around the batched verify step (one MI355X, synthetic inputs, through the C ABI).
+
+    python -m paper_2506_09397_amd.sweeps batch     # step latency vs batch size and speculative length
+    python -m paper_2506_09397_amd.sweeps rows      # projection time vs number of packed rows (MFMA regime)
+
+`batch` is the one-GPU analogue of the paper's throughput-versus-batch-size curve (Sec. 5) and of its
+study of the speculative length: Llama-3-8B shape, contexts uniform in [512, 2048], every request
+with the same k.  `rows` packs many short requests (16 context tokens, k = 8) so that attention is
+negligible and reads the time of the projection kernels from the library's timing hooks:
+useful FLOP = 2 * rows * streamed parameters.
+"""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import torch
+
+from . import sled, synth
+from .runtime import Verifier
+
+MFMA_PEAK_BF16 = 2.5e15
+
+
+def _time_steps(v, reqs, k, tokens, steps=8, warmup=2, profile=False):
+    def step():
+        logits = v.verify(reqs, k, tokens)
+        a, t = v.accept(sled.GREEDY, k, logits, tokens)
+        v.commit(reqs, a)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for s in range(steps):
+        step()
+        ev[s + 1].record()
+    torch.cuda.synchronize()
+    lat = sorted(ev[s].elapsed_time(ev[s + 1]) for s in range(steps))
+    out = {"p50_ms": lat[len(lat) // 2]}
+    if profile:
+        sled.sled_profile_enable(v.model, True)
+        for _ in range(3):
+            step()
+        ms, n = sled.sled_profile_read(v.model)
+        sled.sled_profile_enable(v.model, False)
+        out["proj_ms"] = ms[sled.PROF_PROJ] / 3
+        out["attn_ms"] = ms[sled.PROF_ATTN] / 3
+    return out
+
+
+def batch_sweep(seed=0):
+    shape = synth.SHAPES["llama8b"]
+    weights = synth.SynthWeights(shape, seed=seed, device="cuda")
+    rng = np.random.default_rng(seed)
+    ctx_all = rng.integers(512, 2049, size=64).tolist()
+    print(f"{'B':>3s} {'k':>2s} {'T':>4s} {'ctx tokens':>10s} {'p50 ms':>8s} {'verified draft tok/s':>21s} {'HBM frac':>9s}")
+    for B in (1, 2, 4, 8, 16, 32, 64):
+        ctx = ctx_all[:B]
+        budget = sum(ctx) + B * 9 * 16
+        v = Verifier(shape, weights, budget // 16 + 2 * B + 8, B, B, budget)
+        reqs = [v.open() for _ in range(B)]
+        for i in range(B):
+            K, V = synth.context_kv(shape, ctx[i], seed=seed, req=i, device="cuda")
+            v.append_context([reqs[i]], [K], [V])
+        for k1 in (2, 4, 8):
+            k = [k1] * B
+            T = B * (k1 + 1)
+            tokens = torch.from_numpy(rng.integers(0, shape.vocab, size=T).astype(np.int32)).cuda()
+            r = _time_steps(v, reqs, k, tokens)
+            lens = v.lengths(reqs)
+            step_bytes = shape.streamed_params() * 2 + sum(lens) * shape.kv_bytes_per_token() + T * shape.vocab * 4
+            print(f"{B:3d} {k1:2d} {T:4d} {sum(lens):10d} {r['p50_ms']:8.3f} {B * k1 / (r['p50_ms'] * 1e-3):21.0f} "
+                  f"{step_bytes / (r['p50_ms'] * 1e-3) / 8e12:9.3f}")
+        v.destroy()
+
+
+def rows_sweep(seed=0):
+    shape = synth.SHAPES["llama8b"]
+    weights = synth.SynthWeights(shape, seed=seed, device="cuda")
+    rng = np.random.default_rng(seed)
+    flop_per_row = 2.0 * shape.streamed_params()
+    print(f"{'rows':>5s} {'p50 ms':>8s} {'proj ms':>8s} {'useful TFLOP/s':>15s} {'of bf16 MFMA peak':>18s} {'weight GB/s':>12s}")
+    for T in (128, 256, 512, 1024, 2048, 4096):
+        B = (T + 8) // 9
+        k = [8] * B
+        k[-1] = T - 9 * (B - 1) - 1
+        if k[-1] < 0:
+            B -= 1
+            k = [8] * B
+        T_real = sum(k) + B
+        ctx = [16] * B
+        budget = sum(ctx) + B * 9 * 16
+        v = Verifier(shape, weights, budget // 16 + 2 * B + 8, B, B, budget)
+        reqs = [v.open() for _ in range(B)]
+        K, V = synth.context_kv(shape, 16, seed=seed, req=0, device="cuda")
+        for i in range(B):
+            v.append_context([reqs[i]], [K], [V])
+        tokens = torch.from_numpy(rng.integers(0, shape.vocab, size=T_real).astype(np.int32)).cuda()
+        r = _time_steps(v, reqs, k, tokens, steps=4, warmup=1, profile=True)
+        tf = flop_per_row * T_real / (r["proj_ms"] * 1e-3)
+        print(f"{T_real:5d} {r['p50_ms']:8.3f} {r['proj_ms']:8.3f} {tf / 1e12:15.1f} {tf / MFMA_PEAK_BF16:18.3f} "
+              f"{shape.streamed_params() * 2 / (r['proj_ms'] * 1e-3) / 1e9:12.0f}")
+        v.destroy()
+
+
+if __name__ == "__main__":
+    sled.lib()
+    torch.cuda.set_device(0)
+    which = sys.argv[1] if len(sys.argv) > 1 else ""
+    if which == "batch":
+        batch_sweep()
+    elif which == "rows":
+        rows_sweep()
+    else:
+        print(__doc__)
+        sys.exit(2)
