@@ -17,13 +17,14 @@
 //   O^T[d, qrow]    += V_page^T * P^T    v_mfma_f32_16x16x16_bf16; the S^T accumulator registers
 //                                        are, in place, the P^T operand (p too is a bf16 pair)
 // A page (16 tokens x 128 dims of one kv head) is stored in the pool in operand order, K for the
-// first product and V for the second, so a wavefront moves a whole page with 4 + 4 contiguous
-// 1 KiB direct-to-LDS loads into its private ring of three page buffers, two pages in flight while one
-// is consumed.  The four wavefronts of a workgroup take alternate pages and merge their (max, sum, O)
-// states through LDS at the end.  When a
-// (request, kv head) is split over several work items, each stores its state and the last one to
-// arrive (a device-scope counter) merges them in a fixed order; either way the output is written in
-// the operand order of the following projection, as a bf16 pair.
+// first product and V for the second, so a page moves with 4 + 4 contiguous 1 KiB direct-to-LDS loads.
+// A workgroup is NPG page groups of QT consumer wavefronts and one producer wavefront: the producer
+// streams every NPG-th page of the work item through the group's ring of three LDS page buffers (two
+// pages in flight), and each consumer computes one tile of 16 query rows against the page.  One
+// barrier per round keeps the groups in step.  At the end the groups' (max, sum, O) states are folded
+// through LDS.  When a (request, kv head) is split over several work items, each stores its state and
+// the last one to arrive (a device-scope counter) merges them in a fixed order; either way the
+// output is written in the operand order of the following projection, as a bf16 pair.
 //
 // fp32 kernel (fp32 models): one wavefront per (row, query head), lanes over keys.
 #include "sled_internal.h"
@@ -32,24 +33,25 @@ namespace {
 
 constexpr float NEG_BIG = -1.0e30f;
 
-constexpr int ATTN_WAVES = 4;  // wavefronts per workgroup: one per SIMD, each with the whole register file
+// Wavefronts of a workgroup: NPG page groups x (QT consumers + 1 producer).  Page group p takes the
+// pages page0 + p, + NPG, ... of the work item; its consumer qt owns the 16 query rows of tile qt, its
+// producer does nothing but move the group's pages into LDS.  Several wavefronts per SIMD hide each
+// other's dependent chains (S^T -> softmax -> O^T); the producer is separate because a wavefront
+// issues in order and a direct-to-LDS load can hold the issue slot for a couple of hundred clocks.
+__host__ __device__ constexpr int attn_groups(int QT) { return QT <= 3 ? 4 : (QT == 4 ? 3 : 2); }
+constexpr int ATTN_RING = 3;  // page buffers per page group: the one being read and two in flight
 
-// LDS merge slots: floats per slot = O tile + max + sum
-__host__ __device__ constexpr int attn_slot_floats(int QT) { return QT * 8 * 64 * 4 + 2 * QT * 16; }
-__host__ __device__ constexpr int attn_slots(int QT) { return QT <= 5 ? 2 : 1; }
+// floats of one parked state in LDS: O tile [8][64 lanes][4] + max[16] + sum[16]
+constexpr int ATTN_PARK_F = 8 * 64 * 4 + 32;
 
 template <int QT>
-__global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bf16_kernel(
+__global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_kernel(
     sled_step_meta meta, const int32_t* __restrict__ len_dev, const bf16_t* __restrict__ Q, size_t q_plane,
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int64_t n_pages, int layer, int Hq, int Hkv,
     float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml, int32_t* __restrict__ arrive,
     bf16_t* __restrict__ X, size_t x_plane) {
-    constexpr int D = 128;
+    constexpr int D = 128, NPG = attn_groups(QT), RING = ATTN_RING;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // main loop: Q operand tiles [2 planes][QT][4 k-steps][64 lanes][8] (the size of one O tile);
-    // afterwards the same bytes serve as merge slots
-    bf16_t* sh_q = reinterpret_cast<bf16_t*>(smem);
-    float* sh_f = reinterpret_cast<float*>(smem);
     __shared__ int sh_last;
 
     const int w = blockIdx.x;
@@ -57,6 +59,8 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
     const int page0 = meta.work[4 * w + 2], npg = meta.work[4 * w + 3];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: page ids are then fetched by scalar loads
+    const bool producer = wv >= NPG * QT;
+    const int pgid = producer ? wv - NPG * QT : wv / QT, qt = producer ? 0 : wv - pgid * QT;
     const int G = Hq / Hkv;
     const int L = len_dev[meta.req_id[b]];
     const int n = meta.k[b] + 1;
@@ -67,56 +71,36 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
     const int32_t* pages = meta.pages + meta.cu_pages[b];
     const int lq = lane & 15, lg = lane >> 4;
 
-    // Q operand tiles, both planes of the bf16 pair: qrow r = qt*16 + l%16 -> (query position
-    // j = r / G, head g*G + r % G); element k = ks*32 + (l/16)*8 ..+8
-    for (int e = tid; e < 2 * QT * 4 * 64; e += 64 * ATTN_WAVES) {
-        const int l = e & 63, ks = (e >> 6) & 3, qt = (e >> 8) % QT, pl = e / (QT * 256);
-        const int r = qt * 16 + (l & 15);
-        uint4 val = make_uint4(0u, 0u, 0u, 0u);
-        if (r < rows) {
-            const int j = r / G, hh = r - j * G;
-            val = *reinterpret_cast<const uint4*>(Q + pl * q_plane + ((size_t)(row0 + j) * Hq + g * G + hh) * D + ks * 32 +
-                                                  (l >> 4) * 8);
-        }
-        *reinterpret_cast<uint4*>(sh_q + (size_t)e * 8) = val;
-    }
-    __syncthreads();
-    int jrow[QT];
-#pragma unroll
-    for (int qt = 0; qt < QT; qt++) jrow[qt] = (qt * 16 + lq) / G;
-    // every wavefront keeps the whole Q operand in registers (one wavefront per SIMD owns the full
-    // register file): the main loop's LDS traffic is then the K/V pages alone
-    // (up to 48 query rows; larger tiles would spill and keep reading Q from LDS)
-    constexpr bool Q_IN_REGS = QT <= 3;
-    bf16x8_t qreg[2][Q_IN_REGS ? QT : 1][4];
-    if (Q_IN_REGS) {
+    // Q operand of this wavefront's tile, both planes of the bf16 pair, straight into registers:
+    // qrow r = qt*16 + l%16 -> (query position j = r / G, head g*G + r % G); element k = ks*32 + (l/16)*8 ..+8
+    const int r_mine = qt * 16 + lq;
+    const int jrow = r_mine / G;
+    bf16x8_t qf[2][4];
+    {
+        const int hh = r_mine - jrow * G;
 #pragma unroll
         for (int pl = 0; pl < 2; pl++)
 #pragma unroll
-            for (int qt = 0; qt < QT; qt++)
-#pragma unroll
-                for (int ks = 0; ks < 4; ks++)
-                    qreg[pl][qt][ks] = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)((pl * QT + qt) * 4 + ks) * 64 + lane) * 8);
+            for (int ks = 0; ks < 4; ks++) {
+                uint4 val = make_uint4(0u, 0u, 0u, 0u);
+                if (!producer && r_mine < rows)
+                    val = *reinterpret_cast<const uint4*>(Q + pl * q_plane + ((size_t)(row0 + jrow) * Hq + g * G + hh) * D +
+                                                          ks * 32 + lg * 8);
+                qf[pl][ks] = __builtin_bit_cast(bf16x8_t, val);
+            }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the hand-counted waits below start from an empty queue
 
-    float m[QT], lsum[QT];
-    float4_t o[QT][8];
+    float m = NEG_BIG, lsum = 0.f;
+    float4_t o[8];
 #pragma unroll
-    for (int qt = 0; qt < QT; qt++) {
-        m[qt] = NEG_BIG;
-        lsum[qt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < 8; dt++) o[qt][dt] = float4_t{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int dt = 0; dt < 8; dt++) o[dt] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    // K/V pages go from HBM straight into a private LDS ring of this wavefront (RING pages of 8 KiB:
-    // the one being consumed and the ones in flight) with direct-to-LDS loads: 4 + 4 loads of 1 KiB
-    // per page, lane l's 16 bytes landing at base + 16*l, i.e. the page keeps its operand order.
-    // The loads are issued from inline assembly and waited for by hand: they are the only
-    // vector-memory operations of the main loop, loads retire in order, so "at most 8*n
-    // outstanding" means every page but the last n issued has landed.
-    constexpr int RING = 3;
-    bf16_t* ring = sh_q + (size_t)QT * 4096 + (size_t)wv * RING * 4096;  // after the Q tiles
+    // K/V pages go from HBM straight into the page group's LDS ring (RING pages of 8 KiB) with
+    // direct-to-LDS loads: 4 + 4 loads of 1 KiB per page, lane l's 16 bytes landing at base + 16*l,
+    // i.e. the page keeps its operand order.  The loads are issued from inline assembly and waited for
+    // by hand: they are this wavefront's only vector-memory operations in the main loop.
+    bf16_t* ring = reinterpret_cast<bf16_t*>(smem) + (size_t)pgid * RING * 4096;
     const unsigned ring_lds = (unsigned)(size_t)(__attribute__((address_space(3))) void*)ring;
     auto load_page = [&](int slot, int pg) {
         // page ids come through the constant address space: uniform index, so a scalar load that does
@@ -132,249 +116,232 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) __attribute__((amdgpu_waves_per_eu
             asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gp), "s"(dst) : "memory");
         }
     };
-    struct page_regs {
+    auto process = [&](int slot, int pg) {
         bf16x8_t kf[4];
         uint4 vraw[4];
-    };
-    auto process = [&](int slot, int pg) {
-        page_regs pr;
         {
             const bf16_t* pb = ring + (size_t)slot * 4096 + lane * 8;
 #pragma unroll
-            for (int c = 0; c < 4; c++) pr.kf[c] = *reinterpret_cast<const bf16x8_t*>(pb + c * 512);
+            for (int c = 0; c < 4; c++) kf[c] = *reinterpret_cast<const bf16x8_t*>(pb + c * 512);
 #pragma unroll
-            for (int c = 0; c < 4; c++) pr.vraw[c] = *reinterpret_cast<const uint4*>(pb + 2048 + c * 512);
+            for (int c = 0; c < 4; c++) vraw[c] = *reinterpret_cast<const uint4*>(pb + 2048 + c * 512);
         }
         const bool need_mask = (pg * 16 + 15) > L;  // page reaches beyond the context: causal part / tail
+        float4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            float4_t s = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < 4; ks++) {
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[0][ks], s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[1][ks], s, 0, 0, 0);
+        }
+        float sv[4];
 #pragma unroll
-            for (int ks = 0; ks < 4; ks++) {
-                bf16x8_t qh, ql;
-                if (Q_IN_REGS) {
-                    qh = qreg[0][qt][ks];
-                    ql = qreg[1][qt][ks];
-                } else {
-                    qh = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)(qt * 4 + ks) * 64 + lane) * 8);
-                    ql = *reinterpret_cast<const bf16x8_t*>(sh_q + ((size_t)((QT + qt) * 4 + ks) * 64 + lane) * 8);
-                }
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pr.kf[ks], qh, s, 0, 0, 0);
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pr.kf[ks], ql, s, 0, 0, 0);
+        for (int i = 0; i < 4; i++) {
+            sv[i] = s[i] * scale_log2;
+            if (need_mask) {
+                const int tokpos = pg * 16 + lg * 4 + i;
+                if (tokpos > L + jrow) sv[i] = -INFINITY;
             }
-            float sv[4];
+        }
+        float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        // The running reference is kept on whole numbers (scores are in log2 units), so every
+        // rescale is an exact power of two and the rounding of p does not depend on the order in
+        // which pages are visited: bf16(2^(s-M)) * 2^(M-M') == bf16(2^(s-M')).
+        const float mnew = fmaxf(m, ceilf(mloc));
+        // the reference moves only on whole numbers, so after the first pages it rarely moves at all:
+        // the O accumulators are rescaled only when some row of the tile needs it (wave-uniform test)
+        const bool rescale = __builtin_amdgcn_ballot_w64(mnew != m) != 0ull;
+        // arguments are <= 0: the bare hardware exponential is enough (results below 2^-126 flush to 0)
+        const float alpha = __builtin_amdgcn_exp2f(m - mnew);
+        float psum = 0.f;
+        short4_t ph, pl;  // p as a bf16 pair
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                sv[i] = s[i] * scale_log2;
-                if (need_mask) {
-                    const int tokpos = pg * 16 + lg * 4 + i;
-                    if (tokpos > L + jrow[qt]) sv[i] = -INFINITY;
-                }
-            }
-            float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            // The running reference is kept on whole numbers (scores are in log2 units), so every
-            // rescale is an exact power of two and the rounding of p does not depend on the order in
-            // which pages are visited: bf16(2^(s-M)) * 2^(M-M') == bf16(2^(s-M')).
-            const float mnew = fmaxf(m[qt], ceilf(mloc));
-            // the reference moves only on whole numbers, so after the first pages it rarely moves at all:
-            // the O accumulators are rescaled only when some row of the tile needs it (wave-uniform test)
-            const bool rescale = __builtin_amdgcn_ballot_w64(mnew != m[qt]) != 0ull;
-            // arguments are <= 0: the bare hardware exponential is enough (results below 2^-126 flush to 0)
-            const float alpha = __builtin_amdgcn_exp2f(m[qt] - mnew);
-            float psum = 0.f;
-            short4_t ph, pl;  // p as a bf16 pair
+        for (int i = 0; i < 4; i++) {
+            const float p = __builtin_amdgcn_exp2f(sv[i] - mnew);
+            psum += p;
+            const __bf16 hi = (__bf16)p;  // round to nearest even, in hardware
+            const __bf16 lo = (__bf16)(p - (float)hi);
+            ph[i] = __builtin_bit_cast(short, hi);
+            pl[i] = __builtin_bit_cast(short, lo);
+        }
+        lsum = lsum * alpha + psum;
+        m = mnew;
+        if (rescale) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const float p = __builtin_amdgcn_exp2f(sv[i] - mnew);
-                psum += p;
-                const __bf16 hi = (__bf16)p;  // round to nearest even, in hardware
-                const __bf16 lo = (__bf16)(p - (float)hi);
-                ph[i] = __builtin_bit_cast(short, hi);
-                pl[i] = __builtin_bit_cast(short, lo);
-            }
-            lsum[qt] = lsum[qt] * alpha + psum;
-            m[qt] = mnew;
-            if (rescale) {
+            for (int dt = 0; dt < 8; dt++)
 #pragma unroll
-                for (int dt = 0; dt < 8; dt++)
+                for (int i = 0; i < 4; i++) o[dt][i] *= alpha;
+        }
 #pragma unroll
-                    for (int i = 0; i < 4; i++) o[qt][dt][i] *= alpha;
-            }
-#pragma unroll
-            for (int dt = 0; dt < 8; dt++) {
-                // V operand for dims dt*16 .. dt*16+15: half of the 16-byte chunk vraw[dt/2]
-                const uint4 r4 = pr.vraw[dt >> 1];
-                const uint32_t lo = (dt & 1) ? r4.z : r4.x, hi = (dt & 1) ? r4.w : r4.y;
-                short4_t va;
-                va[0] = (short)(lo & 0xffff);
-                va[1] = (short)(lo >> 16);
-                va[2] = (short)(hi & 0xffff);
-                va[3] = (short)(hi >> 16);
-                float4_t acc = o[qt][dt];
-                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, ph, acc, 0, 0, 0);
-                o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pl, acc, 0, 0, 0);
-            }
+        for (int dt = 0; dt < 8; dt++) {
+            // V operand for dims dt*16 .. dt*16+15: half of the 16-byte chunk vraw[dt/2]
+            const uint4 r4 = vraw[dt >> 1];
+            const uint2 half = (dt & 1) ? make_uint2(r4.z, r4.w) : make_uint2(r4.x, r4.y);
+            const short4_t va = __builtin_bit_cast(short4_t, half);
+            float4_t acc = o[dt];
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, ph, acc, 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, pl, acc, 0, 0, 0);
         }
     };
 
-    // the wavefront's pages page0 + wv, + ATTN_WAVES, ...: two in flight while one is consumed
-    {
-        const int first = page0 + wv;
-        const int n_my = first < page_end ? (page_end - first + ATTN_WAVES - 1) / ATTN_WAVES : 0;
-        if (n_my > 0) load_page(0, first);
-        if (n_my > 1) load_page(1, first + ATTN_WAVES);
-        int slot = 0, slot2 = 2;
-        for (int i = 0; i < n_my; i++) {
-            // slot2 held page i-1, whose LDS reads have been consumed by the arithmetic above
-            if (i + 2 < n_my) {
-                load_page(slot2, first + (i + 2) * ATTN_WAVES);
-                __builtin_amdgcn_s_waitcnt((16 & 15) | (7 << 4) | (15 << 8) | ((16 >> 4) << 14));  // vmcnt(16): page i has landed
-            } else if (i + 1 < n_my) {
-                __builtin_amdgcn_s_waitcnt(8 | (7 << 4) | (15 << 8));
-            } else {
-                __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    // Rounds: in round r page group p works on page page0 + p + r*NPG (if the work item has it).
+    // The group's producer fetches that page two rounds ahead into ring slot r % RING and waits for it
+    // before the barrier that opens round r; after the barrier the consumers may read it -- and they
+    // have all finished round r-1, whose slot the fetch issued right after the barrier (for round r+2)
+    // overwrites.  Loads retire in order: the page of round r+1 has landed once at most the 8 loads of
+    // round r+2 are outstanding.
+    constexpr int PF = RING - 1;
+    const int n_rounds = (page_end - page0 + NPG - 1) / NPG;                  // uniform over the workgroup
+    const int my_rounds = max(0, (page_end - page0 - pgid + NPG - 1) / NPG);  // rounds in which this group has a page
+    auto page_of = [&](int r) { return page0 + pgid + r * NPG; };
+    if (producer) {
+#pragma unroll
+        for (int r = 0; r < PF; r++)
+            if (r < my_rounds) load_page(r % RING, page_of(r));
+        if (my_rounds > 1)
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (int r = 0; r < n_rounds; r++) {
+            __builtin_amdgcn_s_barrier();
+            if (r + PF < my_rounds) load_page((r + PF) % RING, page_of(r + PF));
+            // issued so far: rounds < min(r + PF + 1, my_rounds); the page of round r + 1 is needed next
+            if (r + 1 < my_rounds) {
+                if (r + 2 < my_rounds)
+                    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
+        }
+    } else {
+        for (int r = 0; r < n_rounds; r++) {
+            __builtin_amdgcn_s_waitcnt(7 << 4 | 3 << 14 | 15);  // lgkmcnt(0): this wavefront's LDS reads are back
+            __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            process(slot, first + i * ATTN_WAVES);
+            if (r < my_rounds) process(r % RING, page_of(r));
             asm volatile("" ::: "memory");
-            slot = slot == RING - 1 ? 0 : slot + 1;
-            slot2 = slot2 == RING - 1 ? 0 : slot2 + 1;
         }
     }
-    __syncthreads();  // all wavefronts are done with the Q tiles: the bytes become the merge buffer
+    __syncthreads();  // every page has been consumed, no load is in flight: the rings become the merge buffer
+
     // lane-partial sums -> per-qrow sums
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
+    // page groups 1 .. NPG-1 park their states in LDS; group 0 folds them in, in ascending order
+    // (exact: every rescale is a power of two)
+    float* park = reinterpret_cast<float*>(smem);
+    auto fold = [&](float m2, float l2, auto o2_of) {
+        const float mnew = fmaxf(m, m2);
+        const float a1 = exp2f(m - mnew), a2 = exp2f(m2 - mnew);
+        lsum = lsum * a1 + l2 * a2;
+        m = mnew;
 #pragma unroll
-    for (int qt = 0; qt < QT; qt++) {
-        lsum[qt] += __shfl_xor(lsum[qt], 16);
-        lsum[qt] += __shfl_xor(lsum[qt], 32);
+        for (int dt = 0; dt < 8; dt++) {
+            const float4_t o2 = o2_of(dt);
+#pragma unroll
+            for (int i = 0; i < 4; i++) o[dt][i] = o[dt][i] * a1 + o2[i] * a2;
+        }
+    };
+    if (!producer && pgid > 0) {
+        float* slot = park + (size_t)((pgid - 1) * QT + qt) * ATTN_PARK_F;
+        if (lg == 0) {
+            slot[2048 + lq] = m;
+            slot[2048 + 16 + lq] = lsum;
+        }
+#pragma unroll
+        for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(slot + (dt * 64 + lane) * 4) = o[dt];
     }
-    // merge the wavefronts' states pairwise through LDS: 4 -> 2 -> 1 (exact: every rescale is
-    // a power of two), at most attn_slots(QT) writers at a time
-    auto merge_from = [&](const float* slot) {
-#pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            const float m2 = slot[QT * 2048 + qt * 16 + lq], l2 = slot[QT * 2048 + QT * 16 + qt * 16 + lq];
-            const float mnew = fmaxf(m[qt], m2);
-            const float a1 = exp2f(m[qt] - mnew), a2 = exp2f(m2 - mnew);
-            lsum[qt] = lsum[qt] * a1 + l2 * a2;
-            m[qt] = mnew;
-#pragma unroll
-            for (int dt = 0; dt < 8; dt++) {
-                const float4_t o2 = *reinterpret_cast<const float4_t*>(slot + ((qt * 8 + dt) * 64 + lane) * 4);
-#pragma unroll
-                for (int i = 0; i < 4; i++) o[qt][dt][i] = o[qt][dt][i] * a1 + o2[i] * a2;
-            }
-        }
-    };
-    auto store_to = [&](float* slot) {
-#pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            if (lg == 0) {
-                slot[QT * 2048 + qt * 16 + lq] = m[qt];
-                slot[QT * 2048 + QT * 16 + qt * 16 + lq] = lsum[qt];
-            }
-#pragma unroll
-            for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(slot + ((qt * 8 + dt) * 64 + lane) * 4) = o[qt][dt];
-        }
-    };
-    constexpr int SLOTS = attn_slots(QT), SLOT_F = attn_slot_floats(QT);
-#pragma unroll
-    for (int half = ATTN_WAVES / 2; half >= 1; half >>= 1) {
-        for (int g0 = 0; g0 < half; g0 += SLOTS) {
-            // wavefronts half+g0 .. half+g0+SLOTS-1 hand their state to wavefronts g0 .. g0+SLOTS-1
-            if (wv >= half + g0 && wv < half + g0 + SLOTS && wv < 2 * half) store_to(sh_f + (size_t)(wv - half - g0) * SLOT_F);
-            __syncthreads();
-            if (wv >= g0 && wv < g0 + SLOTS && wv < half) merge_from(sh_f + (size_t)(wv - g0) * SLOT_F);
-            __syncthreads();
+    __syncthreads();
+    if (!producer && pgid == 0) {
+        for (int p2 = 1; p2 < NPG; p2++) {
+            const float* slot = park + (size_t)((p2 - 1) * QT + qt) * ATTN_PARK_F;
+            fold(slot[2048 + lq], slot[2048 + 16 + lq],
+                 [&](int dt) { return *reinterpret_cast<const float4_t*>(slot + (dt * 64 + lane) * 4); });
         }
     }
 
-    // Wavefront 0 now holds the state of work item w.  If the (request, kv head) has several work
-    // items, each stores its state; the one that arrives last merges them all in ascending order
-    // (so the result does not depend on which one that is) and writes the output.
+    // The wavefronts of page group 0 now hold the state of work item w, one query tile each.  If the
+    // (request, kv head) has several work items, each stores its state; the one that arrives last
+    // merges them all in ascending order (so the result does not depend on which one that is) and
+    // writes the output.
     const int bg = b * Hkv + g;
     const int w0 = meta.cu_work[bg], w1 = meta.cu_work[bg + 1];
     const bool single = (w1 - w0) == 1;
+    // Cross-workgroup hand-over without a device-scope fence (which writes back and invalidates a whole
+    // L2 and, with one per workgroup, serialises on each XCD): the partial states are written and read
+    // with device-scope atomic accesses, which go to the memory-side coherence point themselves, and
+    // the arrival counter is bumped only after this workgroup's stores have been acknowledged.
+    auto put = [&](float* q4, const float4_t& v) {  // 16 bytes at q4 as two 8-byte coherent stores
+        const uint2 a = make_uint2(__float_as_uint(v[0]), __float_as_uint(v[1])), c = make_uint2(__float_as_uint(v[2]), __float_as_uint(v[3]));
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(q4), __builtin_bit_cast(unsigned long long, a), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(reinterpret_cast<unsigned long long*>(q4) + 1, __builtin_bit_cast(unsigned long long, c), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto get = [&](const float* q4) {
+        const unsigned long long a = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(q4), __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long c = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(q4) + 1, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+        const uint2 a2 = __builtin_bit_cast(uint2, a), c2 = __builtin_bit_cast(uint2, c);
+        return float4_t{__uint_as_float(a2.x), __uint_as_float(a2.y), __uint_as_float(c2.x), __uint_as_float(c2.y)};
+    };
     if (!single) {
-        if (wv == 0) {
-#pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                const int r = qt * 16 + lq;
-                if (lg == 0) {
-                    part_ml[((size_t)w * 2 + 0) * (QT * 16) + r] = m[qt];
-                    part_ml[((size_t)w * 2 + 1) * (QT * 16) + r] = lsum[qt];
-                }
-#pragma unroll
-                for (int dt = 0; dt < 8; dt++)
-                    *reinterpret_cast<float4_t*>(part_o + ((size_t)w * (QT * 16) + r) * D + dt * 16 + lg * 4) = o[qt][dt];
+        if (!producer && pgid == 0) {
+            if (lg == 0) {
+                __hip_atomic_store(&part_ml[((size_t)w * 2 + 0) * (QT * 16) + r_mine], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&part_ml[((size_t)w * 2 + 1) * (QT * 16) + r_mine], lsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __threadfence();  // the stores above are visible device-wide before the arrival is counted
-            if (lane == 0) {
-                const int old = atomicAdd(&arrive[bg], 1);
-                const int last = old == (w1 - w0 - 1);
-                if (last) arrive[bg] = 0;  // ready for the next layer
-                sh_last = last;
-            }
+#pragma unroll
+            for (int dt = 0; dt < 8; dt++) put(part_o + ((size_t)w * (QT * 16) + r_mine) * D + dt * 16 + lg * 4, o[dt]);
+            // every store above has been acknowledged before this wavefront reaches the barrier
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
         }
         __syncthreads();
-        if (!sh_last) return;
-        if (wv != 0) return;
-        __threadfence();  // see the other work items' stores
-#pragma unroll
-        for (int qt = 0; qt < QT; qt++) {
-            m[qt] = NEG_BIG;
-            lsum[qt] = 0.f;
-#pragma unroll
-            for (int dt = 0; dt < 8; dt++) o[qt][dt] = float4_t{0.f, 0.f, 0.f, 0.f};
+        if (tid == 0) {
+            const int old = __hip_atomic_fetch_add(&arrive[bg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int last = old == (w1 - w0 - 1);
+            if (last) __hip_atomic_store(&arrive[bg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next layer
+            sh_last = last;
         }
+        __syncthreads();
+        if (!sh_last || producer || pgid != 0) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        m = NEG_BIG;
+        lsum = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 8; dt++) o[dt] = float4_t{0.f, 0.f, 0.f, 0.f};
         for (int ww = w0; ww < w1; ww++) {
-#pragma unroll
-            for (int qt = 0; qt < QT; qt++) {
-                const int r = qt * 16 + lq;
-                const float m2 = part_ml[((size_t)ww * 2 + 0) * (QT * 16) + r];
-                const float l2 = part_ml[((size_t)ww * 2 + 1) * (QT * 16) + r];
-                const float mnew = fmaxf(m[qt], m2);
-                const float a1 = exp2f(m[qt] - mnew), a2 = exp2f(m2 - mnew);
-                lsum[qt] = lsum[qt] * a1 + l2 * a2;
-                m[qt] = mnew;
-#pragma unroll
-                for (int dt = 0; dt < 8; dt++) {
-                    const float4_t o2 = *reinterpret_cast<const float4_t*>(part_o + ((size_t)ww * (QT * 16) + r) * D + dt * 16 + lg * 4);
-#pragma unroll
-                    for (int i = 0; i < 4; i++) o[qt][dt][i] = o[qt][dt][i] * a1 + o2[i] * a2;
-                }
-            }
+            const float m2 = __hip_atomic_load(&part_ml[((size_t)ww * 2 + 0) * (QT * 16) + r_mine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float l2 = __hip_atomic_load(&part_ml[((size_t)ww * 2 + 1) * (QT * 16) + r_mine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            fold(m2, l2, [&](int dt) { return get(part_o + ((size_t)ww * (QT * 16) + r_mine) * D + dt * 16 + lg * 4); });
         }
-    } else if (wv != 0) {
+    } else if (producer || pgid != 0) {
         return;
     }
     // normalise and write the attention output as a bf16 pair, in the operand order of the O
     // projection: X[t = row0 + j][col = (g*G + hh)*D + d]; lane holds qrow lq, dims dt*16 + lg*4 + 0..3
+    if (r_mine >= rows) return;
     const int Kdim = Hq * D;
+    const float inv = 1.0f / lsum;
+    const int hh = r_mine - jrow * G;
+    const int t = row0 + jrow;
 #pragma unroll
-    for (int qt = 0; qt < QT; qt++) {
-        const int r = qt * 16 + lq;
-        if (r >= rows) continue;
-        const float inv = 1.0f / lsum[qt];
-        const int j = r / G, hh = r - j * G;
-        const int t = row0 + j;
+    for (int dt = 0; dt < 8; dt++) {
+        const int col = (g * G + hh) * D + dt * 16 + lg * 4;
+        uint32_t hi2[2], lo2[2];
 #pragma unroll
-        for (int dt = 0; dt < 8; dt++) {
-            const int col = (g * G + hh) * D + dt * 16 + lg * 4;
-            uint32_t hi2[2], lo2[2];
-#pragma unroll
-            for (int e = 0; e < 2; e++) {
-                const float x0 = o[qt][dt][2 * e] * inv, x1 = o[qt][dt][2 * e + 1] * inv;
-                const bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
-                hi2[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-                lo2[e] = (uint32_t)f32_to_bf16(x0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(x1 - bf16_to_f32(h1)) << 16);
-            }
-            const size_t off = frag_offset(t, col, Kdim);
-            *reinterpret_cast<uint2*>(X + off) = make_uint2(hi2[0], hi2[1]);
-            *reinterpret_cast<uint2*>(X + x_plane + off) = make_uint2(lo2[0], lo2[1]);
+        for (int e = 0; e < 2; e++) {
+            const float x0 = o[dt][2 * e] * inv, x1 = o[dt][2 * e + 1] * inv;
+            const bf16_t h0 = f32_to_bf16(x0), h1 = f32_to_bf16(x1);
+            hi2[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            lo2[e] = (uint32_t)f32_to_bf16(x0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(x1 - bf16_to_f32(h1)) << 16);
         }
+        const size_t off = frag_offset(t, col, Kdim);
+        *reinterpret_cast<uint2*>(X + off) = make_uint2(hi2[0], hi2[1]);
+        *reinterpret_cast<uint2*>(X + x_plane + off) = make_uint2(lo2[0], lo2[1]);
     }
 }
 
@@ -430,8 +397,9 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const
 }  // namespace
 
 size_t sled_attn_lds_bytes(int QT) {
-    const size_t loop_bytes = (size_t)QT * 8192 + (size_t)ATTN_WAVES * 3 * 8192;  // Q tiles + per-wavefront page rings
-    const size_t merge_bytes = (size_t)attn_slots(QT) * attn_slot_floats(QT) * sizeof(float);
+    const int npg = attn_groups(QT);
+    const size_t loop_bytes = (size_t)npg * ATTN_RING * 8192;                                      // page rings
+    const size_t merge_bytes = (size_t)(npg - 1) * QT * ATTN_PARK_F * sizeof(float);              // parked states
     return loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
 }
 
@@ -442,7 +410,7 @@ int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_
     if (s.dtype == SLED_BF16) {
         const float scale_log2 = 1.4426950408889634f / sqrtf((float)s.head_dim);
         const size_t lds = sled_attn_lds_bytes(QT);
-        dim3 grid(meta.n_work), blk(64 * ATTN_WAVES);
+        dim3 grid(meta.n_work), blk(64 * (QT + 1) * attn_groups(QT));
 #define SLED_ATTN_CASE(N)                                                                                            \
     case N: {                                                                                                        \
         static bool allowed = false;                                                                                 \
