@@ -91,6 +91,9 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the hand-counted waits below start from an empty queue
 
+    // the tile count follows the longest request the model allows; a request with fewer query rows
+    // leaves the upper tiles' wavefronts without work (they only keep the barriers company)
+    const bool active = qt * 16 < rows;
     float m = NEG_BIG, lsum = 0.f;
     float4_t o[8];
 #pragma unroll
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
             __builtin_amdgcn_s_waitcnt(7 << 4 | 3 << 14 | 15);  // lgkmcnt(0): this wavefront's LDS reads are back
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            if (r < my_rounds) process(r % RING, page_of(r));
+            if (active && r < my_rounds) process(r % RING, page_of(r));
             asm volatile("" ::: "memory");
         }
     }
