@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0
 # L2 fetch + write-back bytes per projection launch (FETCH_SIZE and WRITE_SIZE of rocprofv3, each scaled by
 # what the counter reads for a 1 GiB copy; profiles/verify_step_llama8b_b16_hbm_traffic.txt).  Taken with the
 # projection kernel as it stands; to be reset to None whenever that kernel changes.
-MEASURED_TRAFFIC = {"llama8b_b16": 154.2e6}
-CPU_SAMPLE_REQUESTS, CPU_SAMPLE_LAYERS = 16, 16   # the oracle's bounded sample (about 10-20 s of CPU work)
+MEASURED_TRAFFIC = {"llama8b_b16": 154.4e6}
+CPU_SAMPLE_REQUESTS, CPU_SAMPLE_LAYERS = 16, 24   # the oracle's bounded sample (about 10-20 s of CPU work)
 
 
 def parse():
@@ -189,8 +189,8 @@ def cpu_baseline(shape, weights, batch, KV, args):
     except Exception:
         cores = os.cpu_count() or 1
     n_req = min(CPU_SAMPLE_REQUESTS, batch.B)
-    # the oracle widens the sampled layers to float64: keep that under about 40 GB of host memory
-    n_lay = max(1, min(CPU_SAMPLE_LAYERS, shape.n_layers, int(40e9 // (shape.layer_params() * 8))))
+    # the oracle widens the sampled layers to float64: keep that under about 45 GB of host memory
+    n_lay = max(1, min(CPU_SAMPLE_LAYERS, shape.n_layers, int(45e9 // (shape.layer_params() * 8))))
     om = oracle_model(shape, weights, n_layers=n_lay)
     offs = batch.row_offsets()
     reqs = []
