@@ -223,3 +223,61 @@ def test_verify_argument_errors():
         v.append_context([r0], [K], [V])                  # 70 tokens need 5 pages, the pool has 4
     assert e.value.code == sled.ENOMEM
     v.destroy()
+
+
+@pytest.mark.parametrize("kind", ["tiny", "tiny_bf16"])
+def test_gpu_greedy_loop_reproduces_autoregressive_decoding(kind):
+    """Several requests run the draft -> verify -> accept -> commit loop on the GPU (sled_verify_batch,
+    sled_accept greedy, sled_kv_append with the device accept_len) with drafts that are partly right
+    and partly wrong; the generated text must equal the oracle's plain one-token-at-a-time greedy
+    decoding of the same prompts, token for token (Sec. 3.1: verification leaves the target's output
+    unchanged)."""
+    shape = synth.SHAPES[kind]
+    B, n_new = 3, 24
+    v, w = build_verifier(shape, 5, n_pages=64, max_requests=B, B_max=B, ctx_tokens_max=B * 96, gain_jitter=0.1,
+                          std=0.08)
+    om = oracle_model(shape, w)
+    rng = np.random.default_rng(11)
+    prompts = [synth.context_tokens(L, shape.vocab, seed=40 + i).tolist() for i, L in enumerate([9, 17, 3])]
+    want = [O.decode_greedy(om, p, n_new) for p in prompts]
+
+    reqs = [v.open() for _ in range(B)]
+    # prompt ingestion through the same path: all prompt tokens but the last, in chunks, fully committed
+    for i, p in enumerate(prompts):
+        body = p[:-1]
+        for s in range(0, len(body), shape.k_max + 1):
+            chunk = body[s: s + shape.k_max + 1]
+            tk = torch.tensor(chunk, dtype=torch.int32, device="cuda")
+            v.verify([reqs[i]], [len(chunk) - 1], tk)
+            v.commit([reqs[i]], torch.tensor([len(chunk) - 1], dtype=torch.int32, device="cuda"))
+    pending = [p[-1] for p in prompts]
+    out = [[] for _ in range(B)]
+    rounds = 0
+    while min(len(o) for o in out) < n_new:
+        rounds += 1
+        k, toks = [], []
+        for i in range(B):
+            # drafts: the true continuation, corrupted from a random position on; random length 0..k_max
+            ki = int(rng.integers(0, shape.k_max + 1))
+            truth = want[i][len(out[i]): len(out[i]) + ki]
+            drafts = list(truth) + [int(x) for x in rng.integers(0, shape.vocab, size=ki - len(truth))]
+            cut = int(rng.integers(0, ki + 1))
+            drafts[cut:] = [int(x) for x in rng.integers(0, shape.vocab, size=ki - cut)]
+            k.append(ki)
+            toks += [pending[i]] + drafts
+        tokens = torch.tensor(toks, dtype=torch.int32, device="cuda")
+        logits = v.verify(reqs, k, tokens)
+        a, t = v.accept(sled.GREEDY, k, logits, tokens)
+        v.commit(reqs, a)
+        a, t = a.cpu().numpy(), t.cpu().numpy()
+        row = 0
+        for i in range(B):
+            drafts = toks[row + 1: row + 1 + k[i]]
+            out[i] += drafts[: a[i]] + [int(t[i])]
+            pending[i] = int(t[i])
+            row += k[i] + 1
+    for i in range(B):
+        assert out[i][:n_new] == want[i], f"request {i} diverged after {rounds} rounds"
+    # the cache holds the prompt body, every emitted token but the pending one
+    assert v.lengths(reqs) == [len(p) - 1 + len(o) for p, o in zip(prompts, out)]
+    v.destroy()
