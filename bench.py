@@ -34,9 +34,13 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--workload", default="llama8b_b16", choices=["llama8b_b16", "llama8b_hetero64", "llama70b_b32", "tiny_bf16"],
+    ap.add_argument("--workload", default="llama8b_b16", choices=["llama8b_b16", "llama8b_hetero64", "llama70b_b32", "tiny_bf16", "accept_only"],
                     help="llama8b_b16 is the headline configuration; hetero64 uses sampling acceptance over "
-                         "full-vocabulary draft probabilities, the others greedy")
+                         "full-vocabulary draft probabilities, the others greedy; accept_only times sled_accept "
+                         "alone (256 requests x 8 drafts, vocabulary 128256, sampling) on given logits")
+    ap.add_argument("--sigma", type=float, default=1.0,
+                    help="accept_only: standard deviation of the noise between draft and target logits (the other "
+                         "two of 0.25, 1, 4 are reported in the breakdown)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy three times before the steps, so that a counter run "
@@ -60,6 +64,9 @@ def main():
         sys.exit(2)
     sled.lib()  # fails loudly if libsled.so has not been built
     torch.cuda.set_device(0)
+    if args.workload == "accept_only":
+        print(json.dumps(bench_accept(args)))
+        return
 
     if args.workload == "llama8b_b16":
         shape, kind = synth.SHAPES["llama8b"], "b16"
@@ -123,6 +130,7 @@ def main():
     lat = sorted(ev[s].elapsed_time(ev[s + 1]) for s in range(args.steps))
     p50, p90 = lat[len(lat) // 2], lat[min(len(lat) - 1, int(len(lat) * 0.9))]
     value = n_drafts * args.steps / (t1 - t0)
+    emitted = int(v.accept_len[:B].sum().item()) + B   # accepted drafts + one correction/bonus token each, last step
 
     # context actually held after the timed region (greedy on random tokens accepts ~0 drafts, so it
     # grew by about one token per step); used for the algorithmic K/V bytes
@@ -149,11 +157,14 @@ def main():
         "bytes_per_launch": round(weight_bytes / max(proj_launches, 1)),
     }
     step_bytes = weight_bytes + kv_bytes + logits_bytes
+    copy_gbs = copy_bandwidth_gbs()
     breakdown = {
         "proj_ms": round(proj_ms, 4), "attn_ms": round(ms[sled.PROF_ATTN] / psteps, 4),
         "rows_ms": round(ms[sled.PROF_ROWS] / psteps, 4),
         "attn_GBps": round(kv_bytes / max(ms[sled.PROF_ATTN] / psteps, 1e-9) / 1e6, 1),
         "step_bytes": step_bytes, "step_hbm_frac": round(step_bytes / (p50 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "copy_GBps": round(copy_gbs, 1), "step_frac_of_copy": round(step_bytes / (p50 * 1e-3) / 1e9 / copy_gbs, 4),
+        "emitted_tokens_per_s": round(emitted / (p50 * 1e-3), 1),
     }
 
     cpu = None
@@ -173,6 +184,117 @@ def main():
     }
     print(json.dumps(out))
     v.destroy()
+
+
+def copy_bandwidth_gbs():
+    """Bytes moved per second (read + write) by a 1 GiB device-to-device copy on this GPU."""
+    import torch
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def bench_accept(args):
+    """sled_accept alone: 256 requests x (8 drafts + 1 bonus row) x vocabulary 128256, target logits N(0, 2), draft
+    logits = target + sigma * N(0, 1), drafts drawn from q, speculative-sampling acceptance (Eq. 1)."""
+    import numpy as np
+    import torch
+    from paper_2506_09397_amd import sled, synth
+    vocab, k = 128256, [8] * 256
+    B, T, nd = len(k), sum(k) + len(k), sum(k)
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(B, T, vocab))
+    a = torch.zeros(B, dtype=torch.int32, device="cuda")
+    t = torch.zeros(B, dtype=torch.int32, device="cuda")
+    row_bytes = vocab * 4
+    per_sigma = {}
+    main = None
+    sigmas = [args.sigma] + [x for x in (0.25, 1.0, 4.0) if x != args.sigma]
+    cpu = None
+    for sg in sigmas:
+        case = synth.accept_case(k, vocab, sg, seed=args.seed + int(sg * 100), device="cuda")
+
+        def step():
+            sled.sled_accept(sled.SAMPLE, k, vocab, 1.0, case.logits, case.tokens, case.q, case.u_acc, case.u_smp, a, t, ws)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for s in range(args.steps):
+            step()
+            ev[s + 1].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        lat = sorted(ev[s].elapsed_time(ev[s + 1]) for s in range(args.steps))
+        p50, p90 = lat[len(lat) // 2], lat[min(len(lat) - 1, int(len(lat) * 0.9))]
+        acc = a.cpu().numpy()
+        # least the rule has to touch: rows 0..a_i of each request, and the draft distribution of the rejected draft
+        min_bytes = int(sum((int(x) + 1) + (1 if x < ki else 0) for x, ki in zip(acc, k))) * row_bytes
+        scan_bytes = T * row_bytes + int(sum(1 for x, ki in zip(acc, k) if x < ki)) * row_bytes * 2 + \
+            int(sum(1 for x, ki in zip(acc, k) if x >= ki)) * row_bytes
+        rec = {"ms_per_step": round((t1 - t0) * 1e3 / args.steps, 4), "p50_ms": round(p50, 4), "p90_ms": round(p90, 4),
+               "mean_accept_len": round(float(acc.mean()), 3), "verified_draft_tokens_per_s": round(nd / (p50 * 1e-3), 1),
+               "min_bytes": min_bytes, "min_bytes_GBps": round(min_bytes / (p50 * 1e-3) / 1e9, 1),
+               "touched_bytes": scan_bytes, "touched_GBps": round(scan_bytes / (p50 * 1e-3) / 1e9, 1)}
+        per_sigma[str(sg)] = rec
+        if main is None:
+            main = dict(rec, wall=(t1 - t0))
+            if not args.no_cpu_baseline:
+                cpu = cpu_baseline_accept(case, k, vocab)
+        del case
+        torch.cuda.empty_cache()
+    copy_gbs = copy_bandwidth_gbs()
+    achieved = main["touched_GBps"]
+    return {
+        "metric": "verified draft tokens/sec, acceptance step alone", "value": round(nd * args.steps / main["wall"], 1),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main["ms_per_step"],
+        "p50_ms": main["p50_ms"], "p90_ms": main["p90_ms"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32 logits, f64 sums", "data": "synthetic",
+        "config": {"workload": f"accept_only: B={B}, k=8 (+1 bonus row), V={vocab}, T={T} logits rows, sampling, "
+                               f"sigma={args.sigma}, seed {args.seed}"},
+        "roofline": {"bound": "hbm", "kernel": "sled_accept (accept_row_stats scan of all rows, accept_decide, accept_resample)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_launch": main["touched_bytes"],
+                     "frac_on_min_bytes": round(main["min_bytes_GBps"] / HBM_PEAK_GBS, 4),
+                     "copy_GBps": round(copy_gbs, 1), "frac_of_copy": round(achieved / copy_gbs, 4)},
+        "breakdown": per_sigma, "cpu_baseline": cpu,
+    }
+
+
+def cpu_baseline_accept(case, k, vocab, n_req=16):
+    """The oracle's acceptance on the first n_req requests of the case."""
+    import numpy as np
+    from oracle import sled_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    kk = k[:n_req]
+    T, nd = sum(kk) + n_req, sum(kk)
+    logits = case.logits[:T].cpu().numpy().astype(np.float64)
+    tokens = case.tokens[:T].cpu().numpy()
+    q = case.q[:nd].cpu().numpy().astype(np.float64)
+    u_acc = case.u_acc[:nd].cpu().numpy().astype(np.float64)
+    u_smp = case.u_smp[:n_req].cpu().numpy().astype(np.float64)
+    t0 = time.perf_counter()
+    reps = 0
+    while time.perf_counter() - t0 < 10.0:
+        O.accept_batch("sample", kk, logits, tokens, q, u_acc, u_smp)
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": round(nd / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_req} of {len(k)} requests ({T} logits rows), {reps} repetitions, {dt:.3f} s each"}
 
 
 def cpu_baseline(shape, weights, batch, KV, args):

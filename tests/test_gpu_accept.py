@@ -97,4 +97,4 @@ def test_accept_argument_errors():
         sled.sled_accept(sled.SAMPLE, k, vocab, 1.0, case.logits, case.tokens, None, case.u_acc, case.u_smp, a, a.clone(), ws)
     with pytest.raises(sled.SledError):
         sled.sled_accept(sled.SAMPLE, k, vocab, 1.0, case.logits, case.tokens, case.q, case.u_acc, case.u_smp, a, a.clone(),
-                         ws[:256])
+                         ws[:64])
