@@ -262,7 +262,7 @@ def bench_accept(args):
         "vs_baseline": None, "dtype": "f32 logits, f64 sums", "data": "synthetic",
         "config": {"workload": f"accept_only: B={B}, k=8 (+1 bonus row), V={vocab}, T={T} logits rows, sampling, "
                                f"sigma={args.sigma}, seed {args.seed}"},
-        "roofline": {"bound": "hbm", "kernel": "sled_accept (accept_row_stats scan of all rows, accept_decide, accept_resample)",
+        "roofline": {"bound": "hbm", "kernel": "sled_accept: accept_row_stats (scan of all logits rows) + accept_finish (decision, inverse-CDF draw)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None, "bytes_per_launch": main["touched_bytes"],
                      "frac_on_min_bytes": round(main["min_bytes_GBps"] / HBM_PEAK_GBS, 4),
