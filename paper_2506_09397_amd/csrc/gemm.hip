@@ -43,15 +43,20 @@
 namespace {
 
 constexpr int PLANES = 2;    // activation planes: hi, lo
-constexpr int KG = 4;        // k-groups = k-steps of 16 per stage
-constexpr int CG = 2;        // column groups
 constexpr int NW = 2;        // 32-column tiles per wavefront
-constexpr int WAVES = KG * CG;
+constexpr int WAVES = 8;     // = k-groups x column groups of a workgroup shape
 constexpr int DEPTH = 3;     // weight stages in flight beyond the one in use
 constexpr int NBUF = DEPTH + 1;
 constexpr int AHEAD = DEPTH + 1;  // activation stages in flight beyond the one being read
 constexpr int NXB = AHEAD + 1;    // LDS ring
-constexpr int COLS_PER_WG = CG * NW * 32;
+// Two workgroup shapes (KG k-groups = k-steps of 16 per stage, CG column groups of 64 columns):
+//   narrow  KG 4, CG 2: 128 columns, 64 k per stage.  Most workgroups per projection: the shape for one block of
+//           rows (up to 128), where the chip has to be filled by column blocks and K slices alone.
+//   wide    KG 2, CG 4: 256 columns, 32 k per stage.  Per MFMA it fetches two thirds of the bytes (half the
+//           activations, the same weights): the shape for several row blocks, where the workgroups are many
+//           anyway and the L2 -> CU path, not HBM, is what the MFMAs wait for.
+constexpr int NARROW_KG = 4, NARROW_CG = 2, WIDE_KG = 2, WIDE_CG = 4;
+constexpr int NARROW_COLS = NARROW_CG * NW * 32;
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float float16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4_t;
@@ -65,7 +70,7 @@ __device__ __forceinline__ void wait_loads(u32x4_t& a, u32x4_t& b) {
 }
 
 // MT: 32-row tiles of activations per block.
-template <int MT, int EPI>
+template <int MT, int EPI, int KG, int CG>
 __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
                                                                const bf16_t* __restrict__ Wp, int NT, int KS,
                                                                int ks_per_split, int n_col, int n_split, int n_zb,
@@ -77,6 +82,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     constexpr int MY_TILES = STAGE_TILES / WAVES;  // = MT: tiles of a stage this wavefront fetches
     constexpr int PER_ITER = MY_TILES + NW;        // vector-memory instructions a wavefront issues per stage
     constexpr unsigned STAGE_BYTES = STAGE_TILES * 1024;
+    static_assert(KG * CG == WAVES, "a workgroup is eight wavefronts");
     static_assert(STAGE_TILES % WAVES == 0, "stage does not divide among the wavefronts");
     static_assert(PER_ITER * DEPTH < 64, "too many loads in flight for the counter");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -111,9 +117,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
         // Lanes whose row lies past the last token (rounded up to whole 128-byte lines of 8 rows) re-read
         // the tile's first line instead: the fetch unit merges them into that line's request, so padding
         // rows cost no L2 traffic.  What lands in their LDS bytes only reaches their own output rows.
-        const int row = (mt_base + b) * 32 + (lane & 31);
+        // A block may reach past the last row tile (the wide shape always takes four): such a tile re-reads the
+        // last one, and its results are not stored.
+        const int mt = min(mt_base + b, T_pad / 32 - 1);
+        const int row = mt * 32 + (lane & 31);
         const int src_lane = row < row_lim ? lane : (lane & 32) + (lane & 7);
-        xsrc[j] = Xp + pl * x_plane + ((size_t)(mt_base + b) * KS + ks_begin + g) * 512 + src_lane * 8;
+        xsrc[j] = Xp + pl * x_plane + ((size_t)mt * KS + ks_begin + g) * 512 + src_lane * 8;
         xdst[j] = lds_base + i * 1024;
     }
     // one direct-to-LDS load moves a whole operand tile: lane l's 16 bytes land at m0 + 16*l
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     stage(integral_constant<int, 0>{}, xbuf, integral_constant<int, 3>{}, false, -1, 0, -1);
     __syncthreads();  // every stage has been consumed and no load is in flight: the ring is free
 
-    // ---- add the four k-groups' sums: (0 + 2) + (1 + 3), through LDS ------------------------------------
+    // ---- add the k-groups' sums through LDS: (0 + 2) + (1 + 3) for four groups, 0 + 1 for two ----------------
     {
         constexpr int PER_WAVE = NW * MT * 16 * 64;  // floats a wavefront parks
         float* red = reinterpret_cast<float*>(smem);
@@ -276,11 +285,13 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
 #pragma unroll
                     for (int e = 0; e < 16; e++) acc[a][b][e] += red[(size_t)slot * PER_WAVE + ((a * MT + b) * 16 + e) * 64 + lane];
         };
-        if (kgi >= 2) park((kgi - 2) * CG + cg);
-        __syncthreads();
-        if (kgi >= 2) return;
-        take(kgi * CG + cg);
-        __syncthreads();
+        if (KG == 4) {
+            if (kgi >= 2) park((kgi - 2) * CG + cg);
+            __syncthreads();
+            if (kgi >= 2) return;
+            take(kgi * CG + cg);
+            __syncthreads();
+        }
         if (kgi == 1) park(cg);
         __syncthreads();
         if (kgi == 1) return;
@@ -371,11 +382,11 @@ struct gemm_args {
     int F_act;
 };
 
-template <int MT, int EPI>
+template <int MT, int EPI, int KG, int CG>
 int launch_one(const gemm_args& a) {
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
-    auto kern = gemm_bf16_kernel<MT, EPI>;
+    auto kern = gemm_bf16_kernel<MT, EPI, KG, CG>;
     if (!allowed) {
         SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
@@ -386,12 +397,12 @@ int launch_one(const gemm_args& a) {
     return SLED_OK;
 }
 
-template <int MT>
+template <int MT, int KG, int CG>
 int launch_epi(int epi, const gemm_args& a) {
     switch (epi) {
-        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL>(a);
-        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU>(a);
-        default: return launch_one<MT, SLED_EPI_STORE>(a);
+        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL, KG, CG>(a);
+        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU, KG, CG>(a);
+        default: return launch_one<MT, SLED_EPI_STORE, KG, CG>(a);
     }
 }
 
@@ -427,10 +438,10 @@ const std::vector<tune_entry>& tune_table() {
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k) {
     sled_gemm_plan p{1};
     if (m->s.dtype != SLED_BF16) return p;
-    auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * KG * NBUF) == 0; };
+    auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * NARROW_KG * NBUF) == 0; };  // legal for both shapes
     for (const auto& te : tune_table())
         if (te.N == N && te.K == K && legal(te.split) && (!needs_full_k || te.split == 1)) return sled_gemm_plan{te.split};
-    const int n_wg = (N + COLS_PER_WG - 1) / COLS_PER_WG;
+    const int n_wg = (N + NARROW_COLS - 1) / NARROW_COLS;
     if (!needs_full_k)
         while (n_wg * p.split < 160 && legal(p.split * 2)) p.split *= 2;
     return p;
@@ -441,18 +452,23 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
                      hipStream_t st) {
     if (m->s.dtype == SLED_BF16) {
         const int NT = N / 32, KS = K / 16;
-        if (N % 32 || K % 16 || T_pad % 32 || plan.split < 1 || KS % (plan.split * KG * NBUF))
+        if (N % 32 || K % 16 || T_pad % 32 || plan.split < 1 || KS % (plan.split * NARROW_KG * NBUF))
             SLED_FAIL(SLED_EINVAL, "gemm: unsupported shape N=%d K=%d T_pad=%d split=%d", N, K, T_pad, plan.split);
         const int mt_total = T_pad / 32;
-        // rows are processed in blocks of at most 4 tiles (128 rows), evenly sized
+        // rows are processed in blocks of at most 4 tiles (128 rows): one block -> narrow shape with exactly its
+        // tiles; several -> wide shape, four tiles each (the last block may reach past the end)
+        const bool wide = mt_total > 4;
         const int zb = (mt_total + 3) / 4;
-        const int MT = (mt_total + zb - 1) / zb;
+        const int MT = wide ? 4 : mt_total;
+        const int KG = wide ? WIDE_KG : NARROW_KG, CG = wide ? WIDE_CG : NARROW_CG;
         gemm_args a;
         a.n_col = (NT + CG * NW - 1) / (CG * NW);
         a.n_split = plan.split;
-        a.n_zb = (mt_total + MT - 1) / MT;
+        a.n_zb = zb;
         a.grid = dim3((a.n_col * a.n_split + 7) / 8 * 8 * a.n_zb, 1, 1);
-        a.lds = (size_t)NXB * PLANES * MT * KG * 1024;  // also holds the MT * 32 KiB of the final reduction
+        // the ring of activation stages; afterwards the same memory holds the sums parked by the k-groups that
+        // hand theirs over (half of the wavefronts, NW * MT * 4 KiB each)
+        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (size_t)(WAVES / 2) * NW * MT * 4096);
         a.st = st;
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;
@@ -467,11 +483,12 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.out_act = static_cast<bf16_t*>(out_act);
         a.act_plane = act_plane;
         a.F_act = F_act;
+        if (wide) return launch_epi<4, WIDE_KG, WIDE_CG>(epilogue, a);
         switch (MT) {
-            case 1: return launch_epi<1>(epilogue, a);
-            case 2: return launch_epi<2>(epilogue, a);
-            case 3: return launch_epi<3>(epilogue, a);
-            default: return launch_epi<4>(epilogue, a);
+            case 1: return launch_epi<1, NARROW_KG, NARROW_CG>(epilogue, a);
+            case 2: return launch_epi<2, NARROW_KG, NARROW_CG>(epilogue, a);
+            case 3: return launch_epi<3, NARROW_KG, NARROW_CG>(epilogue, a);
+            default: return launch_epi<4, NARROW_KG, NARROW_CG>(epilogue, a);
         }
     }
     // fp32: no split, plain store (partial buffer with one slice has the same layout)
