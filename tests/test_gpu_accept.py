@@ -43,6 +43,37 @@ def test_greedy_matches_oracle(vocab, k):
     assert max(int(x) for x in a) > 0
 
 
+@pytest.mark.parametrize("mode", ["greedy", "sample"])
+def test_long_drafts_fail_beyond_the_first_wavefront_pass(mode):
+    """k up to the maximum of 255: the deciding wavefront judges 64 rows per pass, so the first
+    failure is put at draft 0, inside the first pass, on a pass boundary, deep in a later pass, and nowhere."""
+    vocab = 512
+    k = [255, 200, 130, 64, 65, 255, 3]
+    fail_at = [0, 37, 64, 63, None, 254, None]     # index of the first rejected draft
+    case = synth.accept_case(k, vocab, 0.0, seed=9, device="cuda")   # sigma 0: q == p, every draft passes Eq. 1
+    off = doff = 0
+    for ki, f in zip(k, fail_at):
+        rows = slice(off, off + ki)
+        if mode == "greedy":
+            case.tokens[off + 1: off + 1 + ki] = torch.argmax(case.logits[rows], dim=1).int()
+            if f is not None:
+                case.tokens[off + 1 + f] = (case.tokens[off + 1 + f] + 1) % vocab
+        elif f is not None:
+            # draft probability 1 for a token the target gives about 1/512: rejected for u = 0.9
+            d = int(case.tokens[off + 1 + f])
+            case.q[doff + f].zero_()
+            case.q[doff + f, d] = 1.0
+            case.u_acc[doff + f] = 0.9
+        off += ki + 1
+        doff += ki
+    m = sled.GREEDY if mode == "greedy" else sled.SAMPLE
+    a, t = run_accept_gpu(m, case, vocab)
+    want = oracle_accept(m, case)
+    assert [w["accept_len"] for w in want] == [ki if f is None else f for ki, f in zip(k, fail_at)]
+    assert compare_accept(m, k, a, t, want, mode) <= (0 if mode == "greedy" else 1)
+    assert a.tolist() == [w["accept_len"] for w in want]
+
+
 def test_greedy_ties_take_lowest_id():
     vocab, k = 4096, [3, 2]
     T = sum(k) + len(k)
