@@ -129,6 +129,7 @@ BF16_CASES = [
     ([0, 5, 16, 17, 130, 257, 1000], [8, 0, 3, 8, 1, 7, 8]),
     ([300] * 20, [2, 4, 6, 8] * 5),           # 120 packed rows: one full row block of the projections
     ([200, 40, 333] * 15, [8, 7, 8] * 15),    # 405 packed rows: four row blocks sharing each weight tile, the last one ragged
+    ([90] * 15, [8] * 15),                    # 135 packed rows: two row blocks, the second holding a single 32-row tile
 ]
 
 
