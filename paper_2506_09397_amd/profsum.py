@@ -2,6 +2,7 @@
 
     python -m paper_2506_09397_amd.profsum stats  <dir with *_kernel_stats.csv>
     python -m paper_2506_09397_amd.profsum traffic <FETCH_SIZE dir> <WRITE_SIZE dir>
+    python -m paper_2506_09397_amd.profsum mfma    <dir of a --pmc SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE --kernel-trace run>
 
 `traffic` scales the FETCH_SIZE / WRITE_SIZE counters (KiB per dispatch as rocprofv3 reports them) by
 what the same counters read for the 1 GiB device-to-device copy that `bench.py --copy-calibration`
@@ -80,11 +81,30 @@ def traffic(dfetch: str, dwrite: str) -> None:
         print(f"{n:70s} {g:10d} {len(fe[key]):5d} {f_mb:10.2f} {w_mb:10.2f}")
 
 
+def mfma(d: str) -> None:
+    """MFMA pipe occupancy of the projection kernels: SQ_VALU_MFMA_BUSY_CYCLES (summed over all SIMDs) over the SIMD
+    cycles of the dispatch, GRBM_GUI_ACTIVE (summed over the 8 XCDs) / 8 x 256 CUs x 4 SIMDs; and the shader clock
+    that GRBM_GUI_ACTIVE implies for the dispatch's duration."""
+    busy, act = per_kernel(d, "SQ_VALU_MFMA_BUSY_CYCLES"), per_kernel(d, "GRBM_GUI_ACTIVE")
+    dur = collections.defaultdict(list)
+    for r in csv.DictReader(open(glob.glob(d + "/*kernel_trace.csv")[0])):
+        grid = int(r["Grid_Size_X"]) * int(r["Grid_Size_Y"]) * int(r["Grid_Size_Z"])
+        dur[(short(r["Kernel_Name"]), grid)].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    print(f"{'kernel':40s} {'grid':>9s} {'n':>5s} {'avg us':>9s} {'MFMA busy':>10s} {'clock GHz':>10s}")
+    for key in sorted(busy, key=lambda k: -sum(busy[k])):
+        if "gemm_bf16" not in key[0] or key not in act or key not in dur:
+            continue
+        b, a, t = sum(busy[key]) / len(busy[key]), sum(act[key]) / len(act[key]), sum(dur[key]) / len(dur[key])
+        print(f"{key[0]:40s} {key[1]:9d} {len(busy[key]):5d} {t:9.1f} {b / (a / 8 * 1024):10.3f} {a / 8 / (t * 1e3):10.2f}")
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 3 and sys.argv[1] == "stats":
         stats(sys.argv[2])
     elif len(sys.argv) >= 4 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3])
+    elif len(sys.argv) >= 3 and sys.argv[1] == "mfma":
+        mfma(sys.argv[2])
     else:
         print(__doc__)
         sys.exit(2)

@@ -75,13 +75,13 @@ def batch_sweep(seed=0):
         v.destroy()
 
 
-def rows_sweep(seed=0):
+def rows_sweep(seed=0, sizes=(128, 256, 512, 1024, 2048, 4096)):
     shape = synth.SHAPES["llama8b"]
     weights = synth.SynthWeights(shape, seed=seed, device="cuda")
     rng = np.random.default_rng(seed)
     flop_per_row = 2.0 * shape.streamed_params()
     print(f"{'rows':>5s} {'p50 ms':>8s} {'proj ms':>8s} {'useful TFLOP/s':>15s} {'of bf16 MFMA peak':>18s} {'weight GB/s':>12s}")
-    for T in (128, 256, 512, 1024, 2048, 4096):
+    for T in sizes:
         B = (T + 8) // 9
         k = [8] * B
         k[-1] = T - 9 * (B - 1) - 1
@@ -111,7 +111,8 @@ if __name__ == "__main__":
     if which == "batch":
         batch_sweep()
     elif which == "rows":
-        rows_sweep()
+        # optional list of row counts, e.g. `rows 1024` for a counter run over one size
+        rows_sweep(sizes=tuple(int(a) for a in sys.argv[2:]) or (128, 256, 512, 1024, 2048, 4096))
     else:
         print(__doc__)
         sys.exit(2)
