@@ -64,9 +64,10 @@ class Response:
 class Server:
     """Queue + static batch planner + the verification step for a set of devices."""
 
-    def __init__(self, verifier: Verifier, batch_size: int):
+    def __init__(self, verifier: Verifier, batch_size: int, device: str = "cuda"):
         self.v = verifier
         self.batch_size = batch_size
+        self.device = device        # where the packed token ids of a step are put
         self.queue: Deque[Pending] = collections.deque()
         self.req_of: Dict[int, int] = {}              # device -> request id in the pool
         self.last: Dict[int, Response] = {}           # device -> answer of its latest verified round
@@ -126,7 +127,7 @@ class Server:
         toks: List[int] = []
         for p in batch:
             toks += [p.pending_token] + p.drafts
-        tokens = torch.tensor(toks, dtype=torch.int32, device="cuda")
+        tokens = torch.tensor(toks, dtype=torch.int32, device=self.device)
         logits = self.v.verify(reqs, k, tokens)
         a, t = self.v.accept(sled.GREEDY, k, logits, tokens)
         self.v.commit(reqs, a)
@@ -244,10 +245,13 @@ def simulate(server: Server, drafters: Dict[int, ReplayDrafter], first_tokens: D
             now = max(now, t)
             send(d, now)
         assert server.queue, "every running device is either drafting or queued"
-        torch.cuda.synchronize()
+        on_gpu = server.device != "cpu"
+        if on_gpu:
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         resp = server.run_batch(allow_partial=True)
-        torch.cuda.synchronize()
+        if on_gpu:
+            torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) * 1e3
         gpu_ms += dt
         now += dt
