@@ -16,6 +16,8 @@
  *   sled_kv_append      bring a request's context K/V into the server-side cache, or
  *                       commit the K/V of the tokens just accepted (the iterate-until-
  *                       done loop of Sec. 3.2)
+ *   sled_prefill        (beyond the step) a request's prompt through the same kernels into
+ *                       its cache
  *
  * General rules
  *   - Plain C.  Every function returns SLED_OK (0) or a negative error code; nothing
@@ -169,6 +171,23 @@ SLED_API size_t sled_verify_workspace_bytes(const sled_model* m, int B_max, int 
 SLED_API int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int* req_ids /*host*/, const int* k /*host*/,
                       const int32_t* tokens /*dev*/, float* logits /*dev*/,
                       void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
+/* Context ingest through the target model itself: runs n_tokens prompt tokens of ONE request through the
+ * same kernels as the verification step, on top of whatever the request has cached, writes their K/V into the
+ * request's pages and commits them (L += n_tokens).  This is how a device's prompt p^n reaches the server-side
+ * cache (Sec. 3.2: the tokenised prompt is what a device holds before it drafts); the other way in is
+ * sled_kv_append with externally produced K/V.
+ *   tokens[n_tokens]     dev int32, the tokens at positions L .. L + n_tokens - 1
+ *   logits_last[vocab]   dev float32 out or NULL: logits of the last token, i.e. the target's distribution of
+ *                        the first token to generate (the last prompt token may instead be kept back as the
+ *                        pending token of the first verification)
+ *   workspace            dev scratch, 256-byte aligned; any size that sled_verify_workspace_bytes returns for
+ *                        B_max >= 1 will do: the prompt is cut into slices of as many blocks of k_max + 1 rows
+ *                        as the workspace holds (larger workspace, fewer and larger slices)
+ * Rows that an earlier, uncommitted sled_verify_batch staged for the request are overwritten.
+ * Errors: SLED_EINVAL, SLED_ENOMEM (no free page). */
+SLED_API int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tokens, const int32_t* tokens /*dev*/,
+                 float* logits_last /*dev or NULL*/, void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
 /* Bytes of scratch sled_accept needs for T packed rows. */
 SLED_API size_t sled_accept_workspace_bytes(int B, int T, int vocab);

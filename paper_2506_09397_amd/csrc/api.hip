@@ -432,7 +432,7 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
 namespace {
 
 struct ws_plan {
-    size_t h, xa, xo, xf, q, partial, cs, part_o, part_ml, arrive, total, T_alloc;
+    size_t h, xa, xo, xf, q, x1, partial, cs, part_o, part_ml, arrive, total, T_alloc;
 };
 
 // Attention work list.  A work item is a run of pages of one (request, kv head), processed by one
@@ -476,6 +476,7 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     w.xo = take(planes * T_alloc * HD * m->elem);
     w.xf = take(planes * T_alloc * F * m->elem);
     w.q = take(planes * T_alloc * HD * m->elem);
+    w.x1 = take(planes * 32 * d * m->elem);  // one 32-row tile: the single row whose logits a prompt asks for
     size_t part = 0;
     part = std::max(part, (size_t)sled_gemm_make_plan(m, m->n_qkv, s.d_model, false).split * T_pad * m->n_qkv);
     part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, (int)HD, false).split * T_pad * d);
@@ -509,38 +510,45 @@ extern "C" size_t sled_verify_workspace_bytes(const sled_model* m, int B_max, in
     return worst + 256;
 }
 
-extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int* req_ids, const int* k,
-                                 const int32_t* tokens, float* logits, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
-    if (!m || !p || !req_ids || !k || !tokens || !logits || !workspace) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: null argument");
-    if (p->m != m) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: pool belongs to another model");
-    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: workspace must be 256-byte aligned");
-    int rc = check_requests(p, B, req_ids, "sled_verify_batch");
-    if (rc != SLED_OK) return rc;
+namespace {
+
+// One row block of a step: `rows` consecutive tokens of request `req`, the first of them `pos0` positions behind
+// the request's committed length.  A verification request is one block (pos0 = 0, rows = k + 1); a prompt is cut
+// into blocks of at most k_max + 1 rows that follow one another.
+struct step_entry {
+    int req, pos0, rows;
+};
+
+// The forward pass over the packed rows of `ent` on top of the cached contexts: new K/V go to the requests' pages
+// (nothing is committed here), and the logits of all rows go to logits_all [T, vocab], or those of the single row
+// one_row to logits_one [vocab], or nowhere.
+int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& ent, const int32_t* tokens, float* logits_all,
+                int one_row, float* logits_one, void* workspace, size_t workspace_bytes, hipStream_t st, const char* who) {
     const sled_shape& s = m->s;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = (int)ent.size();
     const int Hkv = s.n_kv_heads, G = s.n_q_heads / Hkv;
-    int T = 0, kmax = 0;
-    for (int i = 0; i < B; i++) {
-        if (k[i] < 0 || k[i] > s.k_max) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: k[%d] = %d outside [0, %d]", i, k[i], s.k_max);
-        T += k[i] + 1;
-        kmax = std::max(kmax, k[i]);
+    int rc;
+    int T = 0, nmax = 0;
+    for (const step_entry& e : ent) {
+        T += e.rows;
+        nmax = std::max(nmax, e.rows);
     }
-    // pages for the staged tokens, attention work list
+    // pages for the new tokens, attention work list
     int64_t total_pages = 0;
-    for (int i = 0; i < B; i++) {
-        sled_request& rq = p->reqs[req_ids[i]];
-        if ((rc = ensure_pages(p, req_ids[i], rq.len_ub + k[i] + 1)) != SLED_OK) return rc;
-        total_pages += ceil_div(rq.len_ub + k[i] + 1, 16);
-    }
     std::vector<int> np_all(B);
-    for (int i = 0; i < B; i++) np_all[i] = ceil_div(p->reqs[req_ids[i]].len_ub + k[i] + 1, 16);
+    for (int i = 0; i < B; i++) {
+        const sled_request& rq = p->reqs[ent[i].req];
+        const int reach = rq.len_ub + ent[i].pos0 + ent[i].rows;  // upper bound of the last position + 1
+        if ((rc = ensure_pages(p, ent[i].req, reach)) != SLED_OK) return rc;
+        np_all[i] = ceil_div(reach, 16);
+        total_pages += np_all[i];
+    }
     const int tgt = attn_pages_per_item(np_all, Hkv);
     std::vector<int32_t> work;
     std::vector<int32_t> cu_work(B * Hkv + 1);
     for (int i = 0; i < B; i++) {
         const int np = np_all[i];
-        const int chunk = ceil_div(np, ceil_div(np, tgt));  // even split of this request's pages
+        const int chunk = ceil_div(np, ceil_div(np, tgt));  // even split of this block's pages
         for (int g = 0; g < Hkv; g++) {
             cu_work[i * Hkv + g] = (int)(work.size() / 4);
             for (int p0 = 0; p0 < np; p0 += chunk) {
@@ -553,32 +561,31 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     }
     const int n_work = (int)(work.size() / 4);
     cu_work[B * Hkv] = n_work;
-    const int QT = std::max(1, ceil_div(G * (kmax + 1), 16));
+    const int QT = std::max(1, ceil_div(G * nmax, 16));
     const ws_plan wp = plan_workspace(m, T, n_work, QT);
-    if (wp.total > workspace_bytes)
-        SLED_FAIL(SLED_EINVAL, "sled_verify_batch: workspace of %zu bytes, %zu needed", workspace_bytes, wp.total);
+    if (wp.total > workspace_bytes) SLED_FAIL(SLED_EINVAL, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, wp.total);
 
     // metadata blob
-    const size_t n_meta = 2 * (size_t)B + 2 * ((size_t)B + 1) + 2 * (size_t)T + (size_t)total_pages + work.size() + cu_work.size();
+    const size_t n_meta = 3 * (size_t)B + 2 * ((size_t)B + 1) + 2 * (size_t)T + (size_t)total_pages + work.size() + cu_work.size();
     sled_stage_slot* sl;
     if ((rc = stage_acquire(p, n_meta, &sl)) != SLED_OK) return rc;
     int32_t* hp = sl->host;
-    size_t o_req = 0, o_k = o_req + B, o_cur = o_k + B, o_cup = o_cur + B + 1, o_rr = o_cup + B + 1, o_rj = o_rr + T,
-           o_pg = o_rj + T, o_wk = o_pg + total_pages, o_cw = o_wk + work.size();
+    size_t o_req = 0, o_k = o_req + B, o_p0 = o_k + B, o_cur = o_p0 + B, o_cup = o_cur + B + 1, o_rr = o_cup + B + 1,
+           o_rj = o_rr + T, o_pg = o_rj + T, o_wk = o_pg + total_pages, o_cw = o_wk + work.size();
     int row = 0, pg = 0;
     for (int i = 0; i < B; i++) {
-        const sled_request& rq = p->reqs[req_ids[i]];
-        hp[o_req + i] = req_ids[i];
-        hp[o_k + i] = k[i];
+        const sled_request& rq = p->reqs[ent[i].req];
+        hp[o_req + i] = ent[i].req;
+        hp[o_k + i] = ent[i].rows - 1;
+        hp[o_p0 + i] = ent[i].pos0;
         hp[o_cur + i] = row;
         hp[o_cup + i] = pg;
-        for (int j = 0; j <= k[i]; j++) {
+        for (int j = 0; j < ent[i].rows; j++) {
             hp[o_rr + row] = i;
             hp[o_rj + row] = j;
             row++;
         }
-        const int np = ceil_div(rq.len_ub + k[i] + 1, 16);
-        for (int q = 0; q < np; q++) hp[o_pg + pg++] = rq.pages[q];
+        for (int q = 0; q < np_all[i]; q++) hp[o_pg + pg++] = rq.pages[q];
     }
     hp[o_cur + B] = row;
     hp[o_cup + B] = pg;
@@ -588,6 +595,7 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     sled_step_meta meta;
     meta.req_id = sl->dev + o_req;
     meta.k = sl->dev + o_k;
+    meta.pos0 = sl->dev + o_p0;
     meta.cu_rows = sl->dev + o_cur;
     meta.cu_pages = sl->dev + o_cup;
     meta.row_req = sl->dev + o_rr;
@@ -605,6 +613,7 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
     void* xo = ws + wp.xo;
     void* xf = ws + wp.xf;
     void* qb = ws + wp.q;
+    void* x1 = ws + wp.x1;
     float* partial = reinterpret_cast<float*>(ws + wp.partial);
     float* cs = reinterpret_cast<float*>(ws + wp.cs);
     float* part_o = reinterpret_cast<float*>(ws + wp.part_o);
@@ -655,13 +664,87 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
         const float* next_gain = (l + 1 < s.n_layers) ? m->layers[l + 1].g_attn : m->g_final;
         SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_dn.split, T, T_pad, h, xa, pl_d, next_gain, st));
     }
-    SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, g_lm, logits, nullptr, 0, 0, st));
+    if (logits_all) {
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, g_lm, logits_all, nullptr, 0, 0, st));
+    } else if (one_row >= 0 && logits_one) {
+        // the LM head over one row: that row becomes row 0 of a one-tile activation block
+        const size_t pl_1 = bf ? (size_t)32 * d : 0;
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_copy_act_row(m, xa, pl_d, one_row, x1, pl_1, d, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, x1, pl_1, m->lm_head, 1, 32, s.vocab, d, SLED_EPI_STORE, g_lm, logits_one, nullptr, 0, 0, st));
+    }
     SLED_TRY(stage_release(sl, st));
 #undef SLED_RUN
 #undef SLED_TRY
+    return SLED_OK;
+}
 
+}  // namespace
+
+extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int* req_ids, const int* k,
+                                 const int32_t* tokens, float* logits, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+    if (!m || !p || !req_ids || !k || !tokens || !logits || !workspace) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: null argument");
+    if (p->m != m) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: pool belongs to another model");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: workspace must be 256-byte aligned");
+    int rc = check_requests(p, B, req_ids, "sled_verify_batch");
+    if (rc != SLED_OK) return rc;
+    std::vector<step_entry> ent(B);
+    for (int i = 0; i < B; i++) {
+        if (k[i] < 0 || k[i] > m->s.k_max) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: k[%d] = %d outside [0, %d]", i, k[i], m->s.k_max);
+        ent[i] = step_entry{req_ids[i], 0, k[i] + 1};
+    }
+    rc = run_forward(m, p, ent, tokens, logits, -1, nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream),
+                     "sled_verify_batch");
+    if (rc != SLED_OK) return rc;
     for (int i = 0; i < B; i++) p->reqs[req_ids[i]].staged = k[i] + 1;
     p->last_batch.assign(req_ids, req_ids + B);
+    return SLED_OK;
+}
+
+extern "C" int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tokens, const int32_t* tokens, float* logits_last,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (!m || !p || !tokens || !workspace) SLED_FAIL(SLED_EINVAL, "sled_prefill: null argument");
+    if (p->m != m) SLED_FAIL(SLED_EINVAL, "sled_prefill: pool belongs to another model");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_prefill: workspace must be 256-byte aligned");
+    if (n_tokens < 1) SLED_FAIL(SLED_EINVAL, "sled_prefill: n_tokens = %d", n_tokens);
+    int rc = check_requests(p, 1, &req_id, "sled_prefill");
+    if (rc != SLED_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const sled_shape& s = m->s;
+    const int per = s.k_max + 1;  // rows of one block: what the attention kernel's query tiles are sized for
+    const int QT = ceil_div(s.n_q_heads / s.n_kv_heads * per, 16);
+    // the largest number of blocks per step that the workspace holds
+    auto fits = [&](int blocks) { return plan_workspace(m, blocks * per, max_work_items(m, blocks, 0), QT).total <= workspace_bytes; };
+    if (!fits(1)) SLED_FAIL(SLED_EINVAL, "sled_prefill: workspace of %zu bytes is too small for one block of %d rows", workspace_bytes, per);
+    int lo = 1, hi = ceil_div(n_tokens, per);
+    while (lo < hi) {  // fits(lo) holds
+        const int mid = (lo + hi + 1) / 2;
+        if (fits(mid)) lo = mid;
+        else hi = mid - 1;
+    }
+    const int blocks_per_step = lo;
+    sled_request& rq = p->reqs[req_id];
+    rq.staged = -1;  // rows staged by an earlier verify are overwritten
+    p->last_batch.clear();
+    for (int done = 0; done < n_tokens;) {
+        const int rows = std::min(n_tokens - done, blocks_per_step * per);
+        std::vector<step_entry> ent;
+        for (int r = 0; r < rows; r += per) ent.push_back(step_entry{req_id, r, std::min(per, rows - r)});
+        const bool last = done + rows == n_tokens;
+        rc = run_forward(m, p, ent, tokens + done, nullptr, (last && logits_last) ? rows - 1 : -1, logits_last, workspace,
+                         workspace_bytes, st, "sled_prefill");
+        if (rc != SLED_OK) return rc;
+        // commit the slice: L += rows, in stream order before the next slice reads L
+        sled_stage_slot* sl;
+        if ((rc = stage_acquire(p, 2, &sl)) != SLED_OK) return rc;
+        sl->host[0] = req_id;
+        sl->host[1] = rows;
+        SLED_HIP(hipMemcpyAsync(sl->dev, sl->host, 2 * sizeof(int32_t), hipMemcpyHostToDevice, st));
+        if ((rc = sled_launch_len_add(p->len_dev, sl->dev, sl->dev + 1, nullptr, 1, st)) != SLED_OK) return rc;
+        if ((rc = stage_release(sl, st)) != SLED_OK) return rc;
+        rq.len_ub += rows;
+        done += rows;
+    }
     return SLED_OK;
 }
 

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
     const bool producer = wv >= NPG * QT;
     const int pgid = producer ? wv - NPG * QT : wv / QT, qt = producer ? 0 : wv - pgid * QT;
     const int G = Hq / Hkv;
-    const int L = len_dev[meta.req_id[b]];
+    const int L = len_dev[meta.req_id[b]] + meta.pos0[b];  // everything before the block's first row is context
     const int n = meta.k[b] + 1;
     const int rows = G * n;
     const int row0 = meta.cu_rows[b];
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const
     const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     const int b = meta.row_req[t], j = meta.row_j[t];
     const int g = h / (Hq / Hkv);
-    const int nkeys = len_dev[meta.req_id[b]] + j + 1;
+    const int nkeys = len_dev[meta.req_id[b]] + meta.pos0[b] + j + 1;
     const int32_t* pages = meta.pages + meta.cu_pages[b];
     float q[D], o[D];
     const float* qp = Q + ((size_t)t * Hq + h) * D;

@@ -116,7 +116,7 @@ __global__ void rope_table_kernel(sled_step_meta meta, const int32_t* __restrict
                                   float2* __restrict__ cs) {
     const int t = blockIdx.x;
     const int b = meta.row_req[t];
-    const int pos = len_dev[meta.req_id[b]] + meta.row_j[t];
+    const int pos = len_dev[meta.req_id[b]] + meta.pos0[b] + meta.row_j[t];
     for (int i = threadIdx.x; i < half; i += blockDim.x) {
         double inv = pow(theta, -(double)i / (double)half);
         double ang = (double)pos * inv;
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta,
                                                             void* __restrict__ v_pool, int64_t n_pages, int layer) {
     const int t = blockIdx.x, head = blockIdx.y;
     const int b = meta.row_req[t];
-    const int pos = len_dev[meta.req_id[b]] + meta.row_j[t];
+    const int pos = len_dev[meta.req_id[b]] + meta.pos0[b] + meta.row_j[t];
     const int page = meta.pages[meta.cu_pages[b] + (pos >> 4)];
     const int slot = pos & 15;
     const int half = D >> 1;
@@ -257,6 +257,25 @@ __global__ void kv_ingest_kernel(const void* __restrict__ k_src, const void* __r
     }
 }
 
+// row t of an activation buffer -> row 0 of another one
+template <bool BF16>
+__global__ __launch_bounds__(256) void copy_act_row_kernel(const void* __restrict__ X, size_t plane, int t, void* __restrict__ X1,
+                                                           size_t plane1, int d) {
+    for (int c = (blockIdx.x * 256 + threadIdx.x) * 8; c < d; c += gridDim.x * 256 * 8) {
+        if (BF16) {
+            const bf16_t* src = static_cast<const bf16_t*>(X) + frag_offset(t, c, d);
+            bf16_t* dst = static_cast<bf16_t*>(X1) + frag_offset(0, c, d);
+            *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+            *reinterpret_cast<uint4*>(dst + plane1) = *reinterpret_cast<const uint4*>(src + plane);
+        } else {
+            const float* src = static_cast<const float*>(X) + (size_t)t * d + c;
+            float* dst = static_cast<float*>(X1) + c;
+            *reinterpret_cast<float4*>(dst) = *reinterpret_cast<const float4*>(src);
+            *reinterpret_cast<float4*>(dst + 4) = *reinterpret_cast<const float4*>(src + 4);
+        }
+    }
+}
+
 // len[req_ids[i]] += add[i]            (accept == nullptr)
 // len[req_ids[i]] += accept[i] + 1     (otherwise)
 __global__ void len_add_kernel(int32_t* __restrict__ len_dev, const int32_t* __restrict__ req_ids,
@@ -347,6 +366,18 @@ int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_s
     else
         hipLaunchKernelGGL(residual_norm_kernel<false>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
                            m->s.rms_eps, gain, h, X, plane);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_copy_act_row(const sled_model* m, const void* X, size_t plane, int t, void* X1, size_t plane1, int d,
+                             hipStream_t st) {
+    if (d % 8) SLED_FAIL(SLED_EINVAL, "copy_act_row: d_model %d is not a multiple of 8", d);
+    const int grid = (d / 8 + 255) / 256;
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(copy_act_row_kernel<true>, dim3(grid), dim3(256), 0, st, X, plane, t, X1, plane1, d);
+    else
+        hipLaunchKernelGGL(copy_act_row_kernel<false>, dim3(grid), dim3(256), 0, st, X, plane, t, X1, plane1, d);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

@@ -146,8 +146,9 @@ struct sled_kvpool {
 
 // per-step metadata blob, device side (offsets in int32 units from the blob start)
 struct sled_step_meta {
-    const int32_t* req_id;     // [B]
-    const int32_t* k;          // [B]
+    const int32_t* req_id;     // [B]   per row block of the step (a request has one, a prompt slice several)
+    const int32_t* k;          // [B]   rows of the block - 1
+    const int32_t* pos0;       // [B]   position of the block's first row behind the request's committed length
     const int32_t* cu_rows;    // [B+1]
     const int32_t* cu_pages;   // [B+1]
     const int32_t* row_req;    // [T]   index into the batch (not the request id)
@@ -166,6 +167,9 @@ struct sled_step_meta {
 int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
                           int dst_rows_total, hipStream_t st);
 int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStream_t st);
+// row t of an activation buffer -> row 0 of a one-tile buffer (the single row the LM head is asked for)
+int sled_launch_copy_act_row(const sled_model* m, const void* X, size_t plane, int t, void* X1, size_t plane1, int d,
+                             hipStream_t st);
 int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, float* h, void* X, size_t plane,
                            const float* gain, hipStream_t st);
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,

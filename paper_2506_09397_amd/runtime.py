@@ -43,6 +43,12 @@ class Verifier:
         sled.sled_verify_batch(self.model, self.pool, reqs, k, tokens, out, self.ws)
         return out
 
+    def prefill(self, req: int, tokens: torch.Tensor, want_logits: bool = True) -> Optional[torch.Tensor]:
+        """Run a prompt (int32 ids on the GPU) into the request's cache; returns the last token's logits [vocab]."""
+        out = self.logits[0] if want_logits else None
+        sled.sled_prefill(self.model, self.pool, req, tokens, out, self.ws)
+        return out
+
     def accept(self, mode: int, k: Sequence[int], logits: torch.Tensor, tokens: torch.Tensor,
                draft_q: Optional[torch.Tensor] = None, u_acc: Optional[torch.Tensor] = None,
                u_smp: Optional[torch.Tensor] = None, temperature: float = 1.0):

@@ -29,7 +29,7 @@ TENSOR_IDS = {"embed": T_EMBED, "wq": T_WQ, "wk": T_WK, "wv": T_WV, "wo": T_WO, 
 EXPORTS = [
     "sled_model_create", "sled_model_load", "sled_model_destroy",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
-    "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch",
+    "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
     "sled_accept_workspace_bytes", "sled_accept", "sled_profile_enable", "sled_profile_read",
     "sled_strerror", "sled_last_error",
 ]
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
     L.sled_verify_workspace_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int64]
     L.sled_verify_workspace_bytes.restype = C.c_size_t
     L.sled_verify_batch.argtypes = [vp, vp, C.c_int, ip, ip, vp, vp, vp, C.c_size_t, vp]
+    L.sled_prefill.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp, C.c_size_t, vp]
     L.sled_accept_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     L.sled_accept_workspace_bytes.restype = C.c_size_t
     L.sled_accept.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -175,6 +176,13 @@ def sled_verify_batch(model: int, pool: int, req_ids: Sequence[int], k: Sequence
     assert tokens.dtype == torch.int32 and logits.dtype == torch.float32
     _check(lib().sled_verify_batch(model, pool, len(req_ids), _ints(req_ids), _ints(k), _ptr(tokens), _ptr(logits),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sled_prefill(model: int, pool: int, req_id: int, tokens: torch.Tensor, logits_last: Optional[torch.Tensor],
+                 workspace: torch.Tensor) -> None:
+    assert tokens.dtype == torch.int32 and (logits_last is None or logits_last.dtype == torch.float32)
+    _check(lib().sled_prefill(model, pool, int(req_id), int(tokens.numel()), _ptr(tokens), _ptr(logits_last), _ptr(workspace),
+                              workspace.numel() * workspace.element_size(), _stream()))
 
 
 def sled_accept_workspace_bytes(B: int, T: int, vocab: int) -> int:

@@ -2,6 +2,7 @@
 
     python -m paper_2506_09397_amd.sweeps batch     # step latency vs batch size and speculative length
     python -m paper_2506_09397_amd.sweeps rows      # projection time vs number of packed rows (MFMA regime)
+    python -m paper_2506_09397_amd.sweeps prefill   # prompt ingest (sled_prefill): prompt length x rows per slice
 
 `batch` is the one-GPU analogue of the paper's throughput-versus-batch-size curve (Sec. 5) and of its
 study of the speculative length: Llama-3-8B shape, contexts uniform in [512, 2048], every request
@@ -12,6 +13,7 @@ useful FLOP = 2 * rows * streamed parameters.
 from __future__ import annotations
 
 import sys
+import time
 
 import numpy as np
 import torch
@@ -104,6 +106,36 @@ def rows_sweep(seed=0, sizes=(128, 256, 512, 1024, 2048, 4096)):
         v.destroy()
 
 
+def prefill_sweep(seed=0):
+    """Prompt ingest through sled_prefill, Llama-3-8B shape: prompt length x rows per slice."""
+    shape = synth.SHAPES["llama8b"]
+    weights = synth.SynthWeights(shape, seed=seed, device="cuda")
+    rng = np.random.default_rng(seed)
+    per = shape.k_max + 1
+    print(f"{'prompt':>7s} {'rows/slice':>11s} {'ms':>9s} {'tokens/s':>10s} {'useful TFLOP/s':>15s} {'of bf16 MFMA peak':>18s}")
+    for blocks in (14, 56, 112, 224):
+        for n in (1024, 4096):
+            budget = n + 64
+            v = Verifier(shape, weights, budget // 16 + 8, 1, blocks, budget)
+            r = v.open()
+            toks = torch.from_numpy(rng.integers(0, shape.vocab, size=n).astype(np.int32)).cuda()
+            v.prefill(r, toks[:per])                      # warm-up of the kernels, then a fresh session
+            v.close_request(r)
+            r = v.open()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            v.prefill(r, toks)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            # projections: 2 x streamed parameters per token (the LM head runs for one row only);
+            # attention: QK^T and PV over the causal triangle, 2 x 2 x d_model x n^2 / 2 per layer
+            flop = 2.0 * (shape.streamed_params() - shape.vocab * shape.d_model) * n + \
+                2.0 * shape.n_layers * shape.n_q_heads * shape.head_dim * float(n) * n
+            print(f"{n:7d} {blocks * per:11d} {dt * 1e3:9.2f} {n / dt:10.0f} {flop / dt / 1e12:15.1f} {flop / dt / MFMA_PEAK_BF16:18.3f}",
+                  flush=True)
+            v.destroy()
+
+
 if __name__ == "__main__":
     sled.lib()
     torch.cuda.set_device(0)
@@ -113,6 +145,8 @@ if __name__ == "__main__":
     elif which == "rows":
         # optional list of row counts, e.g. `rows 1024` for a counter run over one size
         rows_sweep(sizes=tuple(int(a) for a in sys.argv[2:]) or (128, 256, 512, 1024, 2048, 4096))
+    elif which == "prefill":
+        prefill_sweep()
     else:
         print(__doc__)
         sys.exit(2)
