@@ -76,14 +76,18 @@ class Server:
         self.drafts_seen = 0
 
     # ---- sessions ---------------------------------------------------------------------------
-    def open(self, device: int, K: Optional[torch.Tensor] = None, V: Optional[torch.Tensor] = None) -> None:
-        """Start a session; K, V ([layers, tokens, kv heads, head dim], model dtype, on the GPU) is the context
-        the device already has (everything before its pending token)."""
+    def open(self, device: int, K: Optional[torch.Tensor] = None, V: Optional[torch.Tensor] = None,
+             prompt: Optional[Sequence[int]] = None) -> None:
+        """Start a session with the context the device already has (everything before its pending token): either
+        its K/V ([layers, tokens, kv heads, head dim], model dtype, on the GPU), or the prompt tokens themselves,
+        which then run through the target model into the cache (sled_prefill)."""
         assert device not in self.req_of
         r = self.v.open()
         self.req_of[device] = r
         if K is not None and K.shape[1] > 0:
             self.v.append_context([r], [K], [V])
+        if prompt is not None and len(prompt) > 0:
+            self.v.prefill(r, torch.tensor([int(t) for t in prompt], dtype=torch.int32, device=self.device), want_logits=False)
 
     def close(self, device: int) -> None:
         self.v.close_request(self.req_of.pop(device))

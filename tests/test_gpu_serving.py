@@ -13,17 +13,6 @@ from helpers import oracle_model
 pytestmark = pytest.mark.gpu
 
 
-def ingest_prompt(server, device, body, k_max):
-    """Bring a prompt (all but its last token) into the device's session through the verify path itself."""
-    server.open(device)
-    r = server.req_of[device]
-    for s in range(0, len(body), k_max + 1):
-        chunk = body[s: s + k_max + 1]
-        tk = torch.tensor(chunk, dtype=torch.int32, device="cuda")
-        server.v.verify([r], [len(chunk) - 1], tk)
-        server.v.commit([r], torch.tensor([len(chunk) - 1], dtype=torch.int32, device="cuda"))
-
-
 @pytest.mark.parametrize("kind", ["tiny", "tiny_bf16"])
 def test_serving_loop_is_lossless_under_batching_retries_and_churn(kind):
     shape = synth.SHAPES[kind]
@@ -44,7 +33,7 @@ def test_serving_loop_is_lossless_under_batching_retries_and_churn(kind):
 
     wave1 = list(range(6))
     for d in wave1:
-        ingest_prompt(server, d, prompts[d][:-1], shape.k_max)
+        server.open(d, prompt=prompts[d][:-1])
     res = run(wave1, beta=0.7, lose_every=4, seed=3)
     for d in wave1:
         assert res["texts"][d] == truth[d], f"device {d}"
@@ -55,7 +44,7 @@ def test_serving_loop_is_lossless_under_batching_retries_and_churn(kind):
         server.close(d)
     wave2 = [6, 7, 8]
     for d in wave2:
-        ingest_prompt(server, d, prompts[d][:-1], shape.k_max)
+        server.open(d, prompt=prompts[d][:-1])
     res2 = run(wave2, beta=0.4, lose_every=0, seed=5)
     for d in wave2:
         assert res2["texts"][d] == truth[d], f"device {d}"

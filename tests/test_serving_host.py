@@ -41,6 +41,9 @@ class ToyVerifier:
     def append_context(self, reqs, K, V):
         raise AssertionError("not used")
 
+    def prefill(self, r, tokens, want_logits=True):
+        self.ctx[r] += tokens.tolist()
+
     def verify(self, reqs, k, tokens):
         self.calls += 1
         toks = tokens.tolist()
@@ -77,8 +80,8 @@ class ToyVerifier:
         return [len(self.ctx[r]) for r in reqs]
 
 
-def toy_truth(first, n):
-    seq, out = [first], []
+def toy_truth(start, n):
+    seq, out = list(start), []
     for _ in range(n):
         out.append(ToyVerifier.f(seq))
         seq.append(out[-1])
@@ -119,15 +122,15 @@ def test_simulation_ends_with_the_targets_own_text(beta, lose_every, batch):
     s = serving.Server(v, batch, device="cpu")
     n_dev, n_new, k = 5, 30, 4
     first = {d: 10 + d for d in range(n_dev)}
-    truth = {d: toy_truth(first[d], n_new) for d in range(n_dev)}
+    truth = {d: toy_truth([3, 1, 4][: d % 3] + [first[d]], n_new) for d in range(n_dev)}
     for d in range(n_dev):
-        s.open(d)
+        s.open(d, prompt=[3, 1, 4][: d % 3])         # sessions may start from a prompt
     drafters = {d: serving.ReplayDrafter(truth[d], ToyShape.vocab, beta, seed=d) for d in range(n_dev)}
     res = serving.simulate(s, drafters, first, n_new, k, draft_ms_per_token=1.0, seed=1, lose_every=lose_every)
     assert res["devices_off_replayed_path"] == 0
     for d in range(n_dev):
         assert res["texts"][d] == truth[d]
-        assert v.ctx[s.req_of[d]][0] == first[d]
+        assert v.ctx[s.req_of[d]][: d % 3 + 1] == [3, 1, 4][: d % 3] + [first[d]]
     assert res["tokens"] == n_dev * n_new
     if beta == 1.0:
         assert res["accepted_per_draft"] == 1.0
