@@ -12,8 +12,9 @@
 //     accuracy than the 2e-2 logit tolerance allows at 8B scale, so each weight tile is multiplied
 //     with both planes.  All wavefronts of a workgroup need all of them: they go from L2 into a
 //     ring of five LDS stage buffers with direct-to-LDS loads, four stages ahead.
-//   - A workgroup is 8 wavefronts (two per SIMD), all alike: 2 column groups x 4 k-groups.  A stage
-//     is 4 k-steps of 16; k-group g works on the g-th of them for the 64 columns (two 32-column
+//   - A workgroup is 8 wavefronts (two per SIMD), all alike: 2 column groups x 4 k-groups (4 x 2 when the
+//     batch has several blocks of rows, see the two shapes below).  A stage is one k-step of 16 per k-group;
+//     k-group g works on the g-th of them for the 64 columns (two 32-column
 //     tiles) of its column group and all rows of the block (MT 32-row tiles), and the k-groups'
 //     sums are added through LDS at the end, in a fixed order.  This shape follows from three
 //     per-CU limits that all sit within a factor of two of the HBM time: one wavefront sustains
