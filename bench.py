@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--sigma", type=float, default=1.0,
                     help="accept_only: standard deviation of the noise between draft and target logits (the other "
                          "two of 0.25, 1, 4 are reported in the breakdown)")
+    ap.add_argument("--q-top", type=int, default=64,
+                    help="accept_only: also time sled_accept_sparse with the draft distributions cut to this many entries (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy three times before the steps, so that a counter run "
@@ -246,6 +248,28 @@ def bench_accept(args):
                "mean_accept_len": round(float(acc.mean()), 3), "verified_draft_tokens_per_s": round(nd / (p50 * 1e-3), 1),
                "min_bytes": min_bytes, "min_bytes_GBps": round(min_bytes / (p50 * 1e-3) / 1e9, 1),
                "touched_bytes": scan_bytes, "touched_GBps": round(scan_bytes / (p50 * 1e-3) / 1e9, 1)}
+        if args.q_top > 0:
+            # the same logits and drafts with the draft distributions cut to their top entries, through the sparse entry point
+            top = torch.topk(case.q, args.q_top, dim=1)
+            q_ids = top.indices.int().contiguous()
+            q_probs = (top.values / top.values.sum(dim=1, keepdim=True)).float().contiguous()
+
+            def step_sparse():
+                sled.sled_accept_sparse(k, vocab, 1.0, case.logits, case.tokens, q_ids, q_probs, case.u_acc, case.u_smp, a, t, ws)
+
+            for _ in range(args.warmup):
+                step_sparse()
+            torch.cuda.synchronize()
+            ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+            ev2[0].record()
+            for s in range(args.steps):
+                step_sparse()
+                ev2[s + 1].record()
+            torch.cuda.synchronize()
+            lat2 = sorted(ev2[s].elapsed_time(ev2[s + 1]) for s in range(args.steps))
+            rec[f"sparse_top{args.q_top}_p50_ms"] = round(lat2[len(lat2) // 2], 4)
+            rec[f"sparse_top{args.q_top}_mean_accept_len"] = round(float(a.float().mean().item()), 3)
+            del top, q_ids, q_probs
         per_sigma[str(sg)] = rec
         if main is None:
             main = dict(rec, wall=(t1 - t0))

@@ -214,6 +214,21 @@ SLED_API int sled_accept(int mode, int B, const int* k /*host*/, int vocab, floa
                 int32_t* accept_len /*dev out*/, int32_t* out_token /*dev out*/,
                 void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
+/* sled_accept in sampling mode with the draft distributions given sparsely: draft j's distribution q_j is
+ * q_probs[j][i] on token q_ids[j][i] (i < q_m) and zero elsewhere.  This is exact, not an approximation, when
+ * the device drew its draft from that very distribution -- e.g. from its top-q_m tokens renormalised -- because
+ * Eq. 1 and the residual norm(max(0, p - q)) only ever need the q the draft was drawn from; it replaces V floats
+ * per draft token on the uplink (Sec. 3.2 wants tokens, not activations, to travel) by q_m (id, probability) pairs.
+ *   q_ids[sum k, q_m]     dev int32; distinct within a row; an id outside [0, vocab) marks padding
+ *   q_probs[sum k, q_m]   dev float32; a probability of 0 marks padding
+ *   1 <= q_m <= 1024
+ * Everything else as sled_accept (mode SLED_SAMPLE).  A drafted token that is not among its row's ids has
+ * q = 0 and is accepted (product form of Eq. 1). */
+SLED_API int sled_accept_sparse(int B, const int* k /*host*/, int vocab, float temperature, const float* logits /*dev*/,
+                       const int32_t* tokens /*dev*/, int q_m, const int32_t* q_ids /*dev*/, const float* q_probs /*dev*/,
+                       const float* u_acc /*dev*/, const float* u_smp /*dev*/, int32_t* accept_len /*dev out*/,
+                       int32_t* out_token /*dev out*/, void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
 /* ---- kernel timing (measurement aid) ---------------------------------------------- */
 
 /* Kernel classes of one verification step. */

@@ -9,7 +9,9 @@
 //                      takes the first failure.  In sampling mode the workgroup then draws the request's
 //                      one token by inverse CDF from the residual max(0, p - q) of the rejecting row (or
 //                      from p of the bonus row), all in float64 and in a fixed order, so that the chosen
-//                      token does not depend on anything beyond ~1e-15 of the total mass.
+//                      token does not depend on anything beyond ~1e-15 of the total mass.  With draft
+//                      distributions given as a few (token, probability) pairs per draft, the residual's
+//                      mass per tile follows from the sums of p and one pass over the pairs.
 #include "sled_internal.h"
 
 #include <type_traits>
@@ -152,6 +154,24 @@ __device__ inline void row_stat(const RowStat* __restrict__ st, int n_split, flo
     }
 }
 
+// Where the draft distributions come from: dense rows q[sum k, V], or, per draft, `m` (token id, probability)
+// pairs of a distribution that is zero elsewhere (ids distinct; an entry with probability 0 or an id outside
+// the vocabulary is padding).
+struct QSrc {
+    const float* dense;
+    const int32_t* ids;
+    const float* probs;
+    int m;  // 0: dense
+};
+
+__device__ inline double q_of(const QSrc& q, int qrow, int V, int d) {
+    if (q.m == 0) return (double)q.dense[(size_t)qrow * V + d];
+    double v = 0.0;
+    for (int i = 0; i < q.m; i++)
+        if (q.ids[(size_t)qrow * q.m + i] == d) v = (double)q.probs[(size_t)qrow * q.m + i];
+    return v;
+}
+
 struct Decision {
     int a;       // accepted prefix length
     int row;     // packed row the output token comes from (row0 + a)
@@ -164,7 +184,7 @@ struct Decision {
 // accepted prefix (Eq. 1; in greedy mode the test is equality with the row's argmax).
 __device__ inline Decision decide_request(int mode, int i, const KPack& kp, int V, int n_split, float inv_tau,
                                           const float* __restrict__ logits, const int32_t* __restrict__ tokens,
-                                          const float* __restrict__ draft_q, const float* __restrict__ u_acc,
+                                          const QSrc& draft_q, const float* __restrict__ u_acc,
                                           const RowStat* __restrict__ stats, int lane) {
     int row0 = 0;
     for (int r = lane; r < i; r += 64) row0 += kp.k[r];
@@ -187,7 +207,7 @@ __device__ inline Decision decide_request(int mode, int i, const KPack& kp, int 
             } else {
                 const double zd = (double)logits[(size_t)(row0 + j) * V + d];
                 const double pd = exp((zd - (double)m) * (double)inv_tau) / S;
-                const double lhs = (double)u_acc[d0 + j] * (double)draft_q[(size_t)(d0 + j) * V + d];
+                const double lhs = (double)u_acc[d0 + j] * q_of(draft_q, d0 + j, V, d);
                 fail = !(lhs <= pd);
             }
         }
@@ -206,21 +226,25 @@ __device__ inline Decision decide_request(int mode, int i, const KPack& kp, int 
     return dc;
 }
 
+constexpr int SLED_SPARSE_Q_MAX = 1024;  // entries per draft of a sparse draft distribution
 constexpr int WTILE = 1024;        // elements per wavefront tile: 16 consecutive ones per lane
 constexpr int MAX_WTILES = 2048;   // covers vocabularies up to 2 097 152
 
 __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V, int n_split, float inv_tau,
                                                       const float* __restrict__ logits, const int32_t* __restrict__ tokens,
-                                                      const float* __restrict__ draft_q, const float* __restrict__ u_acc,
+                                                      QSrc qsrc, const float* __restrict__ u_acc,
                                                       const float* __restrict__ u_smp, const RowStat* __restrict__ stats,
                                                       int32_t* __restrict__ accept_len, int32_t* __restrict__ out_token) {
     __shared__ double tile_sum[MAX_WTILES];
+    __shared__ double sp_take[SLED_SPARSE_Q_MAX];   // sparse q: probability mass entry i removes from p
+    __shared__ int sp_tile[SLED_SPARSE_Q_MAX];      //           and the tile it falls in (-1: padding)
+    __shared__ double q_tile[WTILE];                //           q over the tile that holds the draw
     __shared__ Decision sh_dc;
     __shared__ int sh_tile;
     __shared__ double sh_base, sh_total;
     const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, n_wv = blockDim.x >> 6;
     if (wv == 0) {
-        const Decision dc = decide_request(mode, i, kp, V, n_split, inv_tau, logits, tokens, draft_q, u_acc, stats, lane);
+        const Decision dc = decide_request(mode, i, kp, V, n_split, inv_tau, logits, tokens, qsrc, u_acc, stats, lane);
         if (lane == 0) {
             sh_dc = dc;
             accept_len[i] = dc.a;
@@ -231,11 +255,13 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     __syncthreads();
     const Decision dc = sh_dc;
     const float* z = logits + (size_t)dc.row * V;
-    const float* q = dc.qrow >= 0 ? draft_q + (size_t)dc.qrow * V : nullptr;
+    const bool sparse = qsrc.m > 0;
+    const bool has_q = dc.qrow >= 0;
+    const float* q = (has_q && !sparse) ? qsrc.dense + (size_t)dc.qrow * V : nullptr;
     const double m = (double)dc.m, it = (double)inv_tau;
     const int n_tiles = (V + WTILE - 1) / WTILE;  // at most MAX_WTILES: the host rejects larger vocabularies
     const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0 &&
-                     (reinterpret_cast<uintptr_t>(draft_q) & 15) == 0;
+                     (reinterpret_cast<uintptr_t>(qsrc.dense) & 15) == 0;
 
     // 16 consecutive values of a row starting at v (0 beyond the end of the row when `pad0`, else -inf)
     auto load16 = [&](const float* p, int v, float* x, float pad) {
@@ -256,16 +282,17 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
         }
     };
     // this lane's 16 weights of tile t: exp((z - m)/tau) (proportional to p), or max(0, p - q) with p = that / S
+    // (with sparse q the residual is only ever needed inside the tile that holds the draw, whose q is in q_tile)
     auto weights = [&](int t, bool residual, double inv_S, double* w) {
         const int v = t * WTILE + lane * 16;
         float zx[16], qx[16];
         load16(z, v, zx, -INFINITY);
-        if (residual) load16(q, v, qx, 0.f);
+        if (residual && !sparse) load16(q, v, qx, 0.f);
 #pragma unroll
         for (int e = 0; e < 16; e++) {
             const double ev = exp(((double)zx[e] - m) * it);  // exp(-inf) = 0 beyond the row
             if (residual) {
-                const double r = ev * inv_S - (double)qx[e];
+                const double r = ev * inv_S - (sparse ? q_tile[lane * 16 + e] : (double)qx[e]);
                 w[e] = r > 0.0 ? r : 0.0;
             } else {
                 w[e] = ev;
@@ -326,10 +353,37 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     double inv_S = 1.0;
     sweep(false, 1.0);  // tile sums of exp((z - m)/tau); their total is the normaliser S
     locate(u);
-    if (q != nullptr) {
+    if (has_q) {
         const double S = sh_total;
         __syncthreads();  // everybody has read the total before the tile sums are replaced
-        sweep(true, 1.0 / S);
+        if (!sparse) {
+            sweep(true, 1.0 / S);
+        } else {
+            // sum over a tile of max(0, p - q) = sum of p - sum over the entries in it of min(p, q): one pass over
+            // the m entries instead of a second pass over the vocabulary
+            const int32_t* ids = qsrc.ids + (size_t)dc.qrow * qsrc.m;
+            const float* pr = qsrc.probs + (size_t)dc.qrow * qsrc.m;
+            for (int e = tid; e < qsrc.m; e += blockDim.x) {
+                const int id = ids[e];
+                const double qv = (double)pr[e];
+                const bool real = id >= 0 && id < V && qv > 0.0;
+                double take = 0.0;
+                if (real) {
+                    const double pv = exp(((double)z[id] - m) * it) * (1.0 / S);
+                    take = pv < qv ? pv : qv;
+                }
+                sp_take[e] = take;
+                sp_tile[e] = real ? id / WTILE : -1;
+            }
+            __syncthreads();
+            for (int t = tid; t < n_tiles; t += blockDim.x) {
+                double r = tile_sum[t] * (1.0 / S);
+                for (int e = 0; e < qsrc.m; e++)   // in entry order: the result does not depend on the thread layout
+                    if (sp_tile[e] == t) r -= sp_take[e];
+                tile_sum[t] = r > 0.0 ? r : 0.0;
+            }
+            __syncthreads();
+        }
         locate(u);
         if (sh_total > 0.0) {
             residual = true;
@@ -340,6 +394,17 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
             sweep(false, 1.0);
             locate(u);
         }
+    }
+    if (residual && sparse) {
+        // q over the tile of the draw, dense in LDS
+        const int tt0 = sh_tile;
+        for (int e = tid; e < WTILE; e += blockDim.x) q_tile[e] = 0.0;
+        __syncthreads();
+        const int32_t* ids = qsrc.ids + (size_t)dc.qrow * qsrc.m;
+        const float* pr = qsrc.probs + (size_t)dc.qrow * qsrc.m;
+        for (int e = tid; e < qsrc.m; e += blockDim.x)
+            if (sp_tile[e] == tt0) q_tile[ids[e] - tt0 * WTILE] = (double)pr[e];
+        __syncthreads();
     }
     if (wv != 0) return;
     // inside the tile: 16 weights per lane, an ordered scan over the lanes, then over the lane's own 16
@@ -401,11 +466,14 @@ int sled_accept_pick_split(int T, int vocab) {
 }
 
 int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, float temperature, const float* logits,
-                       const int32_t* tokens, const float* draft_q, const float* u_acc, const float* u_smp,
-                       int32_t* accept_len, int32_t* out_token, void* ws, hipStream_t st) {
+                       const int32_t* tokens, const float* draft_q, const int32_t* q_ids, const float* q_probs, int q_m,
+                       const float* u_acc, const float* u_smp, int32_t* accept_len, int32_t* out_token, void* ws,
+                       hipStream_t st) {
     if ((vocab + WTILE - 1) / WTILE > MAX_WTILES) SLED_FAIL(SLED_EINVAL, "accept: vocabulary %d too large", vocab);
+    if (q_m < 0 || q_m > SLED_SPARSE_Q_MAX) SLED_FAIL(SLED_EINVAL, "accept: %d sparse entries per draft, at most %d", q_m, SLED_SPARSE_Q_MAX);
     KPack kp;
     for (int i = 0; i < B; i++) kp.k[i] = (uint8_t)k_host[i];
+    QSrc qsrc{draft_q, q_ids, q_probs, q_m};
     const int n_split = sled_accept_pick_split(T, vocab);
     int seg = (vocab + n_split - 1) / n_split;
     seg = (seg + 3) & ~3;
@@ -419,7 +487,7 @@ int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, flo
     SLED_LAUNCH_CHECK();
     // greedy needs only the deciding wavefront
     hipLaunchKernelGGL(accept_finish, dim3(B), dim3(mode == SLED_SAMPLE ? 1024 : 64), 0, st, mode, kp, vocab, n_split, inv_tau,
-                       logits, tokens, draft_q, u_acc, u_smp, stats, accept_len, out_token);
+                       logits, tokens, qsrc, u_acc, u_smp, stats, accept_len, out_token);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

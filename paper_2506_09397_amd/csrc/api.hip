@@ -754,26 +754,58 @@ extern "C" size_t sled_accept_workspace_bytes(int B, int T, int vocab) {
     return sled_accept_ws_bytes(B, T, 16) + 256;
 }
 
+namespace {
+
+// checks shared by the two acceptance entry points; on success *T_out = packed rows, *nd_out = drafts
+int accept_checks(const char* who, int mode, int B, const int* k, int vocab, float temperature, const void* logits,
+                  const void* tokens, const void* accept_len, const void* out_token, void* workspace, size_t workspace_bytes,
+                  int* T_out, int* nd_out) {
+    if (!k || !logits || !tokens || !accept_len || !out_token || !workspace) SLED_FAIL(SLED_EINVAL, "%s: null argument", who);
+    if (mode != SLED_GREEDY && mode != SLED_SAMPLE) SLED_FAIL(SLED_EINVAL, "%s: unknown mode %d", who, mode);
+    if (B < 1 || B > 1024) SLED_FAIL(SLED_EINVAL, "%s: batch size %d outside [1, 1024]", who, B);
+    if (vocab < 2 || vocab > 2000000) SLED_FAIL(SLED_EINVAL, "%s: vocab %d unsupported", who, vocab);
+    if (!(temperature > 0.f)) SLED_FAIL(SLED_EINVAL, "%s: temperature must be positive", who);
+    int T = 0, nd = 0;
+    for (int i = 0; i < B; i++) {
+        if (k[i] < 0 || k[i] > 255) SLED_FAIL(SLED_EINVAL, "%s: k[%d] = %d outside [0, 255]", who, i, k[i]);
+        T += k[i] + 1;
+        nd += k[i];
+    }
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "%s: workspace must be 256-byte aligned", who);
+    const size_t need = sled_accept_ws_bytes(B, T, sled_accept_pick_split(T, vocab));
+    if (need > workspace_bytes) SLED_FAIL(SLED_EINVAL, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
+    *T_out = T;
+    *nd_out = nd;
+    return SLED_OK;
+}
+
+}  // namespace
+
 extern "C" int sled_accept(int mode, int B, const int* k, int vocab, float temperature, const float* logits,
                            const int32_t* tokens, const float* draft_q, const float* u_acc, const float* u_smp,
                            int32_t* accept_len, int32_t* out_token, void* workspace, size_t workspace_bytes,
                            void* stream) {
-    if (!k || !logits || !tokens || !accept_len || !out_token || !workspace) SLED_FAIL(SLED_EINVAL, "sled_accept: null argument");
-    if (mode != SLED_GREEDY && mode != SLED_SAMPLE) SLED_FAIL(SLED_EINVAL, "sled_accept: unknown mode %d", mode);
-    if (B < 1 || B > 1024) SLED_FAIL(SLED_EINVAL, "sled_accept: batch size %d outside [1, 1024]", B);
-    if (vocab < 2 || vocab > 2000000) SLED_FAIL(SLED_EINVAL, "sled_accept: vocab %d unsupported", vocab);
-    if (!(temperature > 0.f)) SLED_FAIL(SLED_EINVAL, "sled_accept: temperature must be positive");
-    int T = 0, nd = 0;
-    for (int i = 0; i < B; i++) {
-        if (k[i] < 0 || k[i] > 255) SLED_FAIL(SLED_EINVAL, "sled_accept: k[%d] = %d outside [0, 255]", i, k[i]);
-        T += k[i] + 1;
-        nd += k[i];
-    }
+    int T, nd;
+    int rc = accept_checks("sled_accept", mode, B, k, vocab, temperature, logits, tokens, accept_len, out_token, workspace,
+                           workspace_bytes, &T, &nd);
+    if (rc != SLED_OK) return rc;
     if (mode == SLED_SAMPLE && (!u_smp || (nd > 0 && (!draft_q || !u_acc))))
         SLED_FAIL(SLED_EINVAL, "sled_accept: sampling needs draft_q, u_acc and u_smp");
-    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_accept: workspace must be 256-byte aligned");
-    const size_t need = sled_accept_ws_bytes(B, T, sled_accept_pick_split(T, vocab));
-    if (need > workspace_bytes) SLED_FAIL(SLED_EINVAL, "sled_accept: workspace of %zu bytes, %zu needed", workspace_bytes, need);
-    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, u_acc, u_smp, accept_len, out_token,
-                              workspace, static_cast<hipStream_t>(stream));
+    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, nullptr, nullptr, 0, u_acc, u_smp,
+                              accept_len, out_token, workspace, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int sled_accept_sparse(int B, const int* k, int vocab, float temperature, const float* logits, const int32_t* tokens,
+                                  int q_m, const int32_t* q_ids, const float* q_probs, const float* u_acc, const float* u_smp,
+                                  int32_t* accept_len, int32_t* out_token, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    int T, nd;
+    int rc = accept_checks("sled_accept_sparse", SLED_SAMPLE, B, k, vocab, temperature, logits, tokens, accept_len, out_token,
+                           workspace, workspace_bytes, &T, &nd);
+    if (rc != SLED_OK) return rc;
+    if (q_m < 1 || q_m > 1024) SLED_FAIL(SLED_EINVAL, "sled_accept_sparse: %d entries per draft outside [1, 1024]", q_m);
+    if (!u_smp || (nd > 0 && (!q_ids || !q_probs || !u_acc)))
+        SLED_FAIL(SLED_EINVAL, "sled_accept_sparse: needs q_ids, q_probs, u_acc and u_smp");
+    return sled_launch_accept(SLED_SAMPLE, B, T, k, vocab, temperature, logits, tokens, nullptr, q_ids, q_probs, q_m, u_acc,
+                              u_smp, accept_len, out_token, workspace, static_cast<hipStream_t>(stream));
 }

@@ -114,6 +114,82 @@ def test_acceptance_alone_full_size(sigma):
     assert lo <= mean_a <= hi, mean_a
 
 
+def _sparse_case(k, vocab, m, sigma, seed, pad=0):
+    """Drafts drawn from the top-m tokens (renormalised) of softmax(target row + sigma * noise); returns the case
+    with the dense truncated q (for the oracle) and the (ids, probs) pairs, `pad` padding entries appended."""
+    case = synth.accept_case(k, vocab, sigma, seed=seed, device="cuda")
+    top = torch.topk(case.q, m, dim=1)
+    probs = (top.values / top.values.sum(dim=1, keepdim=True)).float()
+    ids = top.indices.int()
+    g = torch.Generator(device="cuda").manual_seed(seed + 1)
+    pick = torch.multinomial(probs, 1, generator=g).squeeze(1)
+    drafts = ids[torch.arange(ids.shape[0], device="cuda"), pick]
+    off = doff = 0
+    for ki in k:
+        case.tokens[off + 1: off + 1 + ki] = drafts[doff: doff + ki]
+        off += ki + 1
+        doff += ki
+    dense = torch.zeros_like(case.q)
+    dense.scatter_(1, ids.long(), probs)
+    case.q = dense
+    if pad:
+        ids = torch.cat([ids, torch.full((ids.shape[0], pad), -1, dtype=torch.int32, device="cuda")], dim=1)
+        probs = torch.cat([probs, torch.zeros(probs.shape[0], pad, device="cuda")], dim=1)
+        # padding may sit anywhere in a row
+        perm = torch.randperm(ids.shape[1], generator=g, device="cuda")
+        ids, probs = ids[:, perm].contiguous(), probs[:, perm].contiguous()
+    return case, ids.contiguous(), probs.contiguous()
+
+
+def _run_sparse(case, vocab, ids, probs, temperature=1.0):
+    B, T = len(case.k), sum(case.k) + len(case.k)
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(B, T, vocab))
+    a = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    t = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    sled.sled_accept_sparse(case.k, vocab, temperature, case.logits, case.tokens, ids, probs, case.u_acc, case.u_smp, a, t, ws)
+    torch.cuda.synchronize()
+    return a.cpu().numpy(), t.cpu().numpy()
+
+
+@pytest.mark.parametrize("vocab,k,m,pad", [
+    (1024, [4, 4, 4, 4], 8, 0),
+    (4099, [8, 0, 3, 5, 1], 64, 5),        # odd vocabulary, padding entries
+    (32000, [2, 4, 6, 8] * 4, 256, 0),
+    (128256, [2, 8, 5, 3, 7, 4] * 3, 64, 0),
+    (1000, [6, 6, 6], 1, 0),               # one-hot q: a greedy drafter
+    (5000, [3] * 5, 1024, 0),              # the largest row the entry point takes
+])
+@pytest.mark.parametrize("sigma", [0.5, 2.0])
+def test_sparse_draft_distributions_match_oracle(vocab, k, m, pad, sigma):
+    case, ids, probs = _sparse_case(k, vocab, m, sigma, seed=vocab + m, pad=pad)
+    a, t = _run_sparse(case, vocab, ids, probs)
+    want = oracle_accept(sled.SAMPLE, case)
+    n_sub = compare_accept(sled.SAMPLE, k, a, t, want, f"V={vocab} m={m} sigma={sigma}")
+    assert n_sub <= 1
+    # and the dense entry point, given the same truncated q, agrees
+    a2, t2 = run_accept_gpu(sled.SAMPLE, case, vocab)
+    assert compare_accept(sled.SAMPLE, k, a2, t2, want) <= 1
+
+
+def test_sparse_token_outside_its_row_is_accepted_and_errors():
+    vocab, k = 2048, [3, 2]
+    case, ids, probs = _sparse_case(k, vocab, 16, 1.0, seed=3)
+    # a draft that its own row does not list has q = 0: the product form of Eq. 1 accepts it
+    outside = [t for t in range(vocab) if t not in set(ids[0].tolist())][0]
+    case.tokens[1] = outside
+    a, t = _run_sparse(case, vocab, ids, probs)
+    want = oracle_accept(sled.SAMPLE, case)
+    assert want[0]["accept_len"] >= 1
+    assert compare_accept(sled.SAMPLE, k, a, t, want) <= 1
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(2, 7, vocab))
+    o = torch.zeros(2, dtype=torch.int32, device="cuda")
+    big_i = torch.zeros(5, 1025, dtype=torch.int32, device="cuda")
+    with pytest.raises(sled.SledError):
+        sled.sled_accept_sparse(k, vocab, 1.0, case.logits, case.tokens, big_i, big_i.float(), case.u_acc, case.u_smp, o, o.clone(), ws)
+    with pytest.raises(sled.SledError):
+        sled.sled_accept_sparse(k, vocab, 0.0, case.logits, case.tokens, ids, probs, case.u_acc, case.u_smp, o, o.clone(), ws)
+
+
 def test_accept_argument_errors():
     vocab, k = 1024, [2, 2]
     case = synth.accept_case(k, vocab, 1.0, seed=1, device="cuda")

@@ -140,6 +140,31 @@ def test_sampling_preserves_target_distribution_chi_square():
     assert stats.chisquare(wrong, p[0] * N).pvalue < 1e-6
 
 
+def test_truncated_draft_distribution_is_lossless_when_the_draft_was_drawn_from_it():
+    """A device that drafts from its top-m tokens renormalised and sends only those m (id, probability) pairs
+    loses nothing: Eq. 1 with that truncated q still emits exactly p.  Using the truncated q for a draft that
+    was drawn from the FULL q, however, is not lossless -- so the exactness is a property of how the draft was
+    drawn, which the sparse entry point's contract states."""
+    rng = np.random.default_rng(77)
+    V, m, N = 12, 4, 30000
+    z, p = _random_dists(rng, 2, V)
+    _, q_full = _random_dists(rng, 1, V, sharp=1.0)
+    top = np.argsort(-q_full[0])[:m]
+    q_trunc = np.zeros((1, V))
+    q_trunc[0, top] = q_full[0, top] / q_full[0, top].sum()
+    good = np.zeros(V)
+    bad = np.zeros(V)
+    for _ in range(N):
+        d = int(rng.choice(V, p=q_trunc[0]))
+        r = O.accept_sample(z, [d], q_trunc, rng.random(1), rng.random())
+        good[([d][: r["accept_len"]] + [r["out_token"]])[0]] += 1
+        d = int(rng.choice(V, p=q_full[0]))
+        r = O.accept_sample(z, [d], q_trunc, rng.random(1), rng.random())
+        bad[([d][: r["accept_len"]] + [r["out_token"]])[0]] += 1
+    assert stats.chisquare(good, p[0] * N).pvalue > 1e-3
+    assert stats.chisquare(bad, p[0] * N).pvalue < 1e-6
+
+
 def test_expected_accept_length_closed_form():
     """Same (p, q) in every row: E[accept_len] = beta (1 - beta^k) / (1 - beta)."""
     rng = np.random.default_rng(5)
