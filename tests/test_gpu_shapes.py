@@ -119,3 +119,19 @@ def test_llama70b_shape_two_layers():
         if r["margin"] > 0:
             assert (int(a[i]), int(t[i])) == (r["accept_len"], r["out_token"]), f"request {i}"
     v.destroy()
+
+
+def test_512_rows_four_row_blocks_per_weight_tile():
+    """512 packed rows on the 8B layer shape (one layer, vocabulary 65536): every projection runs in the wide
+    workgroup shape with four 128-row blocks per weight tile (split-K partials, SwiGLU and logits epilogues).
+    All rows of a sample of requests against the oracle."""
+    shape = synth.scaled_shape(synth.SHAPES["llama8b"], n_layers=1, vocab=65536)
+    B = 64
+    batch = synth.make_batch([16 + (i % 5) for i in range(B)], [7] * B, shape.vocab, seed=21)
+    assert batch.T == 512
+    sample = [0, 9, 17, 31, 32, 47, 63]    # rows from all four blocks
+    v, w, reqs, KV = _setup(shape, batch, 6, set(sample))
+    got = v.verify(reqs, batch.k, torch.from_numpy(batch.tokens).cuda()).cpu().numpy().astype(np.float64)
+    errs = _logit_errors(shape, w, batch, KV, got, sample, "8B layer shape, 512 rows")
+    assert max(errs) < TOL_BF16
+    v.destroy()
