@@ -43,6 +43,8 @@ def parse():
                          "two of 0.25, 1, 4 are reported in the breakdown)")
     ap.add_argument("--q-top", type=int, default=64,
                     help="accept_only: also time sled_accept_sparse with the draft distributions cut to this many entries (0 = skip)")
+    ap.add_argument("--batch-invariant", action="store_true",
+                    help="time the step with sled_model_set_batch_invariant on (results independent of the batch to the last bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy three times before the steps, so that a counter run "
@@ -84,7 +86,7 @@ def main():
     ctx_budget = sum(batch.ctx_len) + B * (shape.k_max + 1) * (total_steps + 1)
     n_pages = ctx_budget // 16 + 2 * B + 8
     weights = synth.SynthWeights(shape, seed=args.seed, device="cuda")
-    v = Verifier(shape, weights, n_pages, B, B, ctx_budget)
+    v = Verifier(shape, weights, n_pages, B, B, ctx_budget, batch_invariant=args.batch_invariant)
     reqs = [v.open() for _ in range(B)]
     KV = []
     for i in range(B):
@@ -181,7 +183,7 @@ def main():
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers d={shape.d_model} Hq/Hkv={shape.n_q_heads}/"
                                f"{shape.n_kv_heads} F={shape.d_ffn} V={shape.vocab}, B={B}, T={T} packed rows, "
                                f"{n_drafts} draft tokens, {sum(lens)} context tokens, {'sampling' if sampling else 'greedy'} acceptance, "
-                               f"seed {args.seed}"},
+                               f"seed {args.seed}" + (", batch-invariant mode" if args.batch_invariant else "")},
         "roofline": roofline, "breakdown": breakdown, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

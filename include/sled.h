@@ -108,6 +108,13 @@ SLED_API int sled_model_create(const sled_shape* shape /*host*/, sled_model** ou
  * may be freed once the stream has passed this point.  Errors: SLED_EINVAL. */
 SLED_API int sled_model_load(sled_model* m, int tensor_id, int layer, const void* src /*dev*/, void* stream);
 
+/* on != 0: the logits of a request no longer depend, not even in the last bit, on which other requests share its
+ * batch or on how many rows the batch has -- so a greedy text is the same however the server happens to batch it.
+ * The projections then keep one workgroup shape at every batch size and attention sums a request's keys in fixed
+ * runs of 768 tokens instead of runs balanced over the CUs for the batch at hand; both cost speed on large or
+ * uneven batches.  Set it before sizing workspaces (sled_verify_workspace_bytes depends on it).  Default: off. */
+SLED_API int sled_model_set_batch_invariant(sled_model* m, int on);
+
 SLED_API int sled_model_destroy(sled_model* m);
 
 /* ---- paged K/V pool -------------------------------------------------------------- */

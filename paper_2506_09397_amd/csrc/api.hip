@@ -169,6 +169,12 @@ struct prof_scope {
     }
 };
 
+extern "C" int sled_model_set_batch_invariant(sled_model* m, int on) {
+    if (!m) SLED_FAIL(SLED_EINVAL, "sled_model_set_batch_invariant: null model");
+    m->batch_invariant = on != 0;
+    return SLED_OK;
+}
+
 extern "C" int sled_profile_enable(sled_model* m, int on) {
     if (!m) SLED_FAIL(SLED_EINVAL, "sled_profile_enable: null model");
     m->prof_on = on != 0;
@@ -440,6 +446,7 @@ struct ws_plan {
 // kv head) pairs than that), all of similar size.  Returns the largest number of pages an item may
 // hold so that the item count stays within that cap; each pair then splits its pages evenly.
 constexpr int ATTN_CUS = 256;
+constexpr int SLED_FIXED_CHUNK_PAGES = 48;  // 768 tokens; divisible by 4, 3 and 2 page groups
 int attn_item_cap(int B, int Hkv) { return ATTN_CUS * ((B * Hkv + ATTN_CUS - 1) / ATTN_CUS); }
 int attn_pages_per_item(const std::vector<int>& np, int Hkv) {
     int64_t total = 0;
@@ -493,8 +500,11 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
 
 // upper bound of the attention work list
 int max_work_items(const sled_model* m, int B, int64_t ctx_tokens) {
-    (void)ctx_tokens;
-    return attn_item_cap(B, m->s.n_kv_heads) + B * m->s.n_kv_heads;
+    const int balanced = attn_item_cap(B, m->s.n_kv_heads) + B * m->s.n_kv_heads;
+    if (!m->batch_invariant) return balanced;
+    // fixed runs of pages: one item per started run of every block and kv head
+    const int64_t runs = ctx_tokens / (16 * SLED_FIXED_CHUNK_PAGES) + B;
+    return (int)std::max<int64_t>(balanced, runs * m->s.n_kv_heads);
 }
 
 }  // namespace
@@ -543,12 +553,15 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
         np_all[i] = ceil_div(reach, 16);
         total_pages += np_all[i];
     }
-    const int tgt = attn_pages_per_item(np_all, Hkv);
+    // Pages per attention work item.  Normally whatever spreads this batch evenly over the CUs; for a
+    // batch-invariant model a fixed run of pages, so that the keys of a request are always summed in the same
+    // groups (a multiple of every page-group count the kernel uses).
+    const int tgt = m->batch_invariant ? 0 : attn_pages_per_item(np_all, Hkv);
     std::vector<int32_t> work;
     std::vector<int32_t> cu_work(B * Hkv + 1);
     for (int i = 0; i < B; i++) {
         const int np = np_all[i];
-        const int chunk = ceil_div(np, ceil_div(np, tgt));  // even split of this block's pages
+        const int chunk = m->batch_invariant ? SLED_FIXED_CHUNK_PAGES : ceil_div(np, ceil_div(np, tgt));  // even split of this block's pages
         for (int g = 0; g < Hkv; g++) {
             cu_work[i * Hkv + g] = (int)(work.size() / 4);
             for (int p0 = 0; p0 < np; p0 += chunk) {
@@ -561,7 +574,9 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     }
     const int n_work = (int)(work.size() / 4);
     cu_work[B * Hkv] = n_work;
-    const int QT = std::max(1, ceil_div(G * nmax, 16));
+    // query tiles follow the longest block of the batch -- or, batch-invariant, of the model: the tile count sets
+    // the number of page groups a workgroup splits its pages over
+    const int QT = std::max(1, ceil_div(G * (m->batch_invariant ? s.k_max + 1 : nmax), 16));
     const ws_plan wp = plan_workspace(m, T, n_work, QT);
     if (wp.total > workspace_bytes) SLED_FAIL(SLED_EINVAL, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, wp.total);
 
@@ -714,7 +729,8 @@ extern "C" int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tok
     const int per = s.k_max + 1;  // rows of one block: what the attention kernel's query tiles are sized for
     const int QT = ceil_div(s.n_q_heads / s.n_kv_heads * per, 16);
     // the largest number of blocks per step that the workspace holds
-    auto fits = [&](int blocks) { return plan_workspace(m, blocks * per, max_work_items(m, blocks, 0), QT).total <= workspace_bytes; };
+    const int64_t reach = (int64_t)p->reqs[req_id].len_ub + n_tokens;  // every block of a slice may see that many keys
+    auto fits = [&](int blocks) { return plan_workspace(m, blocks * per, max_work_items(m, blocks, blocks * reach), QT).total <= workspace_bytes; };
     if (!fits(1)) SLED_FAIL(SLED_EINVAL, "sled_prefill: workspace of %zu bytes is too small for one block of %d rows", workspace_bytes, per);
     int lo = 1, hi = ceil_div(n_tokens, per);
     while (lo < hi) {  // fits(lo) holds

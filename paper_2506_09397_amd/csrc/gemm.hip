@@ -458,9 +458,11 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         const int mt_total = T_pad / 32;
         // rows are processed in blocks of at most 4 tiles (128 rows): one block -> narrow shape with exactly its
         // tiles; several -> wide shape, four tiles each (the last block may reach past the end)
-        const bool wide = mt_total > 4;
+        // (a batch-invariant model keeps the narrow shape at every size: the two shapes add the k-steps up in
+        // different groupings, so a row's sums would depend on whether its batch has more than 128 rows)
+        const bool wide = mt_total > 4 && !m->batch_invariant;
         const int zb = (mt_total + 3) / 4;
-        const int MT = wide ? 4 : mt_total;
+        const int MT = wide ? 4 : (mt_total + zb - 1) / zb;
         const int KG = wide ? WIDE_KG : NARROW_KG, CG = wide ? WIDE_CG : NARROW_CG;
         gemm_args a;
         a.n_col = (NT + CG * NW - 1) / (CG * NW);

@@ -103,6 +103,8 @@ struct sled_model {
     float* g_final;
     std::vector<sled_layer_weights> layers;
     std::vector<void*> allocs;
+    // results of a request bit-identical whatever batch it is verified in (sled_model_set_batch_invariant)
+    bool batch_invariant = false;
     // kernel timing (sled_profile_enable): one (class, start event, end event) per launch
     struct prof_span {
         int cls;

@@ -13,9 +13,11 @@ from .synth import ModelShape
 
 class Verifier:
     def __init__(self, shape: ModelShape, weights, n_pages: int, max_requests: int, B_max: int,
-                 ctx_tokens_max: int):
+                 ctx_tokens_max: int, batch_invariant: bool = False):
         self.shape = shape
         self.model = sled.sled_model_create(shape)
+        if batch_invariant:
+            sled.sled_model_set_batch_invariant(self.model, True)   # before the workspace is sized
         sled.load_weights(self.model, weights)
         self.pool = sled.sled_kvpool_create(self.model, n_pages, max_requests)
         self.T_max = B_max * (shape.k_max + 1)

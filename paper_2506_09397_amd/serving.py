@@ -287,6 +287,8 @@ def main() -> None:
     ap.add_argument("--context", type=int, default=1024, help="mean context length (uniform in [c/2, 3c/2])")
     ap.add_argument("--draft-ms", type=float, default=10.0, help="device time per draft token")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--batch-invariant", action="store_true",
+                    help="make a request's logits independent of its batch to the last bit (sled_model_set_batch_invariant)")
     ap.add_argument("--sweep", action="store_true", help="run batch sizes 4..32 x k in {2, 4, 8} instead of --batch/--k")
     args = ap.parse_args()
     sled.lib()
@@ -298,7 +300,8 @@ def main() -> None:
     ctx = rng.integers(args.context // 2, args.context * 3 // 2 + 1, size=args.devices).tolist()
     budget = sum(ctx) + args.devices * (2 * args.tokens + 4 * (shape.k_max + 1))
     weights = synth.SynthWeights(shape, seed=args.seed, device="cuda")
-    v = Verifier(shape, weights, budget // 16 + 3 * args.devices + 8, args.devices, args.devices, budget)
+    v = Verifier(shape, weights, budget // 16 + 3 * args.devices + 8, args.devices, args.devices, budget,
+                 batch_invariant=args.batch_invariant)
     server = Server(v, args.batch)
     devs = list(range(args.devices))
     first = [int(x) for x in rng.integers(0, shape.vocab, size=args.devices)]
@@ -322,7 +325,7 @@ def main() -> None:
         ok = ok and res["devices_off_replayed_path"] == 0
         res.pop("texts")
         res.update({"shape": args.shape, "layers": shape.n_layers, "devices": args.devices, "batch": batch, "k": k,
-                    "beta": args.beta, "draft_ms_per_token": args.draft_ms, "mean_context": int(np.mean(ctx))})
+                    "beta": args.beta, "draft_ms_per_token": args.draft_ms, "mean_context": int(np.mean(ctx)), "batch_invariant": args.batch_invariant})
         print(json.dumps({k_: (round(x, 3) if isinstance(x, float) else x) for k_, x in res.items()}), flush=True)
     v.destroy()
     if not ok:

@@ -27,7 +27,7 @@ TENSOR_IDS = {"embed": T_EMBED, "wq": T_WQ, "wk": T_WK, "wv": T_WV, "wo": T_WO, 
               "wd": T_WDOWN, "g_attn": T_G_ATTN, "g_mlp": T_G_MLP, "g_final": T_G_FINAL, "lm_head": T_LM_HEAD}
 
 EXPORTS = [
-    "sled_model_create", "sled_model_load", "sled_model_destroy",
+    "sled_model_create", "sled_model_load", "sled_model_destroy", "sled_model_set_batch_invariant",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
     "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
     "sled_accept_workspace_bytes", "sled_accept", "sled_accept_sparse", "sled_profile_enable", "sled_profile_read",
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
     L.sled_model_create.argtypes = [C.POINTER(_Shape), C.POINTER(vp)]
     L.sled_model_load.argtypes = [vp, C.c_int, C.c_int, vp, vp]
     L.sled_model_destroy.argtypes = [vp]
+    L.sled_model_set_batch_invariant.argtypes = [vp, C.c_int]
     L.sled_kvpool_create.argtypes = [vp, C.c_int64, C.c_int, C.POINTER(vp)]
     L.sled_kvpool_open.argtypes = [vp, ip]
     L.sled_kvpool_close.argtypes = [vp, C.c_int]
@@ -208,6 +209,10 @@ def sled_accept_sparse(k: Sequence[int], vocab: int, temperature: float, logits:
     _check(lib().sled_accept_sparse(len(k), _ints(k), vocab, float(temperature), _ptr(logits), _ptr(tokens), int(q_ids.shape[-1]),
                                     _ptr(q_ids), _ptr(q_probs), _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sled_model_set_batch_invariant(model: int, on: bool) -> None:
+    _check(lib().sled_model_set_batch_invariant(model, 1 if on else 0))
 
 
 def sled_profile_enable(model: int, on: bool) -> None:
