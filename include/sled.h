@@ -79,6 +79,9 @@ extern "C" {
 #define SLED_T_G_MLP    9   /* [d_model] RMSNorm gain before the MLP                    */
 #define SLED_T_G_FINAL 10   /* [d_model] final RMSNorm gain             (layer ignored) */
 #define SLED_T_LM_HEAD 11   /* [vocab, d_model]                         (layer ignored) */
+/* models with 8-bit (FP8) weights (sled_model_set_weight_bits): SLED_T_SCALE + a matrix id names that matrix's
+ * per-output-row scales, float32 [rows] */
+#define SLED_T_SCALE  100
 
 typedef struct sled_model  sled_model;
 typedef struct sled_kvpool sled_kvpool;
@@ -107,6 +110,17 @@ SLED_API int sled_model_create(const sled_shape* shape /*host*/, sled_model** ou
  * model.  `layer` in [0, n_layers) for per-layer tensors.  Asynchronous on `stream`; `src`
  * may be freed once the stream has passed this point.  Errors: SLED_EINVAL. */
 SLED_API int sled_model_load(sled_model* m, int tensor_id, int layer, const void* src /*dev*/, void* stream);
+
+/* bits = 8: the projection matrices (WQ .. WDOWN, LM_HEAD) are stored as 8-bit floats -- FP8 E4M3 in the OCP
+ * encoding, which gfx950 widens to bf16 in hardware -- with one float32 scale per output row,
+ * W[n][k] = fp8[n][k] * scale[n]: weight-only quantisation, the 8-bit point of the paper's bit-width sweep
+ * (Sec. 5).  Activations, K/V cache and arithmetic stay as in a bf16 model (an FP8 value is exact in bf16; the
+ * scale is applied to the float32 accumulator), so the weight stream halves and nothing else changes.
+ * Call it right after sled_model_create, before any sled_model_load; the matrices are then loaded as FP8 bytes
+ * [out, in] (dev) and their scales under SLED_T_SCALE + id.  NaN encodings are the caller's to avoid.  bf16
+ * models whose projection widths are multiples of 64 only.  bits = 16 restores the default.
+ * Errors: SLED_EINVAL, SLED_ENOMEM. */
+SLED_API int sled_model_set_weight_bits(sled_model* m, int bits);
 
 /* on != 0: the logits of a request no longer depend, not even in the last bit, on which other requests share its
  * batch or on how many rows the batch has -- so a greedy text is the same however the server happens to batch it.

@@ -119,7 +119,41 @@ extern "C" int sled_model_load(sled_model* m, int tensor_id, int layer, const vo
     const int d = s.d_model, F = s.d_ffn, D = s.head_dim, HD = s.n_q_heads * D, KD = s.n_kv_heads * D;
     const bool per_layer = tensor_id >= SLED_T_WQ && tensor_id <= SLED_T_G_MLP;
     if (per_layer && (layer < 0 || layer >= s.n_layers)) SLED_FAIL(SLED_EINVAL, "sled_model_load: layer %d out of range", layer);
+    if (tensor_id >= SLED_T_SCALE) {
+        // scales of an 8-bit matrix: float32 [rows], into the row order of the fused matrix
+        const int mat = tensor_id - SLED_T_SCALE;
+        if (!m->w8) SLED_FAIL(SLED_EINVAL, "sled_model_load: scales given to a model without 8-bit weights");
+        const bool lay = mat >= SLED_T_WQ && mat <= SLED_T_WDOWN;
+        if (lay && (layer < 0 || layer >= s.n_layers)) SLED_FAIL(SLED_EINVAL, "sled_model_load: layer %d out of range", layer);
+        sled_layer_weights* ws = lay ? &m->layers[layer] : nullptr;
+        const float* f = static_cast<const float*>(src);
+        switch (mat) {
+            case SLED_T_WQ: return sled_launch_scatter_scales(f, ws->s_qkv, HD, 0, 1, st);
+            case SLED_T_WK: return sled_launch_scatter_scales(f, ws->s_qkv, KD, HD, 1, st);
+            case SLED_T_WV: return sled_launch_scatter_scales(f, ws->s_qkv, KD, HD + KD, 1, st);
+            case SLED_T_WO: return sled_launch_scatter_scales(f, ws->s_o, d, 0, 1, st);
+            case SLED_T_WGATE: return sled_launch_scatter_scales(f, ws->s_gu, F, 0, 2, st);
+            case SLED_T_WUP: return sled_launch_scatter_scales(f, ws->s_gu, F, 1, 2, st);
+            case SLED_T_WDOWN: return sled_launch_scatter_scales(f, ws->s_down, d, 0, 1, st);
+            case SLED_T_LM_HEAD: return sled_launch_scatter_scales(f, m->s_lm, s.vocab, 0, 1, st);
+            default: SLED_FAIL(SLED_EINVAL, "sled_model_load: tensor %d has no scales", mat);
+        }
+    }
     sled_layer_weights* w = per_layer ? &m->layers[layer] : nullptr;
+    if (m->w8) {
+        // matrices arrive as FP8 E4M3 bytes [out, in]
+        switch (tensor_id) {
+            case SLED_T_WQ: return sled_launch_pack_rows_w8(src, w->w_qkv, HD, d, 0, 1, m->n_qkv, st);
+            case SLED_T_WK: return sled_launch_pack_rows_w8(src, w->w_qkv, KD, d, HD, 1, m->n_qkv, st);
+            case SLED_T_WV: return sled_launch_pack_rows_w8(src, w->w_qkv, KD, d, HD + KD, 1, m->n_qkv, st);
+            case SLED_T_WO: return sled_launch_pack_rows_w8(src, w->w_o, d, HD, 0, 1, d, st);
+            case SLED_T_WGATE: return sled_launch_pack_rows_w8(src, w->w_gu, F, d, 0, 2, 2 * F, st);
+            case SLED_T_WUP: return sled_launch_pack_rows_w8(src, w->w_gu, F, d, 1, 2, 2 * F, st);
+            case SLED_T_WDOWN: return sled_launch_pack_rows_w8(src, w->w_down, d, F, 0, 1, d, st);
+            case SLED_T_LM_HEAD: return sled_launch_pack_rows_w8(src, m->lm_head, s.vocab, d, 0, 1, s.vocab, st);
+            default: break;  // embedding and gains as in a 16-bit model
+        }
+    }
     switch (tensor_id) {
         case SLED_T_EMBED:
             SLED_HIP(hipMemcpyAsync(m->embed, src, (size_t)s.vocab * d * m->elem, hipMemcpyDeviceToDevice, st));
@@ -168,6 +202,35 @@ struct prof_scope {
         m->prof_spans.push_back(sp);
     }
 };
+
+extern "C" int sled_model_set_weight_bits(sled_model* m, int bits) {
+    if (!m) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: null model");
+    if (bits == 16) {
+        m->w8 = false;
+        return SLED_OK;
+    }
+    if (bits != 8) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: %d bits unsupported (16 or 8)", bits);
+    const sled_shape& s = m->s;
+    if (s.dtype != SLED_BF16) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: 8-bit weights need a bf16 model");
+    if (m->n_qkv % 64 || s.d_model % 64 || (2 * s.d_ffn) % 64 || s.vocab % 64)
+        SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: output widths must be multiples of 64");
+    if (!m->s_lm) {
+        int rc = SLED_OK;
+        auto A = [&](float** p, size_t n) {
+            if (rc == SLED_OK) rc = model_alloc(m, reinterpret_cast<void**>(p), n * sizeof(float));
+        };
+        A(&m->s_lm, s.vocab);
+        for (auto& w : m->layers) {
+            A(&w.s_qkv, m->n_qkv);
+            A(&w.s_o, s.d_model);
+            A(&w.s_gu, 2 * (size_t)s.d_ffn);
+            A(&w.s_down, s.d_model);
+        }
+        if (rc != SLED_OK) return rc;
+    }
+    m->w8 = true;
+    return SLED_OK;
+}
 
 extern "C" int sled_model_set_batch_invariant(sled_model* m, int on) {
     if (!m) SLED_FAIL(SLED_EINVAL, "sled_model_set_batch_invariant: null model");
@@ -664,28 +727,28 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, pl_d, m->layers[0].g_attn, st));
     for (int l = 0; l < s.n_layers; l++) {
         const sled_layer_weights& w = m->layers[l];
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, g_qkv, partial, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_qkv, w.s_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, g_qkv, partial, nullptr, 0, 0, st));
         SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, meta, l, partial, g_qkv.split, T_pad, cs, qb, pl_hd, st));
         SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, part_o, part_ml, arrive, xo, pl_hd, QT, st));
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, pl_hd, w.w_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, g_o, partial, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, pl_hd, w.w_o, w.s_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, g_o, partial, nullptr, 0, 0, st));
         SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_o.split, T, T_pad, h, xa, pl_d, w.g_mlp, st));
         if (gu_fused) {
-            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, g_gu, nullptr, xf, pl_f, F, st));
+            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_gu, w.s_gu, T, T_pad, 2 * F, d, SLED_EPI_SWIGLU, g_gu, nullptr, xf, pl_f, F, st));
         } else {
-            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, g_gu, partial, nullptr, 0, 0, st));
+            SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_gu, w.s_gu, T, T_pad, 2 * F, d, SLED_EPI_PARTIAL, g_gu, partial, nullptr, 0, 0, st));
             SLED_RUN(SLED_PROF_ROWS, sled_launch_swiglu_reduce(m, partial, g_gu.split, T, T_pad, xf, pl_f, st));
         }
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xf, pl_f, w.w_down, T, T_pad, d, F, SLED_EPI_PARTIAL, g_dn, partial, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xf, pl_f, w.w_down, w.s_down, T, T_pad, d, F, SLED_EPI_PARTIAL, g_dn, partial, nullptr, 0, 0, st));
         const float* next_gain = (l + 1 < s.n_layers) ? m->layers[l + 1].g_attn : m->g_final;
         SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_dn.split, T, T_pad, h, xa, pl_d, next_gain, st));
     }
     if (logits_all) {
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, m->lm_head, T, T_pad, s.vocab, d, SLED_EPI_STORE, g_lm, logits_all, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, m->lm_head, m->s_lm, T, T_pad, s.vocab, d, SLED_EPI_STORE, g_lm, logits_all, nullptr, 0, 0, st));
     } else if (one_row >= 0 && logits_one) {
         // the LM head over one row: that row becomes row 0 of a one-tile activation block
         const size_t pl_1 = bf ? (size_t)32 * d : 0;
         SLED_RUN(SLED_PROF_ROWS, sled_launch_copy_act_row(m, xa, pl_d, one_row, x1, pl_1, d, st));
-        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, x1, pl_1, m->lm_head, 1, 32, s.vocab, d, SLED_EPI_STORE, g_lm, logits_one, nullptr, 0, 0, st));
+        SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, x1, pl_1, m->lm_head, m->s_lm, 1, 32, s.vocab, d, SLED_EPI_STORE, g_lm, logits_one, nullptr, 0, 0, st));
     }
     SLED_TRY(stage_release(sl, st));
 #undef SLED_RUN

@@ -70,10 +70,32 @@ __device__ __forceinline__ void wait_loads(u32x4_t& a, u32x4_t& b) {
     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
 }
 
-// MT: 32-row tiles of activations per block.
-template <int MT, int EPI, int KG, int CG>
+// Eight 8-bit weights (FP8 E4M3, the OCP flavour gfx950 converts in hardware) -> a bf16 MFMA operand: one
+// instruction per pair, exact (three mantissa bits fit bf16's seven).
+__device__ __forceinline__ bf16x8_t cvt_w8(uint32_t lo, uint32_t hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_hw;
+    const u32x4_t p = {__builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false)),
+                       __builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true)),
+                       __builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false)),
+                       __builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true))};
+    return __builtin_bit_cast(bf16x8_t, p);
+}
+
+// the same for a single register (never pass one register twice to the two-operand form: the second operand would
+// be a copy taken while the load is still in flight)
+template <int N>
+__device__ __forceinline__ void wait_load(u32x4_t& a) {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
+
+// MT: 32-row tiles of activations per block.  W8: the weights are 8-bit (see w8_offset): the wavefront's two column
+// tiles come with ONE load per stage, are widened to bf16 in registers, and the accumulators are multiplied by the
+// columns' scales on the way out.
+template <int MT, int EPI, int KG, int CG, bool W8>
 __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
-                                                               const bf16_t* __restrict__ Wp, int NT, int KS,
+                                                               const bf16_t* __restrict__ Wp,
+                                                               const float* __restrict__ scale, int NT, int KS,
                                                                int ks_per_split, int n_col, int n_split, int n_zb,
                                                                int T, int T_pad, int N, float* __restrict__ out,
                                                                bf16_t* __restrict__ out_act, size_t act_plane,
@@ -81,7 +103,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int STAGE_TILES = PLANES * MT * KG;  // 1 KiB operand tiles per stage, ordered [plane][row tile][k-step]
     constexpr int MY_TILES = STAGE_TILES / WAVES;  // = MT: tiles of a stage this wavefront fetches
-    constexpr int PER_ITER = MY_TILES + NW;        // vector-memory instructions a wavefront issues per stage
+    constexpr int NWL = W8 ? 1 : NW;               // weight loads per stage
+    constexpr int PER_ITER = MY_TILES + NWL;       // vector-memory instructions a wavefront issues per stage
     constexpr unsigned STAGE_BYTES = STAGE_TILES * 1024;
     static_assert(KG * CG == WAVES, "a workgroup is eight wavefronts");
     static_assert(STAGE_TILES % WAVES == 0, "stage does not divide among the wavefronts");
@@ -139,21 +162,23 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
 
     // ---- weights: NW tiles per stage, straight into registers ------------------------------------------
     const int nt0 = (bx * CG + cg) * NW;
+    const int NTW = W8 ? NT / NW : NT;  // 1 KiB blocks per k-step (an 8-bit block holds the wavefront's two tiles)
     bool nt_ok[NW];
     const bf16_t* wsrc[NW];
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         nt_ok[a] = (nt0 + a) < NT;
-        wsrc[a] = Wp + ((size_t)(ks_begin + kgi) * NT + (nt_ok[a] ? nt0 + a : 0)) * 512 + lane * 8;
+        const int blk = W8 ? nt0 / NW : nt0 + a;
+        wsrc[a] = Wp + ((size_t)(ks_begin + kgi) * NTW + (nt_ok[a] ? blk : 0)) * 512 + lane * 8;
     }
-    u32x4_t wreg[NBUF][NW];
+    u32x4_t wreg[NBUF][NWL];
     auto w_issue_one = [&](int buf, int stage, int a) {
-        const bf16_t* src = wsrc[a] + (size_t)stage * KG * NT * 512;
+        const bf16_t* src = wsrc[a] + (size_t)stage * KG * NTW * 512;
         asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(wreg[buf][a]) : "v"(src) : "memory");
     };
     auto w_issue = [&](int buf, int stage) {
 #pragma unroll
-        for (int a = 0; a < NW; a++) w_issue_one(buf, stage, a);
+        for (int a = 0; a < NWL; a++) w_issue_one(buf, stage, a);
     };
 
     float16_t acc[NW][MT];
@@ -195,8 +220,17 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     xfrag cur;
     auto stage = [&](auto after_c, int xbuf, auto wbuf_c, bool more, int x_stage, int x_buf, int w_stage) {
         constexpr int AFTER = decltype(after_c)::value, WBUF = decltype(wbuf_c)::value;
-        wait_loads<AFTER>(wreg[WBUF][0], wreg[WBUF][1]);
-        const bf16x8_t w0 = __builtin_bit_cast(bf16x8_t, wreg[WBUF][0]), w1 = __builtin_bit_cast(bf16x8_t, wreg[WBUF][1]);
+        bf16x8_t w0, w1;
+        if (W8) {
+            wait_load<AFTER>(wreg[WBUF][0]);
+            const u32x4_t r = wreg[WBUF][0];
+            w0 = cvt_w8(r[0], r[1]);
+            w1 = cvt_w8(r[2], r[3]);
+        } else {
+            wait_loads<AFTER>(wreg[WBUF][0], wreg[WBUF][NWL - 1]);
+            w0 = __builtin_bit_cast(bf16x8_t, wreg[WBUF][0]);
+            w1 = __builtin_bit_cast(bf16x8_t, wreg[WBUF][NWL - 1]);
+        }
         auto issue = [&](int lo, int hi) {  // loads number lo .. hi-1 of this iteration
 #pragma unroll
             for (int i = lo; i < hi; i++) {
@@ -259,9 +293,9 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     // last trip: only the weights of the last stage are left to fetch (in its first iteration)
     stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 0>{}, true, -1, 0, s0 + DEPTH);
     advance();
-    stage(integral_constant<int, PER_ITER + NW>{}, xbuf, integral_constant<int, 1>{}, true, -1, 0, -1);
+    stage(integral_constant<int, PER_ITER + NWL>{}, xbuf, integral_constant<int, 1>{}, true, -1, 0, -1);
     advance();
-    stage(integral_constant<int, NW>{}, xbuf, integral_constant<int, 2>{}, true, -1, 0, -1);
+    stage(integral_constant<int, NWL>{}, xbuf, integral_constant<int, 2>{}, true, -1, 0, -1);
     advance();
     stage(integral_constant<int, 0>{}, xbuf, integral_constant<int, 3>{}, false, -1, 0, -1);
     __syncthreads();  // every stage has been consumed and no load is in flight: the ring is free
@@ -299,6 +333,17 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
         take(cg);
     }
 
+    // 8-bit weights: the scales of this wavefront's columns, all requested at once
+    float4_t sc[NW][4];
+    if (W8) {
+#pragma unroll
+        for (int a = 0; a < NW; a++)
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+                sc[a][q] = nt_ok[a] ? *reinterpret_cast<const float4_t*>(scale + (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4)
+                                    : float4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
     // epilogue: lane holds row (token) mt*32 + lane%32 and, in registers 4q .. 4q+3, the columns
     // nt*32 + 8q + (lane/32)*4 + 0..3
 #pragma unroll
@@ -310,7 +355,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
 #pragma unroll
             for (int q = 0; q < 4; q++) {
                 const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
-                const float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                if (W8) v *= sc[a][q];
                 if (EPI == SLED_EPI_PARTIAL) {
                     if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)by * T_pad + tok) * N + n) = v;
                 } else if (EPI == SLED_EPI_STORE) {
@@ -376,6 +422,7 @@ struct gemm_args {
     const bf16_t* X;
     size_t x_plane;
     const bf16_t* W;
+    const float* scale;
     int NT, KS, kps, n_col, n_split, n_zb, T, T_pad, N;
     float* out;
     bf16_t* out_act;
@@ -383,28 +430,33 @@ struct gemm_args {
     int F_act;
 };
 
-template <int MT, int EPI, int KG, int CG>
+template <int MT, int EPI, int KG, int CG, bool W8>
 int launch_one(const gemm_args& a) {
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
-    auto kern = gemm_bf16_kernel<MT, EPI, KG, CG>;
+    auto kern = gemm_bf16_kernel<MT, EPI, KG, CG, W8>;
     if (!allowed) {
         SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
     }
-    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.NT, a.KS, a.kps, a.n_col,
+    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.scale, a.NT, a.KS, a.kps, a.n_col,
                        a.n_split, a.n_zb, a.T, a.T_pad, a.N, a.out, a.out_act, a.act_plane, a.F_act);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
 
+template <int MT, int KG, int CG, bool W8>
+int launch_epi8(int epi, const gemm_args& a) {
+    switch (epi) {
+        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL, KG, CG, W8>(a);
+        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU, KG, CG, W8>(a);
+        default: return launch_one<MT, SLED_EPI_STORE, KG, CG, W8>(a);
+    }
+}
+
 template <int MT, int KG, int CG>
 int launch_epi(int epi, const gemm_args& a) {
-    switch (epi) {
-        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL, KG, CG>(a);
-        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU, KG, CG>(a);
-        default: return launch_one<MT, SLED_EPI_STORE, KG, CG>(a);
-    }
+    return a.scale ? launch_epi8<MT, KG, CG, true>(epi, a) : launch_epi8<MT, KG, CG, false>(epi, a);
 }
 
 // tuning aid: SLED_GEMM_TUNE="N:K:split;..." overrides the number of K slices of the projections with
@@ -448,9 +500,9 @@ sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs
     return p;
 }
 
-int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, int T, int T_pad, int N, int K,
-                     int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane, int F_act,
-                     hipStream_t st) {
+int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const float* scale, int T, int T_pad,
+                     int N, int K, int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane,
+                     int F_act, hipStream_t st) {
     if (m->s.dtype == SLED_BF16) {
         const int NT = N / 32, KS = K / 16;
         if (N % 32 || K % 16 || T_pad % 32 || plan.split < 1 || KS % (plan.split * NARROW_KG * NBUF))
@@ -476,6 +528,8 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;
         a.W = static_cast<const bf16_t*>(W);
+        a.scale = m->w8 ? scale : nullptr;
+        if (m->w8 && (!scale || N % 64)) SLED_FAIL(SLED_EINVAL, "gemm: 8-bit weights need scales and N (%d) a multiple of 64", N);
         a.NT = NT;
         a.KS = KS;
         a.kps = KS / plan.split;

@@ -8,6 +8,8 @@
 // load time, into the k-step-major tile order of wfrag_offset.
 #include "sled_internal.h"
 
+#include <algorithm>
+
 namespace {
 
 // sum over the workgroup (blockDim.x a multiple of 64, at most 1024); every thread gets the result;
@@ -311,6 +313,25 @@ __global__ void pack_rows_kernel(const void* __restrict__ src, void* __restrict_
     }
 }
 
+// rows of 8-bit weights (FP8 E4M3 bytes) -> paired-tile order
+__global__ void pack_rows_w8_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int rows, int K, int dst_row0,
+                                    int dst_row_stride, int dst_row_tiles) {
+    const size_t n8 = (size_t)rows * (K / 8);
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n8; e += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / (K / 8));
+        const int c = (int)(e - (size_t)r * (K / 8)) * 8;
+        const int dr = dst_row0 + r * dst_row_stride;
+        const uint2 v = *reinterpret_cast<const uint2*>(src + (size_t)r * K + c);
+        *reinterpret_cast<uint2*>(dst + w8_offset(dr, c, dst_row_tiles)) = v;
+    }
+}
+
+__global__ void scatter_scales_kernel(const float* __restrict__ src, float* __restrict__ dst, int rows, int dst_row0,
+                                      int dst_row_stride) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < rows) dst[dst_row0 + i * dst_row_stride] = src[i];
+}
+
 template <bool BF16>
 __global__ void copy_gain_kernel(const void* __restrict__ src, float* __restrict__ dst, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -331,6 +352,24 @@ int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K
         hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride, dst_row_tiles);
     else
         hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(grid), dim3(256), 0, st, src, dst, rows, K, dst_row0, dst_row_stride, dst_row_tiles);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_pack_rows_w8(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
+                             hipStream_t st) {
+    if (K % 16 || dst_rows_total % 64) SLED_FAIL(SLED_EINVAL, "8-bit weights: K %d or rows %d not tileable", K, dst_rows_total);
+    const size_t n8 = (size_t)rows * (K / 8);
+    int grid = (int)std::min<size_t>((n8 + 255) / 256, 65535);
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(pack_rows_w8_kernel, dim3(grid), dim3(256), 0, st, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
+                       rows, K, dst_row0, dst_row_stride, dst_rows_total / 32);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_scatter_scales(const float* src, float* dst, int rows, int dst_row0, int dst_row_stride, hipStream_t st) {
+    hipLaunchKernelGGL(scatter_scales_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, src, dst, rows, dst_row0, dst_row_stride);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

@@ -82,6 +82,14 @@ __host__ __device__ inline size_t wfrag_offset(int r, int k, int NT) {
     return ((size_t)ks * NT + rt) * 512 + (size_t)(((kk >> 3) << 5) + rl) * 8 + (kk & 7);
 }
 
+// 8-bit weights: byte offset of element (row r, column k) of a matrix with NT row tiles (NT even).  Two
+// neighbouring row tiles share one 1 KiB block per k-step, so that a wavefront still fetches its two column tiles
+// with one 16-byte-per-lane load: lane l = (k%16 / 8) * 32 + r%32 holds 8 k-values of tile 2p, then 8 of tile 2p+1.
+__host__ __device__ inline size_t w8_offset(int r, int k, int NT) {
+    const int pair = r >> 6, a = (r >> 5) & 1, rl = r & 31, ks = k >> 4, kk = k & 15;
+    return ((size_t)ks * (NT >> 1) + pair) * 1024 + (size_t)(((kk >> 3) << 5) + rl) * 16 + a * 8 + (kk & 7);
+}
+
 // ------------------------------------------------------------------------------------------
 // handles
 // ------------------------------------------------------------------------------------------
@@ -92,6 +100,11 @@ struct sled_layer_weights {
     void* w_down;   // [ d, F ]
     float* g_attn;  // [d]
     float* g_mlp;   // [d]
+    // 8-bit weights only: one float scale per output row of each matrix (same row order as the matrix)
+    float* s_qkv = nullptr;
+    float* s_o = nullptr;
+    float* s_gu = nullptr;
+    float* s_down = nullptr;
 };
 
 struct sled_model {
@@ -103,6 +116,9 @@ struct sled_model {
     float* g_final;
     std::vector<sled_layer_weights> layers;
     std::vector<void*> allocs;
+    // weights stored as FP8 E4M3 with one scale per output row (sled_model_set_weight_bits)
+    bool w8 = false;
+    float* s_lm = nullptr;     // [V] scales of the LM head
     // results of a request bit-identical whatever batch it is verified in (sled_model_set_batch_invariant)
     bool batch_invariant = false;
     // kernel timing (sled_profile_enable): one (class, start event, end event) per launch
@@ -169,6 +185,11 @@ struct sled_step_meta {
 int sled_launch_pack_rows(int dtype, const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride,
                           int dst_rows_total, hipStream_t st);
 int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStream_t st);
+// 8-bit weights: rows of an FP8 E4M3 matrix [rows, K] into the paired-tile order of w8_offset, and
+// their float scales into the row order of the fused matrix
+int sled_launch_pack_rows_w8(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
+                             hipStream_t st);
+int sled_launch_scatter_scales(const float* src, float* dst, int rows, int dst_row0, int dst_row_stride, hipStream_t st);
 // row t of an activation buffer -> row 0 of a one-tile buffer (the single row the LM head is asked for)
 int sled_launch_copy_act_row(const sled_model* m, const void* X, size_t plane, int t, void* X1, size_t plane1, int d,
                              hipStream_t st);
@@ -193,9 +214,10 @@ struct sled_gemm_plan {
     int split;   // K slices
 };
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
-int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, int T, int T_pad, int N, int K,
-                     int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane, int F_act,
-                     hipStream_t st);
+// `scale`: per-output-column scales of an 8-bit weight matrix (models with 8-bit weights), else nullptr
+int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const float* scale, int T, int T_pad,
+                     int N, int K, int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane,
+                     int F_act, hipStream_t st);
 
 // attention.hip
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,

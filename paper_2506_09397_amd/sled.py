@@ -23,11 +23,13 @@ OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
 GREEDY, SAMPLE = 0, 1
 T_EMBED, T_WQ, T_WK, T_WV, T_WO, T_WGATE, T_WUP, T_WDOWN, T_G_ATTN, T_G_MLP, T_G_FINAL, T_LM_HEAD = range(12)
+T_SCALE = 100   # + a matrix id: that matrix's per-row scales (models with 8-bit weights)
 TENSOR_IDS = {"embed": T_EMBED, "wq": T_WQ, "wk": T_WK, "wv": T_WV, "wo": T_WO, "wg": T_WGATE, "wu": T_WUP,
               "wd": T_WDOWN, "g_attn": T_G_ATTN, "g_mlp": T_G_MLP, "g_final": T_G_FINAL, "lm_head": T_LM_HEAD}
 
 EXPORTS = [
     "sled_model_create", "sled_model_load", "sled_model_destroy", "sled_model_set_batch_invariant",
+    "sled_model_set_weight_bits",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
     "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
     "sled_accept_workspace_bytes", "sled_accept", "sled_accept_sparse", "sled_profile_enable", "sled_profile_read",
@@ -64,6 +66,7 @@ def lib() -> C.CDLL:
     L.sled_model_load.argtypes = [vp, C.c_int, C.c_int, vp, vp]
     L.sled_model_destroy.argtypes = [vp]
     L.sled_model_set_batch_invariant.argtypes = [vp, C.c_int]
+    L.sled_model_set_weight_bits.argtypes = [vp, C.c_int]
     L.sled_kvpool_create.argtypes = [vp, C.c_int64, C.c_int, C.POINTER(vp)]
     L.sled_kvpool_open.argtypes = [vp, ip]
     L.sled_kvpool_close.argtypes = [vp, C.c_int]
@@ -228,13 +231,25 @@ def sled_profile_read(model: int):
 
 # ---------------------------------------------------------------------------------------- helpers
 def load_weights(model: int, weights) -> None:
-    """Streams every tensor of a synth.SynthWeights-like object (on the GPU) into the model."""
+    """Streams every tensor of a synth.SynthWeights-like object (on the GPU) into the model.  An object with
+    bits == 8 (synth.SynthWeightsW8) is loaded as FP8 bytes plus per-row scales."""
+    w8 = getattr(weights, "bits", 16) == 8
+    if w8:
+        _check(lib().sled_model_set_weight_bits(model, 8))
+
+    def put(name: str, layer: int) -> None:
+        if w8 and name in weights.MATRICES:
+            sled_model_load(model, TENSOR_IDS[name], layer, weights.q(name, layer).contiguous().view(torch.uint8))
+            sled_model_load(model, T_SCALE + TENSOR_IDS[name], layer, weights.scale(name, layer).contiguous())
+        else:
+            sled_model_load(model, TENSOR_IDS[name], layer, weights.tensor(name, layer).contiguous())
+
     sled_model_load(model, T_EMBED, 0, weights.embed().contiguous())
     for l in range(weights.shape.n_layers):
-        for name, t in weights.layer(l).items():
-            sled_model_load(model, TENSOR_IDS[name], l, t.contiguous())
-    for name, t in weights.final().items():
-        sled_model_load(model, TENSOR_IDS[name], 0, t.contiguous())
+        for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp"):
+            put(name, l)
+    for name in ("g_final", "lm_head"):
+        put(name, -1)
     torch.cuda.synchronize()
 
 

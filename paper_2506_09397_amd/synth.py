@@ -136,6 +136,46 @@ class SynthWeights:
         return {"g_final": self.tensor("g_final"), "lm_head": self.tensor("lm_head")}
 
 
+class SynthWeightsW8(SynthWeights):
+    """The same model with 8-bit projection weights: W[n][k] = q[n][k] * scale[n], q an FP8 E4M3 number (the
+    encoding torch calls float8_e4m3fn) drawn as N(0, 16) rounded to FP8, scale[n] a bf16-representable value
+    around std / 16 (so that the product is exact in float32 and the matrix still has entries of standard
+    deviation about std).  Both the 8-bit numbers and the scales are inputs: nothing is quantised by the code
+    under test.  Embedding and gains as in SynthWeights.
+
+    tensor() / layer() / final() return the dequantised float32 matrices (exact), which is what a reference
+    implementation multiplies with; q() and scale() return what the 8-bit library path loads."""
+
+    bits = 8
+    MATRICES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "lm_head")
+
+    def q(self, name: str, layer: int = -1) -> torch.Tensor:
+        out_f, in_f = self._dims()[name]
+        z = torch.clamp(self._randn(name, layer, out_f, in_f) * 16.0, -240.0, 240.0)
+        return z.to(torch.float8_e4m3fn)
+
+    def scale(self, name: str, layer: int = -1) -> torch.Tensor:
+        out_f, _ = self._dims()[name]
+        g = torch.Generator(device=self.device)
+        g.manual_seed((_seed_for(self.seed, name, layer) * 7 + 13) % (2**31 - 1))
+        u = torch.rand(out_f, generator=g, device=self.device, dtype=torch.float32)
+        return ((self.std / 16.0) * (0.75 + 0.5 * u)).to(torch.bfloat16).to(torch.float32)
+
+    def _dims(self):
+        s = self.shape
+        return {
+            "wq": (s.n_q_heads * s.head_dim, s.d_model), "wk": (s.n_kv_heads * s.head_dim, s.d_model),
+            "wv": (s.n_kv_heads * s.head_dim, s.d_model), "wo": (s.d_model, s.n_q_heads * s.head_dim),
+            "wg": (s.d_ffn, s.d_model), "wu": (s.d_ffn, s.d_model), "wd": (s.d_model, s.d_ffn),
+            "lm_head": (s.vocab, s.d_model),
+        }
+
+    def tensor(self, name: str, layer: int = -1) -> torch.Tensor:
+        if name in self.MATRICES:
+            return self.q(name, layer).to(torch.float32) * self.scale(name, layer)[:, None]
+        return super().tensor(name, layer)
+
+
 def as_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor (fp32 or bf16) to a float64 numpy array on the host."""
     return t.detach().to("cpu").to(torch.float64).numpy()
