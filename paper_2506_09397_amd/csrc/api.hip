@@ -305,7 +305,8 @@ static int stage_release(sled_stage_slot* s, hipStream_t st) {
 
 extern "C" int sled_kvpool_create(const sled_model* m, int64_t n_pages, int max_requests, sled_kvpool** out) {
     if (!m || !out || n_pages < 1 || max_requests < 1) SLED_FAIL(SLED_EINVAL, "sled_kvpool_create: bad argument");
-    if (n_pages > (int64_t)1 << 30) SLED_FAIL(SLED_EINVAL, "sled_kvpool_create: too many pages");
+    // 16 * page + slot is kept in 32 bits
+    if (n_pages > (int64_t)1 << 27) SLED_FAIL(SLED_EINVAL, "sled_kvpool_create: too many pages");
     sled_kvpool* p = new (std::nothrow) sled_kvpool();
     if (!p) SLED_FAIL(SLED_ENOMEM, "host allocation failed");
     p->m = m;
@@ -501,7 +502,7 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
 namespace {
 
 struct ws_plan {
-    size_t h, xa, xo, xf, q, x1, partial, cs, part_o, part_ml, arrive, total, T_alloc;
+    size_t h, xa, xo, xf, q, x1, partial, cs, kvslot, part_o, part_ml, arrive, total, T_alloc;
 };
 
 // Attention work list.  A work item is a run of pages of one (request, kv head), processed by one
@@ -554,6 +555,7 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     part = std::max(part, (size_t)sled_gemm_make_plan(m, 2 * s.d_ffn, s.d_model, false).split * T_pad * 2 * F);
     w.partial = take(part * sizeof(float));
     w.cs = take((size_t)T * s.head_dim * sizeof(float));
+    w.kvslot = take((size_t)T * sizeof(int32_t));
     w.part_o = take((size_t)n_work * QT * 16 * 128 * sizeof(float));
     w.part_ml = take((size_t)n_work * 2 * QT * 16 * sizeof(float));
     w.arrive = take((size_t)(n_work + 1) * sizeof(int32_t));  // one counter per (request, kv head): at most n_work
@@ -694,6 +696,7 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     void* x1 = ws + wp.x1;
     float* partial = reinterpret_cast<float*>(ws + wp.partial);
     float* cs = reinterpret_cast<float*>(ws + wp.cs);
+    int32_t* kvslot = reinterpret_cast<int32_t*>(ws + wp.kvslot);
     float* part_o = reinterpret_cast<float*>(ws + wp.part_o);
     float* part_ml = reinterpret_cast<float*>(ws + wp.part_ml);
     int32_t* arrive = reinterpret_cast<int32_t*>(ws + wp.arrive);
@@ -723,12 +726,12 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
 
     // arrival counters of the attention work items start at zero (each layer leaves them at zero)
     SLED_RUN(SLED_PROF_ROWS, sled_launch_fill_i32(arrive, 0, (size_t)B * Hkv, st));
-    SLED_RUN(SLED_PROF_ROWS, sled_launch_rope_table(m, p, meta, cs, st));
+    SLED_RUN(SLED_PROF_ROWS, sled_launch_rope_table(m, p, meta, cs, kvslot, st));
     SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, pl_d, m->layers[0].g_attn, st));
     for (int l = 0; l < s.n_layers; l++) {
         const sled_layer_weights& w = m->layers[l];
         SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_qkv, w.s_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, g_qkv, partial, nullptr, 0, 0, st));
-        SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, meta, l, partial, g_qkv.split, T_pad, cs, qb, pl_hd, st));
+        SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, T, l, partial, g_qkv.split, T_pad, cs, kvslot, qb, pl_hd, st));
         SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, part_o, part_ml, arrive, xo, pl_hd, QT, st));
         SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, pl_hd, w.w_o, w.s_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, g_o, partial, nullptr, 0, 0, st));
         SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_o.split, T, T_pad, h, xa, pl_d, w.g_mlp, st));

@@ -246,28 +246,33 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
             for (int i = 0; i < 4; i++) o[dt][i] = o[dt][i] * a1 + o2[i] * a2;
         }
     };
-    if (!producer && pgid > 0) {
-        float* slot = park + (size_t)((pgid - 1) * QT + qt) * ATTN_PARK_F;
-        if (lg == 0) {
-            slot[2048 + lq] = m;
-            slot[2048 + 16 + lq] = lsum;
-        }
+    auto fold_groups = [&]() {  // called by every wavefront that is still alive
+        if (!producer && pgid > 0) {
+            float* slot = park + (size_t)((pgid - 1) * QT + qt) * ATTN_PARK_F;
+            if (lg == 0) {
+                slot[2048 + lq] = m;
+                slot[2048 + 16 + lq] = lsum;
+            }
 #pragma unroll
-        for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(slot + (dt * 64 + lane) * 4) = o[dt];
-    }
-    __syncthreads();
-    if (!producer && pgid == 0) {
-        for (int p2 = 1; p2 < NPG; p2++) {
-            const float* slot = park + (size_t)((p2 - 1) * QT + qt) * ATTN_PARK_F;
-            fold(slot[2048 + lq], slot[2048 + 16 + lq],
-                 [&](int dt) { return *reinterpret_cast<const float4_t*>(slot + (dt * 64 + lane) * 4); });
+            for (int dt = 0; dt < 8; dt++) *reinterpret_cast<float4_t*>(slot + (dt * 64 + lane) * 4) = o[dt];
         }
-    }
+        __syncthreads();
+        if (!producer && pgid == 0) {
+            for (int p2 = 1; p2 < NPG; p2++) {
+                const float* slot = park + (size_t)((p2 - 1) * QT + qt) * ATTN_PARK_F;
+                fold(slot[2048 + lq], slot[2048 + 16 + lq],
+                     [&](int dt) { return *reinterpret_cast<const float4_t*>(slot + (dt * 64 + lane) * 4); });
+            }
+        }
+    };
+    fold_groups();
 
     // The wavefronts of page group 0 now hold the state of work item w, one query tile each.  If the
     // (request, kv head) has several work items, each stores its state; the one that arrives last
-    // merges them all in ascending order (so the result does not depend on which one that is) and
-    // writes the output.
+    // merges them all in a fixed order (so the result does not depend on which one that is) and writes
+    // the output.  Reading a stored state is a round trip to the memory side, so the page groups share
+    // the merge: group p takes items p, p + NPG, ... in ascending order, then the groups are folded
+    // through LDS as above.
     const int bg = b * Hkv + g;
     const int w0 = meta.cu_work[bg], w1 = meta.cu_work[bg + 1];
     const bool single = (w1 - w0) == 1;
@@ -310,17 +315,19 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
             sh_last = last;
         }
         __syncthreads();
-        if (!sh_last || producer || pgid != 0) return;
+        if (!sh_last || producer) return;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         m = NEG_BIG;
         lsum = 0.f;
 #pragma unroll
         for (int dt = 0; dt < 8; dt++) o[dt] = float4_t{0.f, 0.f, 0.f, 0.f};
-        for (int ww = w0; ww < w1; ww++) {
+        for (int ww = w0 + pgid; ww < w1; ww += NPG) {
             const float m2 = __hip_atomic_load(&part_ml[((size_t)ww * 2 + 0) * (QT * 16) + r_mine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const float l2 = __hip_atomic_load(&part_ml[((size_t)ww * 2 + 1) * (QT * 16) + r_mine], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             fold(m2, l2, [&](int dt) { return get(part_o + ((size_t)ww * (QT * 16) + r_mine) * D + dt * 16 + lg * 4); });
         }
+        fold_groups();  // the barrier inside also orders group 0's earlier reads of the parking slots before these writes
+        if (pgid != 0) return;
     } else if (producer || pgid != 0) {
         return;
     }

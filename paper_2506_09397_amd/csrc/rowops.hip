@@ -84,28 +84,121 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const int32_t* __restri
     }
 }
 
-// h[t,:] += sum_s partial[s][t][:]  (s ascending);  X[t,:] = rmsnorm(h) * gain
+// a + sum over the K slices s = 0 .. n_split-1 (ascending) of p[s * stride .. + 3].  The loads of up to eight slices
+// are issued before the first is used: a row kernel is a chain of round trips to L2, not a stream, and a loop
+// that adds slice after slice would pay one round trip per slice.
+__device__ inline float4 add_slices4(float4 a, const float* __restrict__ p, size_t stride, int n_split) {
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            v[u] = s0 + u < n_split ? *reinterpret_cast<const float4*>(p + (size_t)(s0 + u) * stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            a.x += v[u].x;
+            a.y += v[u].y;
+            a.z += v[u].z;
+            a.w += v[u].w;
+        }
+    }
+    return a;
+}
+
+// the same for eight consecutive columns (two float4), all sixteen loads of a trip in flight together
+__device__ inline void add_slices8(float4& a0, float4& a1, const float* __restrict__ p, size_t stride, int n_split) {
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float4 v[8], w[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const bool on = s0 + u < n_split;
+            v[u] = on ? *reinterpret_cast<const float4*>(p + (size_t)(s0 + u) * stride) : zero;
+            w[u] = on ? *reinterpret_cast<const float4*>(p + (size_t)(s0 + u) * stride + 4) : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            a0.x += v[u].x;
+            a0.y += v[u].y;
+            a0.z += v[u].z;
+            a0.w += v[u].w;
+            a1.x += w[u].x;
+            a1.y += w[u].y;
+            a1.z += w[u].z;
+            a1.w += w[u].w;
+        }
+    }
+}
+
+// the same for two single values
+__device__ inline void add_slices1x2(float& a, float& b, const float* __restrict__ pa, const float* __restrict__ pb, size_t stride,
+                                     int n_split) {
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float v[8], w[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const bool on = s0 + u < n_split;
+            v[u] = on ? pa[(size_t)(s0 + u) * stride] : 0.f;
+            w[u] = on ? pb[(size_t)(s0 + u) * stride] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            a += v[u];
+            b += w[u];
+        }
+    }
+}
+
+// ... and for one
+__device__ inline float add_slices1(float a, const float* __restrict__ p, size_t stride, int n_split) {
+    for (int s0 = 0; s0 < n_split; s0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = s0 + u < n_split ? p[(size_t)(s0 + u) * stride] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; u++) a += v[u];
+    }
+    return a;
+}
+
+// h[t,:] += sum_s partial[s][t][:]  (s ascending);  X[t,:] = rmsnorm(h) * gain.  A thread owns 8 consecutive
+// columns per trip over the row; rows of up to 8 * blockDim.x columns (one trip) stay in registers between the
+// sum of squares and the scaling, longer rows are read back from h.
 template <bool BF16>
 __global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __restrict__ partial, int n_split, int T_pad,
                                                             int d, float eps, const float* __restrict__ gain,
                                                             float* __restrict__ h, void* __restrict__ X, size_t plane) {
     __shared__ float sh[16];
     const int t = blockIdx.x;
+    const size_t stride = (size_t)T_pad * d;
+    const bool one_trip = d <= (int)blockDim.x * 8;
     float ss = 0.f;
-    for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
-        float4 a = *reinterpret_cast<const float4*>(h + (size_t)t * d + c);
-        for (int s = 0; s < n_split; s++) {
-            float4 p = *reinterpret_cast<const float4*>(partial + ((size_t)s * T_pad + t) * d + c);
-            a.x += p.x;
-            a.y += p.y;
-            a.z += p.z;
-            a.w += p.w;
+    float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, g0 = a0, g1 = a0;
+    for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
+        float* hp = h + (size_t)t * d + c;
+        const float* pp = partial + (size_t)t * d + c;
+        if (one_trip) {
+            g0 = *reinterpret_cast<const float4*>(gain + c);
+            g1 = *reinterpret_cast<const float4*>(gain + c + 4);
         }
-        *reinterpret_cast<float4*>(h + (size_t)t * d + c) = a;
-        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        a0 = *reinterpret_cast<const float4*>(hp);
+        a1 = *reinterpret_cast<const float4*>(hp + 4);
+        add_slices8(a0, a1, pp, stride, n_split);
+        *reinterpret_cast<float4*>(hp) = a0;
+        *reinterpret_cast<float4*>(hp + 4) = a1;
+        ss += a0.x * a0.x + a0.y * a0.y + a0.z * a0.z + a0.w * a0.w;
+        ss += a1.x * a1.x + a1.y * a1.y + a1.z * a1.z + a1.w * a1.w;
     }
     const float tot = block_sum(ss, sh);
     const float r = 1.0f / sqrtf(tot / (float)d + eps);
+    if (one_trip) {
+        const int c = threadIdx.x * 8;
+        if (c < d) {
+            const float v[8] = {a0.x * r * g0.x, a0.y * r * g0.y, a0.z * r * g0.z, a0.w * r * g0.w,
+                                a1.x * r * g1.x, a1.y * r * g1.y, a1.z * r * g1.z, a1.w * r * g1.w};
+            store_act8<BF16>(X, plane, t, c, d, v);
+        }
+        return;
+    }
     for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
         float v[8];
         for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
@@ -113,12 +206,15 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __rest
     }
 }
 
-// cos/sin of pos * theta^(-2i/D) for every packed row, evaluated in float64, stored as float32
+// Per packed row, once per step: cos/sin of pos * theta^(-2i/D), evaluated in float64 and stored as float32, and
+// where the row's K/V go (16 * page + slot) -- the chain of dependent lookups behind that is then paid once, not
+// in every layer's store kernel.
 __global__ void rope_table_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev, int half, double theta,
-                                  float2* __restrict__ cs) {
+                                  float2* __restrict__ cs, int32_t* __restrict__ kvslot) {
     const int t = blockIdx.x;
     const int b = meta.row_req[t];
     const int pos = len_dev[meta.req_id[b]] + meta.pos0[b] + meta.row_j[t];
+    if (threadIdx.x == 0) kvslot[t] = meta.pages[meta.cu_pages[b] + (pos >> 4)] * 16 + (pos & 15);
     for (int i = threadIdx.x; i < half; i += blockDim.x) {
         double inv = pow(theta, -(double)i / (double)half);
         double ang = (double)pos * inv;
@@ -129,29 +225,23 @@ __global__ void rope_table_kernel(sled_step_meta meta, const int32_t* __restrict
 // Reduce the QKV partial sums of one head of row t (blockIdx = (t, head), heads ordered q, k, v),
 // rotate q and k, write q to Q[T, Hq, D] and k, v into the request's page slot for position L + j.
 template <bool BF16>
-__global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev,
-                                                            const float* __restrict__ partial, int n_split, int T_pad,
+__global__ __launch_bounds__(64) void qkv_rope_store_kernel(const float* __restrict__ partial, int n_split, int T_pad,
                                                             int Hq, int Hkv, int D, const float2* __restrict__ cs,
-                                                            void* __restrict__ Q, size_t q_plane, void* __restrict__ k_pool,
+                                                            const int32_t* __restrict__ kvslot, void* __restrict__ Q, size_t q_plane, void* __restrict__ k_pool,
                                                             void* __restrict__ v_pool, int64_t n_pages, int layer) {
     const int t = blockIdx.x, head = blockIdx.y;
-    const int b = meta.row_req[t];
-    const int pos = len_dev[meta.req_id[b]] + meta.pos0[b] + meta.row_j[t];
-    const int page = meta.pages[meta.cu_pages[b] + (pos >> 4)];
-    const int slot = pos & 15;
     const int half = D >> 1;
     const int n_qkv = (Hq + 2 * Hkv) * D;
     const size_t head_elems = (size_t)16 * D;
-    auto fetch = [&](int col) {
-        float a = 0.f;
-        for (int s = 0; s < n_split; s++) a += partial[((size_t)s * T_pad + t) * n_qkv + col];
-        return a;
-    };
+    const float* prow = partial + (size_t)t * n_qkv;
+    const size_t stride = (size_t)T_pad * n_qkv;
+    const int ps = kvslot[t], page = ps >> 4, slot = ps & 15;
     if (head < Hq + Hkv) {
         for (int i = threadIdx.x; i < half; i += 64) {
             const int c1 = head * D + i, c2 = c1 + half;
-            const float x1 = fetch(c1), x2 = fetch(c2);
             const float2 sc = cs[(size_t)t * half + i];
+            float x1 = 0.f, x2 = 0.f;
+            add_slices1x2(x1, x2, prow + c1, prow + c2, stride, n_split);
             const float y1 = x1 * sc.x - x2 * sc.y;
             const float y2 = x2 * sc.x + x1 * sc.y;
             if (head < Hq) {
@@ -187,9 +277,9 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(sled_step_meta meta,
     } else {
         // v head: no rotation
         const int g = head - Hq - Hkv;
-        const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
         for (int dd = threadIdx.x; dd < D; dd += 64) {
-            const float v = fetch((Hq + Hkv) * D + g * D + dd);
+            const float v = add_slices1(0.f, prow + (Hq + Hkv) * D + g * D + dd, stride, n_split);
+            const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
             if (BF16) {
                 // V page-head block: element (slot, dd) at
                 //   (((dd/16)/2)*64 + (slot/4)*16 + dd%16)*8 + ((dd/16)%2)*4 + slot%4
@@ -212,16 +302,13 @@ __global__ __launch_bounds__(256) void swiglu_reduce_kernel(const float* __restr
     const int t = blockIdx.x;
     for (int f0 = (blockIdx.y * 256 + threadIdx.x) * 8; f0 < F; f0 += gridDim.y * 256 * 8) {
         float acc[16];
-        for (int i = 0; i < 16; i++) acc[i] = 0.f;
-        for (int s = 0; s < n_split; s++) {
-            const float4* p = reinterpret_cast<const float4*>(gu + ((size_t)s * T_pad + t) * (2 * (size_t)F) + 2 * f0);
-            for (int q = 0; q < 4; q++) {
-                const float4 x = p[q];
-                acc[4 * q] += x.x;
-                acc[4 * q + 1] += x.y;
-                acc[4 * q + 2] += x.z;
-                acc[4 * q + 3] += x.w;
-            }
+        const float* p = gu + (size_t)t * (2 * (size_t)F) + 2 * f0;
+        for (int q = 0; q < 4; q++) {
+            const float4 x = add_slices4(make_float4(0.f, 0.f, 0.f, 0.f), p + 4 * q, (size_t)T_pad * (2 * (size_t)F), n_split);
+            acc[4 * q] = x.x;
+            acc[4 * q + 1] = x.y;
+            acc[4 * q + 2] = x.z;
+            acc[4 * q + 3] = x.w;
         }
         float v[8];
         for (int i = 0; i < 8; i++) {
@@ -397,8 +484,8 @@ int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, fl
 
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
                               size_t plane, const float* gain, hipStream_t st) {
-    // one float4 per thread per pass: short rows get small workgroups
-    const int bs = m->s.d_model >= 4096 ? 1024 : m->s.d_model >= 2048 ? 512 : 256;
+    // eight columns per thread per trip: short rows get small workgroups
+    const int bs = m->s.d_model >= 8192 ? 1024 : m->s.d_model >= 4096 ? 512 : m->s.d_model >= 2048 ? 256 : 128;
     if (m->s.dtype == SLED_BF16)
         hipLaunchKernelGGL(residual_norm_kernel<true>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
                            m->s.rms_eps, gain, h, X, plane);
@@ -421,26 +508,25 @@ int sled_launch_copy_act_row(const sled_model* m, const void* X, size_t plane, i
     return SLED_OK;
 }
 
-int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs,
+int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs, int32_t* kvslot,
                            hipStream_t st) {
     hipLaunchKernelGGL(rope_table_kernel, dim3(meta.T), dim3(64), 0, st, meta, p->len_dev, m->s.head_dim / 2,
-                       (double)m->s.rope_theta, reinterpret_cast<float2*>(cs));
+                       (double)m->s.rope_theta, reinterpret_cast<float2*>(cs), kvslot);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }
 
-int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
-                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, size_t q_plane,
-                               hipStream_t st) {
-    const dim3 grid(meta.T, m->s.n_q_heads + 2 * m->s.n_kv_heads);
+int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, int T, int layer, const float* partial, int n_split,
+                               int T_pad, const float* cs, const int32_t* kvslot, void* Q, size_t q_plane, hipStream_t st) {
+    const dim3 grid(T, m->s.n_q_heads + 2 * m->s.n_kv_heads);
     if (m->s.dtype == SLED_BF16)
-        hipLaunchKernelGGL(qkv_rope_store_kernel<true>, grid, dim3(64), 0, st, meta, p->len_dev, partial, n_split,
-                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q, q_plane,
-                           p->k_pool, p->v_pool, p->n_pages, layer);
+        hipLaunchKernelGGL(qkv_rope_store_kernel<true>, grid, dim3(64), 0, st, partial, n_split, T_pad, m->s.n_q_heads,
+                           m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), kvslot, Q, q_plane, p->k_pool,
+                           p->v_pool, p->n_pages, layer);
     else
-        hipLaunchKernelGGL(qkv_rope_store_kernel<false>, grid, dim3(64), 0, st, meta, p->len_dev, partial, n_split,
-                           T_pad, m->s.n_q_heads, m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), Q, q_plane,
-                           p->k_pool, p->v_pool, p->n_pages, layer);
+        hipLaunchKernelGGL(qkv_rope_store_kernel<false>, grid, dim3(64), 0, st, partial, n_split, T_pad, m->s.n_q_heads,
+                           m->s.n_kv_heads, m->s.head_dim, reinterpret_cast<const float2*>(cs), kvslot, Q, q_plane, p->k_pool,
+                           p->v_pool, p->n_pages, layer);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

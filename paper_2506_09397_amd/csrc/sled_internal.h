@@ -197,10 +197,11 @@ int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, fl
                            const float* gain, hipStream_t st);
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
                               size_t plane, const float* gain, hipStream_t st);
-int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs, hipStream_t st);
-int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer,
-                               const float* partial, int n_split, int T_pad, const float* cs, void* Q, size_t q_plane,
-                               hipStream_t st);
+// per packed row: the rotary table cs[T][head_dim/2] and kvslot[T] = 16 * page + slot of the row's position in the cache
+int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs, int32_t* kvslot,
+                           hipStream_t st);
+int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, int T, int layer, const float* partial, int n_split,
+                               int T_pad, const float* cs, const int32_t* kvslot, void* Q, size_t q_plane, hipStream_t st);
 int sled_launch_swiglu_reduce(const sled_model* m, const float* gu, int n_split, int T, int T_pad, void* A, size_t plane,
                               hipStream_t st);
 int sled_launch_kv_ingest(const sled_model* m, const sled_kvpool* p, const void* k_src, const void* v_src, int n_tokens,
