@@ -300,63 +300,63 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     stage(integral_constant<int, 0>{}, xbuf, integral_constant<int, 3>{}, false, -1, 0, -1);
     __syncthreads();  // every stage has been consumed and no load is in flight: the ring is free
 
-    // ---- add the k-groups' sums through LDS: (0 + 2) + (1 + 3) for four groups, 0 + 1 for two ----------------
+    // ---- add the k-groups' sums through LDS ------------------------------------------------------------------------
+    // A lane holds, per (column tile a, row tile b), four groups q of four consecutive columns.  The KG wavefronts
+    // that share a column group divide these groups among themselves (k-group g owns the groups with q % KG == g):
+    // each sends the groups it does not own to their owners and adds what it receives to its own, always in
+    // ascending k-group order.  Afterwards all eight wavefronts hold a disjoint share of the block's outputs and all
+    // of them run the epilogue.  One column tile per pass, so that the exchange fits in the ring's memory.
     {
-        constexpr int PER_WAVE = NW * MT * 16 * 64;  // floats a wavefront parks
-        float* red = reinterpret_cast<float*>(smem);
-        auto park = [&](int slot) {
-#pragma unroll
-            for (int a = 0; a < NW; a++)
-#pragma unroll
-                for (int b = 0; b < MT; b++)
-#pragma unroll
-                    for (int e = 0; e < 16; e++) red[(size_t)slot * PER_WAVE + ((a * MT + b) * 16 + e) * 64 + lane] = acc[a][b][e];
+        constexpr int QPW = 4 / KG;  // groups per (a, b) a wavefront owns
+        float4_t* red = reinterpret_cast<float4_t*>(smem);
+        // parcel (destination k-group, source k-group, row tile, owned group index): 64 lanes x 16 bytes
+        auto parcel = [&](int dest, int src, int b2, int qi) {
+            // the destination has no slot of its own; src == dest is never accessed and maps to slot 0 to stay in range
+            const int s2 = src < dest ? src : (src > dest ? src - 1 : 0);
+            return red + ((size_t)((((cg * KG + dest) * (KG - 1) + s2) * MT + b2) * QPW + qi)) * 64 + lane;
         };
-        auto take = [&](int slot) {
 #pragma unroll
-            for (int a = 0; a < NW; a++)
+        for (int a = 0; a < NW; a++) {
 #pragma unroll
-                for (int b = 0; b < MT; b++)
+            for (int b2 = 0; b2 < MT; b2++)
 #pragma unroll
-                    for (int e = 0; e < 16; e++) acc[a][b][e] += red[(size_t)slot * PER_WAVE + ((a * MT + b) * 16 + e) * 64 + lane];
-        };
-        if (KG == 4) {
-            if (kgi >= 2) park((kgi - 2) * CG + cg);
+                for (int q = 0; q < 4; q++)
+                    if (q % KG != kgi)
+                        *parcel(q % KG, kgi, b2, q / KG) =
+                            float4_t{acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
             __syncthreads();
-            if (kgi >= 2) return;
-            take(kgi * CG + cg);
-            __syncthreads();
+#pragma unroll
+            for (int b2 = 0; b2 < MT; b2++)
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    if (q % KG == kgi) {
+                        const float4_t own = {acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
+                        float4_t v = kgi == 0 ? own : *parcel(kgi, 0, b2, q / KG);
+#pragma unroll
+                        for (int src = 1; src < KG; src++) v += kgi == src ? own : *parcel(kgi, src, b2, q / KG);
+#pragma unroll
+                        for (int i = 0; i < 4; i++) acc[a][b2][4 * q + i] = v[i];
+                    }
+            if (a + 1 < NW) __syncthreads();  // the parcels have been read: the next pass may overwrite them
         }
-        if (kgi == 1) park(cg);
-        __syncthreads();
-        if (kgi == 1) return;
-        take(cg);
-    }
-
-    // 8-bit weights: the scales of this wavefront's columns, all requested at once
-    float4_t sc[NW][4];
-    if (W8) {
-#pragma unroll
-        for (int a = 0; a < NW; a++)
-#pragma unroll
-            for (int q = 0; q < 4; q++)
-                sc[a][q] = nt_ok[a] ? *reinterpret_cast<const float4_t*>(scale + (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4)
-                                    : float4_t{0.f, 0.f, 0.f, 0.f};
     }
 
     // epilogue: lane holds row (token) mt*32 + lane%32 and, in registers 4q .. 4q+3, the columns
-    // nt*32 + 8q + (lane/32)*4 + 0..3
+    // nt*32 + 8q + (lane/32)*4 + 0..3; a wavefront stores the groups q it owns
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         if (!nt_ok[a]) continue;
 #pragma unroll
-        for (int b = 0; b < MT; b++) {
-            const int tok = (mt_base + b) * 32 + (lane & 31);
+        for (int q = 0; q < 4; q++) {
+            if (q % KG != kgi) continue;
+            const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
+            float4_t sc = {1.f, 1.f, 1.f, 1.f};
+            if (W8) sc = *reinterpret_cast<const float4_t*>(scale + n);  // 8-bit weights: the columns' scales
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
+            for (int b = 0; b < MT; b++) {
+                const int tok = (mt_base + b) * 32 + (lane & 31);
                 float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-                if (W8) v *= sc[a][q];
+                if (W8) v *= sc;
                 if (EPI == SLED_EPI_PARTIAL) {
                     if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)by * T_pad + tok) * N + n) = v;
                 } else if (EPI == SLED_EPI_STORE) {
@@ -521,9 +521,9 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.n_split = plan.split;
         a.n_zb = zb;
         a.grid = dim3((a.n_col * a.n_split + 7) / 8 * 8 * a.n_zb, 1, 1);
-        // the ring of activation stages; afterwards the same memory holds the sums parked by the k-groups that
-        // hand theirs over (half of the wavefronts, NW * MT * 4 KiB each)
-        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (size_t)(WAVES / 2) * NW * MT * 4096);
+        // the ring of activation stages; afterwards the same memory holds the parcels the k-groups exchange
+        // (one column tile at a time: every wavefront sends (KG - 1) / KG of its MT * 4 groups of 1 KiB)
+        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (size_t)WAVES * (KG - 1) * MT * (4 / KG) * 1024);
         a.st = st;
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;
