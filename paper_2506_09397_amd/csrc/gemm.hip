@@ -301,19 +301,22 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     __syncthreads();  // every stage has been consumed and no load is in flight: the ring is free
 
     // ---- add the k-groups' sums through LDS ------------------------------------------------------------------------
-    // A lane holds, per (column tile a, row tile b), four groups q of four consecutive columns.  The KG wavefronts
-    // that share a column group divide these groups among themselves (k-group g owns the groups with q % KG == g):
-    // each sends the groups it does not own to their owners and adds what it receives to its own, always in
-    // ascending k-group order.  Afterwards all eight wavefronts hold a disjoint share of the block's outputs and all
-    // of them run the epilogue.  One column tile per pass, so that the exchange fits in the ring's memory.
+    // A lane holds, per (column tile a, row tile b), four groups q of four consecutive columns: 4 * MT units
+    // u = 4 * b + q per column tile.  The KG wavefronts that share a column group divide the units among themselves
+    // in runs (k-group g owns units g * UPW .. (g + 1) * UPW - 1, i.e. whole row tiles when MT is a multiple of KG, so
+    // that the stores of one wavefront fill whole 128-byte lines of an output row): each sends the units it does not
+    // own to their owners and adds what it receives to its own, always in ascending k-group order.  Afterwards all
+    // eight wavefronts hold a disjoint share of the block's outputs and all of them run the epilogue.  One column
+    // tile per pass, so that the exchange fits in the ring's memory.
+    constexpr int UPW = 4 * MT / KG;  // units per wavefront and column tile
+    auto owner = [](int b2, int q) { return (4 * b2 + q) / UPW; };
     {
-        constexpr int QPW = 4 / KG;  // groups per (a, b) a wavefront owns
         float4_t* red = reinterpret_cast<float4_t*>(smem);
-        // parcel (destination k-group, source k-group, row tile, owned group index): 64 lanes x 16 bytes
-        auto parcel = [&](int dest, int src, int b2, int qi) {
+        // parcel (destination k-group, source k-group, unit): 64 lanes x 16 bytes
+        auto parcel = [&](int dest, int src, int u) {
             // the destination has no slot of its own; src == dest is never accessed and maps to slot 0 to stay in range
             const int s2 = src < dest ? src : (src > dest ? src - 1 : 0);
-            return red + ((size_t)((((cg * KG + dest) * (KG - 1) + s2) * MT + b2) * QPW + qi)) * 64 + lane;
+            return red + ((size_t)(((cg * KG + dest) * (KG - 1) + s2) * UPW + (u - dest * UPW))) * 64 + lane;
         };
 #pragma unroll
         for (int a = 0; a < NW; a++) {
@@ -321,19 +324,19 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
             for (int b2 = 0; b2 < MT; b2++)
 #pragma unroll
                 for (int q = 0; q < 4; q++)
-                    if (q % KG != kgi)
-                        *parcel(q % KG, kgi, b2, q / KG) =
+                    if (owner(b2, q) != kgi)
+                        *parcel(owner(b2, q), kgi, 4 * b2 + q) =
                             float4_t{acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
             __syncthreads();
 #pragma unroll
             for (int b2 = 0; b2 < MT; b2++)
 #pragma unroll
                 for (int q = 0; q < 4; q++)
-                    if (q % KG == kgi) {
+                    if (owner(b2, q) == kgi) {
                         const float4_t own = {acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
-                        float4_t v = kgi == 0 ? own : *parcel(kgi, 0, b2, q / KG);
+                        float4_t v = kgi == 0 ? own : *parcel(kgi, 0, 4 * b2 + q);
 #pragma unroll
-                        for (int src = 1; src < KG; src++) v += kgi == src ? own : *parcel(kgi, src, b2, q / KG);
+                        for (int src = 1; src < KG; src++) v += kgi == src ? own : *parcel(kgi, src, 4 * b2 + q);
 #pragma unroll
                         for (int i = 0; i < 4; i++) acc[a][b2][4 * q + i] = v[i];
                     }
@@ -342,21 +345,24 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     }
 
     // epilogue: lane holds row (token) mt*32 + lane%32 and, in registers 4q .. 4q+3, the columns
-    // nt*32 + 8q + (lane/32)*4 + 0..3; a wavefront stores the groups q it owns
+    // nt*32 + 8q + (lane/32)*4 + 0..3; a wavefront stores the units it owns
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         if (!nt_ok[a]) continue;
+        float4_t sc[4];
+        if (W8) {  // 8-bit weights: the columns' scales
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            if (q % KG != kgi) continue;
-            const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
-            float4_t sc = {1.f, 1.f, 1.f, 1.f};
-            if (W8) sc = *reinterpret_cast<const float4_t*>(scale + n);  // 8-bit weights: the columns' scales
+            for (int q = 0; q < 4; q++) sc[q] = *reinterpret_cast<const float4_t*>(scale + (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4);
+        }
 #pragma unroll
-            for (int b = 0; b < MT; b++) {
-                const int tok = (mt_base + b) * 32 + (lane & 31);
+        for (int b = 0; b < MT; b++) {
+            const int tok = (mt_base + b) * 32 + (lane & 31);
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                if (owner(b, q) != kgi) continue;
+                const int n = (nt0 + a) * 32 + q * 8 + (lane >> 5) * 4;
                 float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-                if (W8) v *= sc;
+                if (W8) v *= sc[q];
                 if (EPI == SLED_EPI_PARTIAL) {
                     if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)by * T_pad + tok) * N + n) = v;
                 } else if (EPI == SLED_EPI_STORE) {
@@ -523,7 +529,7 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.grid = dim3((a.n_col * a.n_split + 7) / 8 * 8 * a.n_zb, 1, 1);
         // the ring of activation stages; afterwards the same memory holds the parcels the k-groups exchange
         // (one column tile at a time: every wavefront sends (KG - 1) / KG of its MT * 4 groups of 1 KiB)
-        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (size_t)WAVES * (KG - 1) * MT * (4 / KG) * 1024);
+        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (size_t)WAVES * (KG - 1) * (4 * MT / KG) * 1024);
         a.st = st;
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;

@@ -104,31 +104,6 @@ __device__ inline float4 add_slices4(float4 a, const float* __restrict__ p, size
     return a;
 }
 
-// the same for eight consecutive columns (two float4), all sixteen loads of a trip in flight together
-__device__ inline void add_slices8(float4& a0, float4& a1, const float* __restrict__ p, size_t stride, int n_split) {
-    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s0 = 0; s0 < n_split; s0 += 8) {
-        float4 v[8], w[8];
-#pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const bool on = s0 + u < n_split;
-            v[u] = on ? *reinterpret_cast<const float4*>(p + (size_t)(s0 + u) * stride) : zero;
-            w[u] = on ? *reinterpret_cast<const float4*>(p + (size_t)(s0 + u) * stride + 4) : zero;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; u++) {
-            a0.x += v[u].x;
-            a0.y += v[u].y;
-            a0.z += v[u].z;
-            a0.w += v[u].w;
-            a1.x += w[u].x;
-            a1.y += w[u].y;
-            a1.z += w[u].z;
-            a1.w += w[u].w;
-        }
-    }
-}
-
 // the same for two single values
 __device__ inline void add_slices1x2(float& a, float& b, const float* __restrict__ pa, const float* __restrict__ pb, size_t stride,
                                      int n_split) {
@@ -160,8 +135,28 @@ __device__ inline float add_slices1(float a, const float* __restrict__ p, size_t
     return a;
 }
 
-// h[t,:] += sum_s partial[s][t][:]  (s ascending);  X[t,:] = rmsnorm(h) * gain.  A thread owns 8 consecutive
-// columns per trip over the row; rows of up to 8 * blockDim.x columns (one trip) stay in registers between the
+// store 4 consecutive activations of row t starting at column c0 (a multiple of 4), as store_act8 does for 8
+template <bool BF16>
+__device__ inline void store_act4(void* X, size_t plane, int t, int c0, int K, const float4& v) {
+    if (BF16) {
+        const float f[4] = {v.x, v.y, v.z, v.w};
+        uint32_t wh[2], wl[2];
+        for (int i = 0; i < 2; i++) {
+            const bf16_t h0 = f32_to_bf16(f[2 * i]), h1 = f32_to_bf16(f[2 * i + 1]);
+            const bf16_t l0 = f32_to_bf16(f[2 * i] - bf16_to_f32(h0)), l1 = f32_to_bf16(f[2 * i + 1] - bf16_to_f32(h1));
+            wh[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            wl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        bf16_t* p = static_cast<bf16_t*>(X) + frag_offset(t, c0, K);  // the 8 elements of a k-octet are contiguous
+        *reinterpret_cast<uint2*>(p) = make_uint2(wh[0], wh[1]);
+        *reinterpret_cast<uint2*>(p + plane) = make_uint2(wl[0], wl[1]);
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(X) + (size_t)t * K + c0) = v;
+    }
+}
+
+// h[t,:] += sum_s partial[s][t][:]  (s ascending);  X[t,:] = rmsnorm(h) * gain.  A thread owns 4 consecutive
+// columns per trip over the row; rows of up to 8 * blockDim.x columns (two trips) stay in registers between the
 // sum of squares and the scaling, longer rows are read back from h.
 template <bool BF16>
 __global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __restrict__ partial, int n_split, int T_pad,
@@ -170,39 +165,43 @@ __global__ __launch_bounds__(1024) void residual_norm_kernel(const float* __rest
     __shared__ float sh[16];
     const int t = blockIdx.x;
     const size_t stride = (size_t)T_pad * d;
-    const bool one_trip = d <= (int)blockDim.x * 8;
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
     float ss = 0.f;
-    float4 a0 = make_float4(0.f, 0.f, 0.f, 0.f), a1 = a0, g0 = a0, g1 = a0;
-    for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
-        float* hp = h + (size_t)t * d + c;
-        const float* pp = partial + (size_t)t * d + c;
-        if (one_trip) {
-            g0 = *reinterpret_cast<const float4*>(gain + c);
-            g1 = *reinterpret_cast<const float4*>(gain + c + 4);
+    if (d <= (int)blockDim.x * 8) {
+        float4 a[2] = {zero, zero}, g[2] = {zero, zero};
+#pragma unroll
+        for (int trip = 0; trip < 2; trip++) {
+            const int c = (trip * blockDim.x + threadIdx.x) * 4;
+            if (c < d) {
+                float* hp = h + (size_t)t * d + c;
+                g[trip] = *reinterpret_cast<const float4*>(gain + c);
+                a[trip] = add_slices4(*reinterpret_cast<const float4*>(hp), partial + (size_t)t * d + c, stride, n_split);
+                *reinterpret_cast<float4*>(hp) = a[trip];
+                ss += a[trip].x * a[trip].x + a[trip].y * a[trip].y + a[trip].z * a[trip].z + a[trip].w * a[trip].w;
+            }
         }
-        a0 = *reinterpret_cast<const float4*>(hp);
-        a1 = *reinterpret_cast<const float4*>(hp + 4);
-        add_slices8(a0, a1, pp, stride, n_split);
-        *reinterpret_cast<float4*>(hp) = a0;
-        *reinterpret_cast<float4*>(hp + 4) = a1;
-        ss += a0.x * a0.x + a0.y * a0.y + a0.z * a0.z + a0.w * a0.w;
-        ss += a1.x * a1.x + a1.y * a1.y + a1.z * a1.z + a1.w * a1.w;
-    }
-    const float tot = block_sum(ss, sh);
-    const float r = 1.0f / sqrtf(tot / (float)d + eps);
-    if (one_trip) {
-        const int c = threadIdx.x * 8;
-        if (c < d) {
-            const float v[8] = {a0.x * r * g0.x, a0.y * r * g0.y, a0.z * r * g0.z, a0.w * r * g0.w,
-                                a1.x * r * g1.x, a1.y * r * g1.y, a1.z * r * g1.z, a1.w * r * g1.w};
-            store_act8<BF16>(X, plane, t, c, d, v);
+        const float r = 1.0f / sqrtf(block_sum(ss, sh) / (float)d + eps);
+#pragma unroll
+        for (int trip = 0; trip < 2; trip++) {
+            const int c = (trip * blockDim.x + threadIdx.x) * 4;
+            if (c < d)
+                store_act4<BF16>(X, plane, t, c, d,
+                                 make_float4(a[trip].x * r * g[trip].x, a[trip].y * r * g[trip].y, a[trip].z * r * g[trip].z,
+                                             a[trip].w * r * g[trip].w));
         }
         return;
     }
-    for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
-        float v[8];
-        for (int i = 0; i < 8; i++) v[i] = h[(size_t)t * d + c + i] * r * gain[c + i];
-        store_act8<BF16>(X, plane, t, c, d, v);
+    for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+        float* hp = h + (size_t)t * d + c;
+        const float4 a = add_slices4(*reinterpret_cast<const float4*>(hp), partial + (size_t)t * d + c, stride, n_split);
+        *reinterpret_cast<float4*>(hp) = a;
+        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+    const float r = 1.0f / sqrtf(block_sum(ss, sh) / (float)d + eps);
+    for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+        const float4 a = *reinterpret_cast<const float4*>(h + (size_t)t * d + c);  // this thread's own stores
+        const float4 g = *reinterpret_cast<const float4*>(gain + c);
+        store_act4<BF16>(X, plane, t, c, d, make_float4(a.x * r * g.x, a.y * r * g.y, a.z * r * g.z, a.w * r * g.w));
     }
 }
 
@@ -484,8 +483,8 @@ int sled_launch_embed_norm(const sled_model* m, const int32_t* tokens, int T, fl
 
 int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_split, int T, int T_pad, float* h, void* X,
                               size_t plane, const float* gain, hipStream_t st) {
-    // eight columns per thread per trip: short rows get small workgroups
-    const int bs = m->s.d_model >= 8192 ? 1024 : m->s.d_model >= 4096 ? 512 : m->s.d_model >= 2048 ? 256 : 128;
+    // four columns per thread per trip: short rows get small workgroups
+    const int bs = m->s.d_model >= 4096 ? 1024 : m->s.d_model >= 2048 ? 512 : m->s.d_model >= 1024 ? 256 : 128;
     if (m->s.dtype == SLED_BF16)
         hipLaunchKernelGGL(residual_norm_kernel<true>, dim3(T), dim3(bs), 0, st, partial, n_split, T_pad, m->s.d_model,
                            m->s.rms_eps, gain, h, X, plane);
