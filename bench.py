@@ -43,8 +43,8 @@ def parse():
                          "two of 0.25, 1, 4 are reported in the breakdown)")
     ap.add_argument("--q-top", type=int, default=64,
                     help="accept_only: also time sled_accept_sparse with the draft distributions cut to this many entries (0 = skip)")
-    ap.add_argument("--weights", default="bf16", choices=["bf16", "fp8"],
-                    help="fp8: the same shapes with FP8 E4M3 projection weights and per-row scales (sled_model_set_weight_bits)")
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "fp8", "fp4"],
+                    help="fp8: the same shapes with FP8 E4M3 projection weights and per-row scales; fp4: FP4 E2M1 codes with a power-of-two scale per 32 inputs (sled_model_set_weight_bits)")
     ap.add_argument("--batch-invariant", action="store_true",
                     help="time the step with sled_model_set_batch_invariant on (results independent of the batch to the last bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -87,8 +87,9 @@ def main():
     total_steps = args.warmup + args.steps + args.profile_steps + 2
     ctx_budget = sum(batch.ctx_len) + B * (shape.k_max + 1) * (total_steps + 1)
     n_pages = ctx_budget // 16 + 2 * B + 8
-    w8 = args.weights == "fp8"
-    weights = (synth.SynthWeightsW8 if w8 else synth.SynthWeights)(shape, seed=args.seed, device="cuda")
+    w8 = args.weights != "bf16"
+    wcls = {"bf16": synth.SynthWeights, "fp8": synth.SynthWeightsW8, "fp4": synth.SynthWeightsW4}[args.weights]
+    weights = wcls(shape, seed=args.seed, device="cuda")
     v = Verifier(shape, weights, n_pages, B, B, ctx_budget, batch_invariant=args.batch_invariant)
     reqs = [v.open() for _ in range(B)]
     KV = []
@@ -143,7 +144,7 @@ def main():
     # grew by about one token per step); used for the algorithmic K/V bytes
     lens = v.lengths(reqs)
     kv_bytes = sum(lens) * shape.kv_bytes_per_token()
-    weight_bytes = shape.streamed_params() * (1 if w8 else 2)
+    weight_bytes = shape.streamed_params() * {"bf16": 32, "fp8": 16, "fp4": 8.5}[args.weights] / 16   # fp4: codes + a scale byte per 32
     logits_bytes = T * shape.vocab * 4
 
     # event-instrumented region: per-class kernel time on the stream the kernels run on
@@ -182,11 +183,11 @@ def main():
         "metric": "verified draft tokens/sec per batched verify step", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "p50_ms": round(p50, 4), "p90_ms": round(p90, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 (fp8 e4m3 weights)" if w8 else "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": {"bf16": "bf16", "fp8": "bf16 (fp8 e4m3 weights)", "fp4": "bf16 (mxfp4 weights)"}[args.weights], "data": "synthetic",
         "config": {"workload": f"{args.workload}: {shape.n_layers} layers d={shape.d_model} Hq/Hkv={shape.n_q_heads}/"
                                f"{shape.n_kv_heads} F={shape.d_ffn} V={shape.vocab}, B={B}, T={T} packed rows, "
                                f"{n_drafts} draft tokens, {sum(lens)} context tokens, {'sampling' if sampling else 'greedy'} acceptance, "
-                               f"seed {args.seed}" + (", batch-invariant mode" if args.batch_invariant else "") + (", FP8 E4M3 weights" if w8 else "")},
+                               f"seed {args.seed}" + (", batch-invariant mode" if args.batch_invariant else "") + {"bf16": "", "fp8": ", FP8 E4M3 weights", "fp4": ", MXFP4 weights"}[args.weights]},
         "roofline": roofline, "breakdown": breakdown, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -79,8 +79,8 @@ extern "C" {
 #define SLED_T_G_MLP    9   /* [d_model] RMSNorm gain before the MLP                    */
 #define SLED_T_G_FINAL 10   /* [d_model] final RMSNorm gain             (layer ignored) */
 #define SLED_T_LM_HEAD 11   /* [vocab, d_model]                         (layer ignored) */
-/* models with 8-bit (FP8) weights (sled_model_set_weight_bits): SLED_T_SCALE + a matrix id names that matrix's
- * per-output-row scales, float32 [rows] */
+/* models with 8- or 4-bit weights (sled_model_set_weight_bits): SLED_T_SCALE + a matrix id names that matrix's
+ * scales -- 8 bits: per-output-row, float32 [rows]; 4 bits: per row and block of 32 inputs, uint8 [rows, in / 32] */
 #define SLED_T_SCALE  100
 
 typedef struct sled_model  sled_model;
@@ -119,6 +119,12 @@ SLED_API int sled_model_load(sled_model* m, int tensor_id, int layer, const void
  * Call it right after sled_model_create, before any sled_model_load; the matrices are then loaded as FP8 bytes
  * [out, in] (dev) and their scales under SLED_T_SCALE + id.  NaN encodings are the caller's to avoid.  bf16
  * models whose projection widths are multiples of 64 only.  bits = 16 restores the default.
+ * bits = 4: the 4-bit point of the same sweep, in the MXFP4 arrangement -- FP4 E2M1 codes (0, 0.5, 1, 1.5, 2, 3, 4, 6
+ * and their negatives; bit 3 is the sign), two per byte with the even input index in the low nibble, and one
+ * E8M0 scale byte e per output row and block of 32 inputs, W[n][k] = fp4[n][k] * 2^(e[n][k / 32] - 127).  gfx950
+ * widens two codes to bf16 and applies the block scale in one instruction, exactly; the rest as for 8 bits.
+ * Matrices are loaded as uint8 [out, in / 2] (dev), scales under SLED_T_SCALE + id as uint8 [out, in / 32]; scale
+ * bytes must lie in 1 .. 254 (0 reads as a zero scale, 255 is NaN in E8M0).  Input widths multiples of 32.
  * Errors: SLED_EINVAL, SLED_ENOMEM. */
 SLED_API int sled_model_set_weight_bits(sled_model* m, int bits);
 

@@ -120,37 +120,45 @@ extern "C" int sled_model_load(sled_model* m, int tensor_id, int layer, const vo
     const bool per_layer = tensor_id >= SLED_T_WQ && tensor_id <= SLED_T_G_MLP;
     if (per_layer && (layer < 0 || layer >= s.n_layers)) SLED_FAIL(SLED_EINVAL, "sled_model_load: layer %d out of range", layer);
     if (tensor_id >= SLED_T_SCALE) {
-        // scales of an 8-bit matrix: float32 [rows], into the row order of the fused matrix
+        // scales of an 8-bit matrix: float32 [rows]; of a 4-bit matrix: one byte per row and 32 k, [rows, K/32];
+        // both go into the row order of the fused matrix
         const int mat = tensor_id - SLED_T_SCALE;
-        if (!m->w8) SLED_FAIL(SLED_EINVAL, "sled_model_load: scales given to a model without 8-bit weights");
+        if (m->wbits == 16) SLED_FAIL(SLED_EINVAL, "sled_model_load: scales given to a model with 16-bit weights");
         const bool lay = mat >= SLED_T_WQ && mat <= SLED_T_WDOWN;
         if (lay && (layer < 0 || layer >= s.n_layers)) SLED_FAIL(SLED_EINVAL, "sled_model_load: layer %d out of range", layer);
         sled_layer_weights* ws = lay ? &m->layers[layer] : nullptr;
-        const float* f = static_cast<const float*>(src);
+        auto put = [&](void* dst, int rows, int K, int row0, int stride, int rows_total) {
+            if (m->wbits == 8) return sled_launch_scatter_scales(static_cast<const float*>(src), static_cast<float*>(dst), rows, row0, stride, st);
+            return sled_launch_pack_scales_w4(src, dst, rows, K, row0, stride, rows_total, st);
+        };
         switch (mat) {
-            case SLED_T_WQ: return sled_launch_scatter_scales(f, ws->s_qkv, HD, 0, 1, st);
-            case SLED_T_WK: return sled_launch_scatter_scales(f, ws->s_qkv, KD, HD, 1, st);
-            case SLED_T_WV: return sled_launch_scatter_scales(f, ws->s_qkv, KD, HD + KD, 1, st);
-            case SLED_T_WO: return sled_launch_scatter_scales(f, ws->s_o, d, 0, 1, st);
-            case SLED_T_WGATE: return sled_launch_scatter_scales(f, ws->s_gu, F, 0, 2, st);
-            case SLED_T_WUP: return sled_launch_scatter_scales(f, ws->s_gu, F, 1, 2, st);
-            case SLED_T_WDOWN: return sled_launch_scatter_scales(f, ws->s_down, d, 0, 1, st);
-            case SLED_T_LM_HEAD: return sled_launch_scatter_scales(f, m->s_lm, s.vocab, 0, 1, st);
+            case SLED_T_WQ: return put(ws->s_qkv, HD, d, 0, 1, m->n_qkv);
+            case SLED_T_WK: return put(ws->s_qkv, KD, d, HD, 1, m->n_qkv);
+            case SLED_T_WV: return put(ws->s_qkv, KD, d, HD + KD, 1, m->n_qkv);
+            case SLED_T_WO: return put(ws->s_o, d, HD, 0, 1, d);
+            case SLED_T_WGATE: return put(ws->s_gu, F, d, 0, 2, 2 * F);
+            case SLED_T_WUP: return put(ws->s_gu, F, d, 1, 2, 2 * F);
+            case SLED_T_WDOWN: return put(ws->s_down, d, F, 0, 1, d);
+            case SLED_T_LM_HEAD: return put(m->s_lm, s.vocab, d, 0, 1, s.vocab);
             default: SLED_FAIL(SLED_EINVAL, "sled_model_load: tensor %d has no scales", mat);
         }
     }
     sled_layer_weights* w = per_layer ? &m->layers[layer] : nullptr;
-    if (m->w8) {
-        // matrices arrive as FP8 E4M3 bytes [out, in]
+    if (m->wbits != 16) {
+        // matrices arrive as FP8 E4M3 bytes [out, in], or as FP4 E2M1 codes, two per byte, [out, in / 2]
+        auto put = [&](void* dst, int rows, int K, int row0, int stride, int rows_total) {
+            if (m->wbits == 8) return sled_launch_pack_rows_w8(src, dst, rows, K, row0, stride, rows_total, st);
+            return sled_launch_pack_rows_w4(src, dst, rows, K, row0, stride, rows_total, st);
+        };
         switch (tensor_id) {
-            case SLED_T_WQ: return sled_launch_pack_rows_w8(src, w->w_qkv, HD, d, 0, 1, m->n_qkv, st);
-            case SLED_T_WK: return sled_launch_pack_rows_w8(src, w->w_qkv, KD, d, HD, 1, m->n_qkv, st);
-            case SLED_T_WV: return sled_launch_pack_rows_w8(src, w->w_qkv, KD, d, HD + KD, 1, m->n_qkv, st);
-            case SLED_T_WO: return sled_launch_pack_rows_w8(src, w->w_o, d, HD, 0, 1, d, st);
-            case SLED_T_WGATE: return sled_launch_pack_rows_w8(src, w->w_gu, F, d, 0, 2, 2 * F, st);
-            case SLED_T_WUP: return sled_launch_pack_rows_w8(src, w->w_gu, F, d, 1, 2, 2 * F, st);
-            case SLED_T_WDOWN: return sled_launch_pack_rows_w8(src, w->w_down, d, F, 0, 1, d, st);
-            case SLED_T_LM_HEAD: return sled_launch_pack_rows_w8(src, m->lm_head, s.vocab, d, 0, 1, s.vocab, st);
+            case SLED_T_WQ: return put(w->w_qkv, HD, d, 0, 1, m->n_qkv);
+            case SLED_T_WK: return put(w->w_qkv, KD, d, HD, 1, m->n_qkv);
+            case SLED_T_WV: return put(w->w_qkv, KD, d, HD + KD, 1, m->n_qkv);
+            case SLED_T_WO: return put(w->w_o, d, HD, 0, 1, d);
+            case SLED_T_WGATE: return put(w->w_gu, F, d, 0, 2, 2 * F);
+            case SLED_T_WUP: return put(w->w_gu, F, d, 1, 2, 2 * F);
+            case SLED_T_WDOWN: return put(w->w_down, d, F, 0, 1, d);
+            case SLED_T_LM_HEAD: return put(m->lm_head, s.vocab, d, 0, 1, s.vocab);
             default: break;  // embedding and gains as in a 16-bit model
         }
     }
@@ -206,29 +214,31 @@ struct prof_scope {
 extern "C" int sled_model_set_weight_bits(sled_model* m, int bits) {
     if (!m) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: null model");
     if (bits == 16) {
-        m->w8 = false;
+        m->wbits = 16;
         return SLED_OK;
     }
-    if (bits != 8) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: %d bits unsupported (16 or 8)", bits);
+    if (bits != 8 && bits != 4) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: %d bits unsupported (16, 8 or 4)", bits);
     const sled_shape& s = m->s;
-    if (s.dtype != SLED_BF16) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: 8-bit weights need a bf16 model");
+    if (s.dtype != SLED_BF16) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: 8- and 4-bit weights need a bf16 model");
     if (m->n_qkv % 64 || s.d_model % 64 || (2 * s.d_ffn) % 64 || s.vocab % 64)
         SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: output widths must be multiples of 64");
     if (!m->s_lm) {
+        // room for either kind of scales: a float per row, or a byte per row and 32 k
         int rc = SLED_OK;
-        auto A = [&](float** p, size_t n) {
-            if (rc == SLED_OK) rc = model_alloc(m, reinterpret_cast<void**>(p), n * sizeof(float));
+        auto A = [&](void** p, size_t rows, size_t K) {
+            if (rc == SLED_OK) rc = model_alloc(m, p, std::max(rows * sizeof(float), rows * (K / 32)));
         };
-        A(&m->s_lm, s.vocab);
+        const size_t d = s.d_model, HD = (size_t)s.n_q_heads * s.head_dim;
+        A(&m->s_lm, s.vocab, d);
         for (auto& w : m->layers) {
-            A(&w.s_qkv, m->n_qkv);
-            A(&w.s_o, s.d_model);
-            A(&w.s_gu, 2 * (size_t)s.d_ffn);
-            A(&w.s_down, s.d_model);
+            A(&w.s_qkv, m->n_qkv, d);
+            A(&w.s_o, d, HD);
+            A(&w.s_gu, 2 * (size_t)s.d_ffn, d);
+            A(&w.s_down, d, s.d_ffn);
         }
         if (rc != SLED_OK) return rc;
     }
-    m->w8 = true;
+    m->wbits = bits;
     return SLED_OK;
 }
 

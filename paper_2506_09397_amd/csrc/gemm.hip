@@ -81,6 +81,16 @@ __device__ __forceinline__ bf16x8_t cvt_w8(uint32_t lo, uint32_t hi) {
     return __builtin_bit_cast(bf16x8_t, p);
 }
 
+// Eight 4-bit weights (FP4 E2M1, low nibble first) times a power-of-two block scale -> a bf16 MFMA operand; exact
+__device__ __forceinline__ bf16x8_t cvt_w4(uint32_t codes, float scale) {
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_hw;
+    const u32x4_t p = {__builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0)),
+                       __builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1)),
+                       __builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 2)),
+                       __builtin_bit_cast(uint32_t, (bf16x2_hw)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 3))};
+    return __builtin_bit_cast(bf16x8_t, p);
+}
+
 // the same for a single register (never pass one register twice to the two-operand form: the second operand would
 // be a copy taken while the load is still in flight)
 template <int N>
@@ -89,13 +99,22 @@ __device__ __forceinline__ void wait_load(u32x4_t& a) {
     asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
 }
 
-// MT: 32-row tiles of activations per block.  W8: the weights are 8-bit (see w8_offset): the wavefront's two column
+typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned u32x2_t;
+// ... and for the two registers of a 4-bit stage (codes and scales)
+template <int N>
+__device__ __forceinline__ void wait_load4(u32x2_t& a, uint32_t& b) {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+
+// MT: 32-row tiles of activations per block.  WB: bits per weight.  8 (see w8_offset): the wavefront's two column
 // tiles come with ONE load per stage, are widened to bf16 in registers, and the accumulators are multiplied by the
-// columns' scales on the way out.
-template <int MT, int EPI, int KG, int CG, bool W8>
+// columns' scales on the way out.  4 (see w4_offset): one 8-byte load per stage for the codes and one 2-byte load
+// for the two rows' block scales, which the widening instruction applies.
+template <int MT, int EPI, int KG, int CG, int WB>
 __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
                                                                const bf16_t* __restrict__ Wp,
-                                                               const float* __restrict__ scale, int NT, int KS,
+                                                               const void* __restrict__ scale_v, int NT, int KS,
                                                                int ks_per_split, int n_col, int n_split, int n_zb,
                                                                int T, int T_pad, int N, float* __restrict__ out,
                                                                bf16_t* __restrict__ out_act, size_t act_plane,
@@ -103,8 +122,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int STAGE_TILES = PLANES * MT * KG;  // 1 KiB operand tiles per stage, ordered [plane][row tile][k-step]
     constexpr int MY_TILES = STAGE_TILES / WAVES;  // = MT: tiles of a stage this wavefront fetches
-    constexpr int NWL = W8 ? 1 : NW;               // weight loads per stage
-    constexpr int PER_ITER = MY_TILES + NWL;       // vector-memory instructions a wavefront issues per stage
+    constexpr bool W8 = WB == 8, W4 = WB == 4;
+    static_assert(WB == 16 || W8 || W4, "16-, 8- or 4-bit weights");
+    constexpr int NWL = WB == 16 ? NW : 1;         // weight loads per stage
+    constexpr int NSL = W4 ? 1 : 0;                // block-scale loads per stage
+    constexpr int PER_ITER = MY_TILES + NWL + NSL; // vector-memory instructions a wavefront issues per stage
+    const float* scale = static_cast<const float*>(scale_v);
     constexpr unsigned STAGE_BYTES = STAGE_TILES * 1024;
     static_assert(KG * CG == WAVES, "a workgroup is eight wavefronts");
     static_assert(STAGE_TILES % WAVES == 0, "stage does not divide among the wavefronts");
@@ -162,23 +185,37 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
 
     // ---- weights: NW tiles per stage, straight into registers ------------------------------------------
     const int nt0 = (bx * CG + cg) * NW;
-    const int NTW = W8 ? NT / NW : NT;  // 1 KiB blocks per k-step (an 8-bit block holds the wavefront's two tiles)
+    const int NTW = WB == 16 ? NT : NT / NW;  // blocks per k-step (an 8- or 4-bit block holds the wavefront's two tiles)
+    constexpr int WBLK = W4 ? 256 : 512;      // size of a block and of a lane's share, in 2-byte units
+    constexpr int WLANE = W4 ? 4 : 8;
     bool nt_ok[NW];
     const bf16_t* wsrc[NW];
 #pragma unroll
     for (int a = 0; a < NW; a++) {
         nt_ok[a] = (nt0 + a) < NT;
-        const int blk = W8 ? nt0 / NW : nt0 + a;
-        wsrc[a] = Wp + ((size_t)(ks_begin + kgi) * NTW + (nt_ok[a] ? blk : 0)) * 512 + lane * 8;
+        const int blk = WB == 16 ? nt0 + a : nt0 / NW;
+        wsrc[a] = Wp + ((size_t)(ks_begin + kgi) * NTW + (nt_ok[a] ? blk : 0)) * WBLK + lane * WLANE;
     }
+    // 4-bit weights: the scale bytes of k-block (ks_begin + stage * KG + kgi) / 2 for this lane's row in both tiles
+    const uint8_t* ssrc = static_cast<const uint8_t*>(scale_v);
+    if (W4) ssrc += ((size_t)((ks_begin + kgi) >> 1) * NTW + (nt_ok[0] ? nt0 / NW : 0)) * 64 + (lane & 31) * 2;
     u32x4_t wreg[NBUF][NWL];
-    auto w_issue_one = [&](int buf, int stage, int a) {
-        const bf16_t* src = wsrc[a] + (size_t)stage * KG * NTW * 512;
-        asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(wreg[buf][a]) : "v"(src) : "memory");
+    u32x2_t w4reg[NBUF];
+    uint32_t sreg[NBUF];
+    auto w_issue_one = [&](int buf, int stage, int a) {  // a: which of the stage's NWL + NSL weight-side loads
+        const bf16_t* src = wsrc[a < NWL ? a : 0] + (size_t)stage * KG * NTW * WBLK;
+        if (W4) {
+            if (a == 0)
+                asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(w4reg[buf]) : "v"(src) : "memory");
+            else
+                asm volatile("global_load_ushort %0, %1, off" : "=&v"(sreg[buf]) : "v"(ssrc + (size_t)stage * (KG / 2) * NTW * 64) : "memory");
+        } else {
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(wreg[buf][a]) : "v"(src) : "memory");
+        }
     };
     auto w_issue = [&](int buf, int stage) {
 #pragma unroll
-        for (int a = 0; a < NWL; a++) w_issue_one(buf, stage, a);
+        for (int a = 0; a < NWL + NSL; a++) w_issue_one(buf, stage, a);
     };
 
     float16_t acc[NW][MT];
@@ -221,7 +258,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     auto stage = [&](auto after_c, int xbuf, auto wbuf_c, bool more, int x_stage, int x_buf, int w_stage) {
         constexpr int AFTER = decltype(after_c)::value, WBUF = decltype(wbuf_c)::value;
         bf16x8_t w0, w1;
-        if (W8) {
+        if (W4) {
+            wait_load4<AFTER>(w4reg[WBUF], sreg[WBUF]);
+            const uint32_t sb = sreg[WBUF];  // E8M0 bytes: 2^(e - 127) is the float with exponent field e
+            w0 = cvt_w4(w4reg[WBUF][0], __uint_as_float((sb & 0xffu) << 23));
+            w1 = cvt_w4(w4reg[WBUF][1], __uint_as_float((sb >> 8) << 23));
+        } else if (W8) {
             wait_load<AFTER>(wreg[WBUF][0]);
             const u32x4_t r = wreg[WBUF][0];
             w0 = cvt_w8(r[0], r[1]);
@@ -293,9 +335,9 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     // last trip: only the weights of the last stage are left to fetch (in its first iteration)
     stage(integral_constant<int, STEADY>{}, xbuf, integral_constant<int, 0>{}, true, -1, 0, s0 + DEPTH);
     advance();
-    stage(integral_constant<int, PER_ITER + NWL>{}, xbuf, integral_constant<int, 1>{}, true, -1, 0, -1);
+    stage(integral_constant<int, PER_ITER + NWL + NSL>{}, xbuf, integral_constant<int, 1>{}, true, -1, 0, -1);
     advance();
-    stage(integral_constant<int, NWL>{}, xbuf, integral_constant<int, 2>{}, true, -1, 0, -1);
+    stage(integral_constant<int, NWL + NSL>{}, xbuf, integral_constant<int, 2>{}, true, -1, 0, -1);
     advance();
     stage(integral_constant<int, 0>{}, xbuf, integral_constant<int, 3>{}, false, -1, 0, -1);
     __syncthreads();  // every stage has been consumed and no load is in flight: the ring is free
@@ -428,7 +470,8 @@ struct gemm_args {
     const bf16_t* X;
     size_t x_plane;
     const bf16_t* W;
-    const float* scale;
+    const void* scale;
+    int wbits;
     int NT, KS, kps, n_col, n_split, n_zb, T, T_pad, N;
     float* out;
     bf16_t* out_act;
@@ -436,11 +479,11 @@ struct gemm_args {
     int F_act;
 };
 
-template <int MT, int EPI, int KG, int CG, bool W8>
+template <int MT, int EPI, int KG, int CG, int WB>
 int launch_one(const gemm_args& a) {
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
-    auto kern = gemm_bf16_kernel<MT, EPI, KG, CG, W8>;
+    auto kern = gemm_bf16_kernel<MT, EPI, KG, CG, WB>;
     if (!allowed) {
         SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
@@ -451,18 +494,22 @@ int launch_one(const gemm_args& a) {
     return SLED_OK;
 }
 
-template <int MT, int KG, int CG, bool W8>
-int launch_epi8(int epi, const gemm_args& a) {
+template <int MT, int KG, int CG, int WB>
+int launch_epi_wb(int epi, const gemm_args& a) {
     switch (epi) {
-        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL, KG, CG, W8>(a);
-        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU, KG, CG, W8>(a);
-        default: return launch_one<MT, SLED_EPI_STORE, KG, CG, W8>(a);
+        case SLED_EPI_PARTIAL: return launch_one<MT, SLED_EPI_PARTIAL, KG, CG, WB>(a);
+        case SLED_EPI_SWIGLU: return launch_one<MT, SLED_EPI_SWIGLU, KG, CG, WB>(a);
+        default: return launch_one<MT, SLED_EPI_STORE, KG, CG, WB>(a);
     }
 }
 
 template <int MT, int KG, int CG>
 int launch_epi(int epi, const gemm_args& a) {
-    return a.scale ? launch_epi8<MT, KG, CG, true>(epi, a) : launch_epi8<MT, KG, CG, false>(epi, a);
+    switch (a.wbits) {
+        case 8: return launch_epi_wb<MT, KG, CG, 8>(epi, a);
+        case 4: return launch_epi_wb<MT, KG, CG, 4>(epi, a);
+        default: return launch_epi_wb<MT, KG, CG, 16>(epi, a);
+    }
 }
 
 // tuning aid: SLED_GEMM_TUNE="N:K:split;..." overrides the number of K slices of the projections with
@@ -506,7 +553,7 @@ sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs
     return p;
 }
 
-int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const float* scale, int T, int T_pad,
+int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const void* scale, int T, int T_pad,
                      int N, int K, int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane,
                      int F_act, hipStream_t st) {
     if (m->s.dtype == SLED_BF16) {
@@ -534,8 +581,10 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;
         a.W = static_cast<const bf16_t*>(W);
-        a.scale = m->w8 ? scale : nullptr;
-        if (m->w8 && (!scale || N % 64)) SLED_FAIL(SLED_EINVAL, "gemm: 8-bit weights need scales and N (%d) a multiple of 64", N);
+        a.wbits = m->wbits;
+        a.scale = m->wbits != 16 ? scale : nullptr;
+        if (m->wbits != 16 && (!scale || N % 64 || K % 32))
+            SLED_FAIL(SLED_EINVAL, "gemm: %d-bit weights need scales, N (%d) a multiple of 64 and K (%d) of 32", m->wbits, N, K);
         a.NT = NT;
         a.KS = KS;
         a.kps = KS / plan.split;

@@ -412,6 +412,30 @@ __global__ void pack_rows_w8_kernel(const uint8_t* __restrict__ src, uint8_t* __
     }
 }
 
+// rows of packed FP4 codes [rows, K/2] -> paired-tile order; a thread moves 8 codes (4 bytes)
+__global__ void pack_rows_w4_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int rows, int K, int dst_row0,
+                                    int dst_row_stride, int dst_row_tiles) {
+    const size_t n8 = (size_t)rows * (K / 8);
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n8; e += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / (K / 8));
+        const int c = (int)(e - (size_t)r * (K / 8)) * 8;
+        const int dr = dst_row0 + r * dst_row_stride;
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(src + (size_t)r * (K / 2) + c / 2);
+        *reinterpret_cast<uint32_t*>(dst + w4_offset(dr, c, dst_row_tiles)) = v;
+    }
+}
+
+// their scale bytes [rows, K/32] -> interleaved order
+__global__ void pack_scales_w4_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int rows, int KB, int dst_row0,
+                                      int dst_row_stride, int dst_row_tiles) {
+    const size_t n = (size_t)rows * KB;
+    for (size_t e = blockIdx.x * (size_t)blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(e / KB);
+        const int kb = (int)(e - (size_t)r * KB);
+        dst[w4_scale_offset(dst_row0 + r * dst_row_stride, kb, dst_row_tiles)] = src[e];
+    }
+}
+
 __global__ void scatter_scales_kernel(const float* __restrict__ src, float* __restrict__ dst, int rows, int dst_row0,
                                       int dst_row_stride) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -450,6 +474,30 @@ int sled_launch_pack_rows_w8(const void* src, void* dst, int rows, int K, int ds
     if (grid < 1) grid = 1;
     hipLaunchKernelGGL(pack_rows_w8_kernel, dim3(grid), dim3(256), 0, st, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
                        rows, K, dst_row0, dst_row_stride, dst_rows_total / 32);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_pack_rows_w4(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
+                             hipStream_t st) {
+    if (K % 32 || dst_rows_total % 64) SLED_FAIL(SLED_EINVAL, "4-bit weights: K %d or rows %d not tileable", K, dst_rows_total);
+    const size_t n8 = (size_t)rows * (K / 8);
+    int grid = (int)std::min<size_t>((n8 + 255) / 256, 65535);
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(pack_rows_w4_kernel, dim3(grid), dim3(256), 0, st, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
+                       rows, K, dst_row0, dst_row_stride, dst_rows_total / 32);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_pack_scales_w4(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
+                               hipStream_t st) {
+    if (K % 32 || dst_rows_total % 64) SLED_FAIL(SLED_EINVAL, "4-bit weights: K %d or rows %d not tileable", K, dst_rows_total);
+    const size_t n = (size_t)rows * (K / 32);
+    int grid = (int)std::min<size_t>((n + 255) / 256, 65535);
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(pack_scales_w4_kernel, dim3(grid), dim3(256), 0, st, static_cast<const uint8_t*>(src),
+                       static_cast<uint8_t*>(dst), rows, K / 32, dst_row0, dst_row_stride, dst_rows_total / 32);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

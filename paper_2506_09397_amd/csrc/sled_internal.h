@@ -90,6 +90,20 @@ __host__ __device__ inline size_t w8_offset(int r, int k, int NT) {
     return ((size_t)ks * (NT >> 1) + pair) * 1024 + (size_t)(((kk >> 3) << 5) + rl) * 16 + a * 8 + (kk & 7);
 }
 
+// 4-bit weights (FP4 E2M1 codes, two per byte, with one power-of-two scale per row and block of 32 k -- the
+// MXFP4 arrangement): byte offset of the byte that holds element (row r, column k); even k sit in the low nibble.
+// As for 8 bits two neighbouring row tiles share a block per k-step, now 512 bytes: lane l = (k%16 / 8) * 32 + r%32
+// holds 8 k-values of tile 2p in 4 bytes, then 8 of tile 2p+1.
+__host__ __device__ inline size_t w4_offset(int r, int k, int NT) {
+    const int pair = r >> 6, a = (r >> 5) & 1, rl = r & 31, ks = k >> 4, kk = k & 15;
+    return ((size_t)ks * (NT >> 1) + pair) * 512 + (size_t)(((kk >> 3) << 5) + rl) * 8 + a * 4 + ((kk & 7) >> 1);
+}
+// ... and of the scale byte (E8M0: 2^(e - 127)) of row r and k-block kb = k / 32: the two tiles of a pair
+// interleaved, so that a lane fetches both of its rows' scales with one 2-byte load
+__host__ __device__ inline size_t w4_scale_offset(int r, int kb, int NT) {
+    return ((size_t)kb * (NT >> 1) + (r >> 6)) * 64 + (size_t)(r & 31) * 2 + ((r >> 5) & 1);
+}
+
 // ------------------------------------------------------------------------------------------
 // handles
 // ------------------------------------------------------------------------------------------
@@ -100,11 +114,12 @@ struct sled_layer_weights {
     void* w_down;   // [ d, F ]
     float* g_attn;  // [d]
     float* g_mlp;   // [d]
-    // 8-bit weights only: one float scale per output row of each matrix (same row order as the matrix)
-    float* s_qkv = nullptr;
-    float* s_o = nullptr;
-    float* s_gu = nullptr;
-    float* s_down = nullptr;
+    // 8-bit weights: one float scale per output row of each matrix (same row order as the matrix);
+    // 4-bit weights: one scale byte per row and block of 32 k (w4_scale_offset)
+    void* s_qkv = nullptr;
+    void* s_o = nullptr;
+    void* s_gu = nullptr;
+    void* s_down = nullptr;
 };
 
 struct sled_model {
@@ -116,9 +131,10 @@ struct sled_model {
     float* g_final;
     std::vector<sled_layer_weights> layers;
     std::vector<void*> allocs;
-    // weights stored as FP8 E4M3 with one scale per output row (sled_model_set_weight_bits)
-    bool w8 = false;
-    float* s_lm = nullptr;     // [V] scales of the LM head
+    // bits per projection weight (sled_model_set_weight_bits): 16, 8 (FP8 E4M3, one scale per output row) or
+    // 4 (FP4 E2M1, one power-of-two scale per row and 32 k)
+    int wbits = 16;
+    void* s_lm = nullptr;      // scales of the LM head
     // results of a request bit-identical whatever batch it is verified in (sled_model_set_batch_invariant)
     bool batch_invariant = false;
     // kernel timing (sled_profile_enable): one (class, start event, end event) per launch
@@ -190,6 +206,12 @@ int sled_launch_copy_gain(int dtype, const void* src, float* dst, int n, hipStre
 int sled_launch_pack_rows_w8(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
                              hipStream_t st);
 int sled_launch_scatter_scales(const float* src, float* dst, int rows, int dst_row0, int dst_row_stride, hipStream_t st);
+// 4-bit weights: rows of packed FP4 codes [rows, K/2] into the order of w4_offset, and their scale bytes
+// [rows, K/32] into the order of w4_scale_offset
+int sled_launch_pack_rows_w4(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
+                             hipStream_t st);
+int sled_launch_pack_scales_w4(const void* src, void* dst, int rows, int K, int dst_row0, int dst_row_stride, int dst_rows_total,
+                               hipStream_t st);
 // row t of an activation buffer -> row 0 of a one-tile buffer (the single row the LM head is asked for)
 int sled_launch_copy_act_row(const sled_model* m, const void* X, size_t plane, int t, void* X1, size_t plane1, int d,
                              hipStream_t st);
@@ -215,8 +237,8 @@ struct sled_gemm_plan {
     int split;   // K slices
 };
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
-// `scale`: per-output-column scales of an 8-bit weight matrix (models with 8-bit weights), else nullptr
-int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const float* scale, int T, int T_pad,
+// `scale`: the scales of an 8-bit or 4-bit weight matrix (models with such weights), else nullptr
+int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const void* scale, int T, int T_pad,
                      int N, int K, int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane,
                      int F_act, hipStream_t st);
 

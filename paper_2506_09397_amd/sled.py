@@ -232,10 +232,12 @@ def sled_profile_read(model: int):
 # ---------------------------------------------------------------------------------------- helpers
 def load_weights(model: int, weights) -> None:
     """Streams every tensor of a synth.SynthWeights-like object (on the GPU) into the model.  An object with
-    bits == 8 (synth.SynthWeightsW8) is loaded as FP8 bytes plus per-row scales."""
-    w8 = getattr(weights, "bits", 16) == 8
+    bits == 8 (synth.SynthWeightsW8) is loaded as FP8 bytes plus per-row scales, one with bits == 4
+    (synth.SynthWeightsW4) as packed FP4 codes plus block exponents."""
+    bits = getattr(weights, "bits", 16)
+    w8 = bits != 16
     if w8:
-        _check(lib().sled_model_set_weight_bits(model, 8))
+        _check(lib().sled_model_set_weight_bits(model, bits))
 
     def put(name: str, layer: int) -> None:
         if w8 and name in weights.MATRICES:

@@ -3,7 +3,7 @@
     python -m paper_2506_09397_amd.sweeps batch     # step latency vs batch size and speculative length
     python -m paper_2506_09397_amd.sweeps rows      # projection time vs number of packed rows (MFMA regime)
     python -m paper_2506_09397_amd.sweeps prefill   # prompt ingest (sled_prefill): prompt length x rows per slice
-    python -m paper_2506_09397_amd.sweeps weights   # verify step with bf16 and with FP8 E4M3 weights, by rows
+    python -m paper_2506_09397_amd.sweeps weights   # verify step with bf16, FP8 and FP4 weights, by rows
 
 `batch` is the one-GPU analogue of the paper's throughput-versus-batch-size curve (Sec. 5) and of its
 study of the speculative length: Llama-3-8B shape, contexts uniform in [512, 2048], every request
@@ -138,13 +138,13 @@ def prefill_sweep(seed=0):
 
 
 def weights_sweep(seed=0):
-    """The verify step with bf16 and with 8-bit (FP8 E4M3 + per-row scale) weights, Llama-3-8B shape,
+    """The verify step with bf16, 8-bit (FP8 E4M3 + per-row scale) and 4-bit (FP4 E2M1 + block scale) weights, Llama-3-8B shape,
     1024 context tokens per request: where halving the weight stream pays (few packed rows) and
     where the projections are no longer bound by it (a hundred rows)."""
     shape = synth.SHAPES["llama8b"]
     cases = ((1, 4), (4, 4), (8, 3), (16, 5), (16, 7))
     res = {}
-    for name, cls in (("bf16", synth.SynthWeights), ("fp8", synth.SynthWeightsW8)):
+    for name, cls in (("bf16", synth.SynthWeights), ("fp8", synth.SynthWeightsW8), ("fp4", synth.SynthWeightsW4)):
         weights = cls(shape, seed=seed, device="cuda")
         K, V = synth.context_kv(shape, 1024, seed=seed, req=0, device="cuda")
         for B, k1 in cases:
@@ -157,11 +157,12 @@ def weights_sweep(seed=0):
             res[name, B, k1] = _time_steps(v, reqs, [k1] * B, tokens, steps=12, warmup=3, profile=True)
             v.destroy()
         del weights
-    print(f"{'B':>3s} {'k':>2s} {'rows':>5s} {'bf16 step ms':>13s} {'fp8 step ms':>12s} {'bf16 proj ms':>13s} {'fp8 proj ms':>12s} {'step ratio':>11s}")
+    print(f"{'B':>3s} {'k':>2s} {'rows':>5s} | step ms: {'bf16':>7s} {'fp8':>7s} {'fp4':>7s} | projections ms: {'bf16':>7s} {'fp8':>7s} {'fp4':>7s} | "
+          f"step vs bf16: {'fp8':>6s} {'fp4':>6s}")
     for B, k1 in cases:
-        a, b = res["bf16", B, k1], res["fp8", B, k1]
-        print(f"{B:3d} {k1:2d} {B * (k1 + 1):5d} {a['p50_ms']:13.3f} {b['p50_ms']:12.3f} {a['proj_ms']:13.3f} {b['proj_ms']:12.3f} "
-              f"{b['p50_ms'] / a['p50_ms']:11.3f}")
+        a, b, c = res["bf16", B, k1], res["fp8", B, k1], res["fp4", B, k1]
+        print(f"{B:3d} {k1:2d} {B * (k1 + 1):5d} |          {a['p50_ms']:7.3f} {b['p50_ms']:7.3f} {c['p50_ms']:7.3f} |                 "
+              f"{a['proj_ms']:7.3f} {b['proj_ms']:7.3f} {c['proj_ms']:7.3f} |               {b['p50_ms'] / a['p50_ms']:6.3f} {c['p50_ms'] / a['p50_ms']:6.3f}")
 
 
 if __name__ == "__main__":

@@ -176,6 +176,48 @@ class SynthWeightsW8(SynthWeights):
         return super().tensor(name, layer)
 
 
+class SynthWeightsW4(SynthWeightsW8):
+    """The same model with 4-bit projection weights in the MXFP4 arrangement: W[n][k] = fp4[n][k] * 2^(e[n][k // 32] - 127),
+    fp4 an E2M1 number (0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives), e one byte per row and block of 32 k.
+    The codes and exponents are drawn the way a quantiser would produce them from N(0, std) weights -- block
+    exponent from the block's largest magnitude, each weight rounded to the nearest E2M1 value -- but they are
+    inputs: tensor() returns the exact dequantised float32 matrix that the stored numbers mean.
+
+    q() returns the packed codes, uint8 [out, in / 2], even k in the low nibble; scale() the exponent bytes,
+    uint8 [out, in / 32]."""
+
+    bits = 4
+    _E2M1 = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)
+
+    def _codes(self, name: str, layer: int):
+        out_f, in_f = self._dims()[name]
+        w = self._randn(name, layer, out_f, in_f) * self.std
+        blocks = w.view(out_f, in_f // 32, 32)
+        amax = blocks.abs().amax(dim=2).clamp_min(1e-30)
+        e = torch.ceil(torch.log2(amax / 6.0)).clamp(-100, 100)           # smallest power of two with amax / 2^e <= 6
+        x = blocks / torch.exp2(e)[:, :, None]
+        table = torch.tensor(self._E2M1, device=w.device, dtype=torch.float32)
+        mid = (table[1:] + table[:-1]) / 2
+        mag = torch.bucketize(x.abs().contiguous(), mid)                  # index of the nearest magnitude
+        code = (mag + 8 * (x < 0)).to(torch.uint8).view(out_f, in_f)
+        return code, (e + 127).to(torch.uint8)
+
+    def q(self, name: str, layer: int = -1) -> torch.Tensor:
+        code, _ = self._codes(name, layer)
+        return (code[:, 0::2] | (code[:, 1::2] << 4)).contiguous()
+
+    def scale(self, name: str, layer: int = -1) -> torch.Tensor:
+        return self._codes(name, layer)[1].contiguous()
+
+    def tensor(self, name: str, layer: int = -1) -> torch.Tensor:
+        if name in self.MATRICES:
+            code, e = self._codes(name, layer)
+            table = torch.tensor(self._E2M1 + tuple(-v for v in self._E2M1), device=code.device, dtype=torch.float32)
+            val = table[code.long()]
+            return (val.view(code.shape[0], -1, 32) * torch.exp2(e.to(torch.float32) - 127.0)[:, :, None]).view(code.shape)
+        return SynthWeights.tensor(self, name, layer)
+
+
 def as_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of a stored tensor (fp32 or bf16) to a float64 numpy array on the host."""
     return t.detach().to("cpu").to(torch.float64).numpy()

@@ -1,6 +1,7 @@
-"""Models with 8-bit projection weights (weight-only quantisation, the 8-bit point of the bit-width sweep of
-Sec. 5): the library loads FP8 E4M3 bytes and their per-row scales, the oracle multiplies with the dequantised
-matrices fp8 * scale in float64.  Same storage contract for activations, same tolerance as for bf16 weights."""
+"""Models with 8-bit and 4-bit projection weights (weight-only quantisation, the 8- and 4-bit points of the
+bit-width sweep of Sec. 5): the library loads FP8 E4M3 bytes and their per-row scales, or FP4 E2M1 codes and
+their block exponents; the oracle multiplies with the dequantised matrices in float64.  Same storage contract
+for activations, same tolerance as for bf16 weights."""
 import numpy as np
 import pytest
 import torch
@@ -28,7 +29,7 @@ def _run(shape, w, ctx_len, k, seed, tol):
     got = v.verify(reqs, k, tokens).cpu().numpy().astype(np.float64)
     want = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w), oracle_requests(batch, Ks, Vs))], axis=0)
     err = np.abs(got - want).max()
-    print(f"8-bit weights, B={B} T={batch.T}: max |logit error| = {err:.3e} (logit std {want.std():.3f})")
+    print(f"{w.bits}-bit weights, B={B} T={batch.T}: max |logit error| = {err:.3e} (logit std {want.std():.3f})")
     assert err < tol
     # greedy acceptance on these logits equals the oracle's on its own
     a, t = v.accept(sled.GREEDY, k, torch.from_numpy(got.astype(np.float32)).cuda(), tokens)
@@ -56,6 +57,25 @@ def test_8b_shape_two_layers_with_8bit_weights():
     _run(shape, w, [700, 33, 1500, 256, 90], [8, 2, 5, 0, 7], seed=6, tol=2e-2)
 
 
+@pytest.mark.parametrize("ctx_len,k", [
+    ([64, 64, 64, 64], [4, 4, 4, 4]),
+    ([0, 5, 16, 17, 130, 257, 1000], [8, 0, 3, 8, 1, 7, 8]),
+    ([300] * 20, [2, 4, 6, 8] * 5),            # 120 rows: one full block
+    ([90] * 15, [8] * 15),                     # 135 rows: the wide shape
+    ([200, 40, 333] * 15, [8, 7, 8] * 15),     # 390 rows
+])
+def test_tiny_model_with_4bit_weights(ctx_len, k):
+    shape = synth.SHAPES["tiny_bf16"]
+    w = synth.SynthWeightsW4(shape, seed=2, device="cuda", std=0.02, gain_jitter=0.1)
+    _run(shape, w, ctx_len, k, seed=4, tol=5e-3)
+
+
+def test_8b_shape_two_layers_with_4bit_weights():
+    shape = synth.scaled_shape(synth.SHAPES["llama8b"], n_layers=2, vocab=8192)
+    w = synth.SynthWeightsW4(shape, seed=1, device="cuda")
+    _run(shape, w, [700, 33, 1500, 256, 90], [8, 2, 5, 0, 7], seed=6, tol=2e-2)
+
+
 def test_weight_bits_argument_errors():
     shape = synth.SHAPES["tiny"]                # an fp32 model cannot take 8-bit weights
     m = sled.sled_model_create(shape)
@@ -64,7 +84,7 @@ def test_weight_bits_argument_errors():
     sled.sled_model_destroy(m)
     m = sled.sled_model_create(synth.SHAPES["tiny_bf16"])
     with pytest.raises(sled.SledError):
-        sled._check(sled.lib().sled_model_set_weight_bits(m, 4))
+        sled._check(sled.lib().sled_model_set_weight_bits(m, 2))
     with pytest.raises(sled.SledError):          # scales for a 16-bit model
         sled.sled_model_load(m, sled.T_SCALE + sled.T_WQ, 0, torch.ones(1024, device="cuda"))
     sled.sled_model_destroy(m)
