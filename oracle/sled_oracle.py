@@ -336,6 +336,18 @@ def accept_batch(mode: str, k: Sequence[int], logits: np.ndarray, tokens: np.nda
     return out
 
 
+def row_confidence(logits: np.ndarray, temperature: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
+    """Confidence score of every row (Eq. 2 compares it with the threshold c_th): the probability that
+    softmax(logits / temperature) gives its most likely token, and that token (lowest id among ties)."""
+    conf = np.empty(logits.shape[0], dtype=np.float64)
+    top = np.empty(logits.shape[0], dtype=np.int64)
+    for r in range(logits.shape[0]):
+        p = softmax64(logits[r], temperature)
+        top[r], _ = argmax_lowest(logits[r])
+        conf[r] = p[top[r]]
+    return conf, top
+
+
 # --------------------------------------------------------------------------- decoding loops
 def decode_greedy(model: OracleModel, prompt: Sequence[int], n_new: int) -> List[int]:
     """Plain autoregressive greedy decoding with a cache: one token per forward."""

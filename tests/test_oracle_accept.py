@@ -298,3 +298,34 @@ def test_greedy_verify_loop_equals_autoregressive_decoding(drafter_kind):
         assert sum(acc) > 0 and len(acc) < n_new      # drafts were accepted: fewer rounds than tokens
     if drafter_kind == "empty":
         assert acc == [0] * n_new
+
+
+def test_row_confidence_closed_forms():
+    """Pins of the confidence score (Eq. 2): two classes give the logistic function of the logit gap over the
+    temperature; equal logits give 1/V with the lowest id; a shift of all logits changes nothing; the
+    temperature interpolates between 1/V and 1; and the score is the largest entry of a library softmax."""
+    from scipy.special import softmax as scipy_softmax
+    rng = np.random.default_rng(11)
+    for a, b, tau in ((0.3, -1.2, 1.0), (2.0, 2.5, 0.7), (-4.0, 3.0, 2.0)):
+        conf, top = O.row_confidence(np.array([[a, b]]), tau)
+        assert top[0] == (0 if a >= b else 1)
+        assert conf[0] == pytest.approx(1.0 / (1.0 + math.exp(-abs(a - b) / tau)), rel=1e-14)
+    conf, top = O.row_confidence(np.full((3, 17), 0.25))
+    assert np.allclose(conf, 1.0 / 17, rtol=1e-15) and (top == 0).all()
+    z = rng.normal(0, 2, size=(5, 300))
+    c0, t0 = O.row_confidence(z, 0.8)
+    c1, t1 = O.row_confidence(z + 123.5, 0.8)
+    assert np.allclose(c0, c1, rtol=1e-12) and (t0 == t1).all()
+    lib = scipy_softmax(z / 0.8, axis=1)
+    assert np.allclose(c0, lib.max(axis=1), rtol=1e-12) and (t0 == lib.argmax(axis=1)).all()
+    hot, _ = O.row_confidence(z, 1e-3)
+    cold, _ = O.row_confidence(z, 1e6)
+    assert np.allclose(hot, 1.0, atol=1e-9) and np.allclose(cold, 1.0 / 300, rtol=1e-4)
+    z[2, 40] = z[2, 7] = z[2].max() + 1.0          # a tie: the lower id wins, the score counts one of them
+    c2, t2 = O.row_confidence(z)
+    assert t2[2] == 7 and c2[2] == pytest.approx(lib_max_of(z[2]), rel=1e-12)
+
+
+def lib_max_of(row):
+    from scipy.special import softmax as scipy_softmax
+    return scipy_softmax(row).max()
