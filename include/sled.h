@@ -256,6 +256,17 @@ SLED_API int sled_accept_sparse(int B, const int* k /*host*/, int vocab, float t
                        const float* u_acc /*dev*/, const float* u_smp /*dev*/, int32_t* accept_len /*dev out*/,
                        int32_t* out_token /*dev out*/, void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
+/* Confidence score of every row of a logits matrix: conf[t] = max_v softmax(logits[t] / temperature)[v], the quantity
+ * the paper's dynamic drafting compares with its threshold c_th (Eq. 2: below it a device asks for verification,
+ * at or above it drafts another token), and top[t] = the token that attains it (lowest id among ties).  One pass
+ * over the logits, the same row scan that sled_accept starts with -- for a drafter that runs next to the server, or
+ * to tell a device how sure the target was of the token it sent back.
+ *   logits[T, V]  dev float32, finite;  conf[T] dev float32 out;  top[T] dev int32 out or NULL
+ *   workspace     dev scratch, 256-byte aligned, sled_accept_workspace_bytes(1, T, vocab) bytes
+ * Errors: SLED_EINVAL. */
+SLED_API int sled_row_confidence(int T, int vocab, float temperature, const float* logits /*dev*/, float* conf /*dev out*/,
+                        int32_t* top /*dev out or NULL*/, void* workspace /*dev*/, size_t workspace_bytes, void* stream);
+
 /* ---- kernel timing (measurement aid) ---------------------------------------------- */
 
 /* Kernel classes of one verification step. */

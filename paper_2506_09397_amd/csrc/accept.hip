@@ -448,6 +448,22 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     if (lane == 0) out_token[i] = found;
 }
 
+// confidence of every row: 1 / sum exp((z - max) / tau) is the probability of the most likely token
+__global__ void row_confidence_finish(const RowStat* __restrict__ stats, int T, int n_split, float inv_tau,
+                                      float* __restrict__ conf, int32_t* __restrict__ top) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= T) return;
+    float m = -INFINITY;
+    int idx = 0x7fffffff;
+    double s = 0.0;
+    for (int sp = 0; sp < n_split; sp++) {  // segments in ascending order of token id
+        const RowStat r = stats[(size_t)row * n_split + sp];
+        stat_merge<true>(m, idx, s, r.m, r.idx, r.s, inv_tau);
+    }
+    conf[row] = (float)(1.0 / s);
+    if (top) top[row] = idx;
+}
+
 }  // namespace
 
 size_t sled_accept_ws_bytes(int B, int T, int n_split) {
@@ -488,6 +504,20 @@ int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, flo
     // greedy needs only the deciding wavefront
     hipLaunchKernelGGL(accept_finish, dim3(B), dim3(mode == SLED_SAMPLE ? 1024 : 64), 0, st, mode, kp, vocab, n_split, inv_tau,
                        logits, tokens, qsrc, u_acc, u_smp, stats, accept_len, out_token);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_row_confidence(int T, int vocab, float temperature, const float* logits, float* conf, int32_t* top, void* ws,
+                               hipStream_t st) {
+    const int n_split = sled_accept_pick_split(T, vocab);
+    int seg = (vocab + n_split - 1) / n_split;
+    seg = (seg + 3) & ~3;
+    RowStat* stats = reinterpret_cast<RowStat*>(ws);
+    const float inv_tau = 1.0f / temperature;
+    hipLaunchKernelGGL(accept_row_stats<true>, dim3(T, n_split), dim3(256), 0, st, logits, vocab, n_split, seg, inv_tau, stats);
+    SLED_LAUNCH_CHECK();
+    hipLaunchKernelGGL(row_confidence_finish, dim3((T + 255) / 256), dim3(256), 0, st, stats, T, n_split, inv_tau, conf, top);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

@@ -901,3 +901,15 @@ extern "C" int sled_accept_sparse(int B, const int* k, int vocab, float temperat
     return sled_launch_accept(SLED_SAMPLE, B, T, k, vocab, temperature, logits, tokens, nullptr, q_ids, q_probs, q_m, u_acc,
                               u_smp, accept_len, out_token, workspace, static_cast<hipStream_t>(stream));
 }
+
+extern "C" int sled_row_confidence(int T, int vocab, float temperature, const float* logits, float* conf, int32_t* top,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (!logits || !conf || !workspace) SLED_FAIL(SLED_EINVAL, "sled_row_confidence: null argument");
+    if (T < 1 || T > (1 << 20)) SLED_FAIL(SLED_EINVAL, "sled_row_confidence: %d rows outside [1, 2^20]", T);
+    if (vocab < 2 || vocab > 2000000) SLED_FAIL(SLED_EINVAL, "sled_row_confidence: vocab %d unsupported", vocab);
+    if (!(temperature > 0.f)) SLED_FAIL(SLED_EINVAL, "sled_row_confidence: temperature must be positive");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) SLED_FAIL(SLED_EINVAL, "sled_row_confidence: workspace must be 256-byte aligned");
+    const size_t need = sled_accept_ws_bytes(1, T, sled_accept_pick_split(T, vocab));
+    if (need > workspace_bytes) SLED_FAIL(SLED_EINVAL, "sled_row_confidence: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    return sled_launch_row_confidence(T, vocab, temperature, logits, conf, top, workspace, static_cast<hipStream_t>(stream));
+}

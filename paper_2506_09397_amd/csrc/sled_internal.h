@@ -251,6 +251,8 @@ int sled_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 // accept.hip
 size_t sled_accept_ws_bytes(int B, int T, int n_split);
 int sled_accept_pick_split(int T, int vocab);
+int sled_launch_row_confidence(int T, int vocab, float temperature, const float* logits, float* conf, int32_t* top, void* ws,
+                               hipStream_t st);
 int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, float temperature, const float* logits,
                        const int32_t* tokens, const float* draft_q, const int32_t* q_ids, const float* q_probs, int q_m,
                        const float* u_acc, const float* u_smp, int32_t* accept_len, int32_t* out_token, void* ws,

@@ -32,7 +32,7 @@ EXPORTS = [
     "sled_model_set_weight_bits",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
     "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
-    "sled_accept_workspace_bytes", "sled_accept", "sled_accept_sparse", "sled_profile_enable", "sled_profile_read",
+    "sled_accept_workspace_bytes", "sled_accept", "sled_accept_sparse", "sled_row_confidence", "sled_profile_enable", "sled_profile_read",
     "sled_strerror", "sled_last_error",
 ]
 PROF_PROJ, PROF_ATTN, PROF_ROWS, PROF_N = 0, 1, 2, 3
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
     L.sled_accept_workspace_bytes.restype = C.c_size_t
     L.sled_accept.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_accept_sparse.argtypes = [C.c_int, ip, C.c_int, C.c_float, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.sled_row_confidence.argtypes = [C.c_int, C.c_int, C.c_float, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_profile_enable.argtypes = [vp, C.c_int]
     L.sled_profile_read.argtypes = [vp, vp, C.POINTER(C.c_float), ip]
     L.sled_strerror.argtypes = [C.c_int]
@@ -212,6 +213,14 @@ def sled_accept_sparse(k: Sequence[int], vocab: int, temperature: float, logits:
     _check(lib().sled_accept_sparse(len(k), _ints(k), vocab, float(temperature), _ptr(logits), _ptr(tokens), int(q_ids.shape[-1]),
                                     _ptr(q_ids), _ptr(q_probs), _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sled_row_confidence(vocab: int, temperature: float, logits: torch.Tensor, conf: torch.Tensor, top: Optional[torch.Tensor],
+                        workspace: torch.Tensor) -> None:
+    assert logits.dtype == torch.float32 and conf.dtype == torch.float32 and (top is None or top.dtype == torch.int32)
+    _check(lib().sled_row_confidence(int(logits.shape[0]), vocab, float(temperature), _ptr(logits), _ptr(conf),
+                                     _ptr(top) if top is not None else None, _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream()))
 
 
 def sled_model_set_batch_invariant(model: int, on: bool) -> None:

@@ -205,3 +205,51 @@ def test_accept_argument_errors():
     with pytest.raises(sled.SledError):
         sled.sled_accept(sled.SAMPLE, k, vocab, 1.0, case.logits, case.tokens, case.q, case.u_acc, case.u_smp, a, a.clone(),
                          ws[:64])
+
+
+@pytest.mark.parametrize("T,vocab,temperature,std", [
+    (1, 130, 1.0, 2.0),
+    (37, 1000, 0.7, 2.0),             # vocab not a multiple of the vector width
+    (9, 4099, 1.0, 4.0),              # odd vocab: scalar path
+    (101, 128256, 1.0, 1.28),         # the headline step's logits shape, logits of the random-weight model's scale
+    (2304, 128256, 2.0, 2.0),         # 256 requests x 9 rows: one segment per row
+])
+def test_row_confidence_matches_oracle(T, vocab, temperature, std):
+    """sled_row_confidence (the score Eq. 2 thresholds) against the oracle's float64 softmax: the token exactly
+    (unless the two best logits are closer than float32 resolves -- none at these seeds), the probability to
+    1e-5 relative (float32 exponentials, float64 sums)."""
+    from oracle import sled_oracle as O
+    g = torch.Generator(device="cuda").manual_seed(T * 7 + vocab)
+    logits = torch.randn(T, vocab, generator=g, device="cuda", dtype=torch.float32) * std
+    logits[0, min(5, vocab - 1)] = logits[0].max() + 3.0          # one confident row
+    if T > 2:
+        logits[2, :] = 0.125                                      # a row of equal logits: 1/V, token 0
+    conf = torch.empty(T, dtype=torch.float32, device="cuda")
+    top = torch.empty(T, dtype=torch.int32, device="cuda")
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(1, T, vocab))
+    sled.sled_row_confidence(vocab, temperature, logits, conf, top, ws)
+    torch.cuda.synchronize()
+    rows = range(T) if T <= 128 else list(range(0, T, 97)) + [T - 1]
+    want_c, want_t = O.row_confidence(logits[list(rows)].cpu().numpy().astype(np.float64), temperature)
+    got_c, got_t = conf.cpu().numpy()[list(rows)], top.cpu().numpy()[list(rows)]
+    assert (got_t == want_t).all()
+    assert np.abs(got_c / want_c - 1.0).max() < 1e-5
+    if T > 2:
+        assert top[2].item() == 0 and abs(conf[2].item() * vocab - 1.0) < 1e-5
+    # the token is optional
+    conf2 = torch.empty_like(conf)
+    sled.sled_row_confidence(vocab, temperature, logits, conf2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(conf, conf2)
+
+
+def test_row_confidence_argument_errors():
+    logits = torch.zeros(4, 256, device="cuda")
+    conf = torch.empty(4, device="cuda")
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(1, 4, 256))
+    with pytest.raises(sled.SledError):
+        sled.sled_row_confidence(256, 0.0, logits, conf, None, ws)          # temperature
+    with pytest.raises(sled.SledError):
+        sled.sled_row_confidence(1, 1.0, logits, conf, None, ws)            # vocabulary
+    with pytest.raises(sled.SledError):
+        sled.sled_row_confidence(256, 1.0, logits, conf, None, ws[:64])     # workspace too small
