@@ -56,7 +56,10 @@ constexpr int NXB = AHEAD + 1;    // LDS ring
 //   wide    KG 2, CG 4: 256 columns, 32 k per stage.  Per MFMA it fetches two thirds of the bytes (half the
 //           activations, the same weights): the shape for several row blocks, where the workgroups are many
 //           anyway and the L2 -> CU path, not HBM, is what the MFMAs wait for.
-constexpr int NARROW_KG = 4, NARROW_CG = 2, WIDE_KG = 2, WIDE_CG = 4;
+//   broad   KG 1, CG 8: 512 columns, 16 k per stage, no sums to exchange at the end.  Per MFMA it fetches half the
+//           bytes of the narrow shape; only a matrix with enough columns to fill the chip without K slices can use
+//           it (the LM head), and only with four row tiles (a stage's eight activation tiles go one to a wavefront).
+constexpr int NARROW_KG = 4, NARROW_CG = 2, WIDE_KG = 2, WIDE_CG = 4, BROAD_KG = 1, BROAD_CG = 8;
 constexpr int NARROW_COLS = NARROW_CG * NW * 32;
 
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float float16_t;
@@ -196,9 +199,9 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
         const int blk = WB == 16 ? nt0 + a : nt0 / NW;
         wsrc[a] = Wp + ((size_t)(ks_begin + kgi) * NTW + (nt_ok[a] ? blk : 0)) * WBLK + lane * WLANE;
     }
-    // 4-bit weights: the scale bytes of k-block (ks_begin + stage * KG + kgi) / 2 for this lane's row in both tiles
+    // 4-bit weights: the scale bytes of this lane's row in both tiles; those of k-block kb lie kb * NTW * 64 bytes on
     const uint8_t* ssrc = static_cast<const uint8_t*>(scale_v);
-    if (W4) ssrc += ((size_t)((ks_begin + kgi) >> 1) * NTW + (nt_ok[0] ? nt0 / NW : 0)) * 64 + (lane & 31) * 2;
+    if (W4) ssrc += (size_t)(nt_ok[0] ? nt0 / NW : 0) * 64 + (lane & 31) * 2;
     u32x4_t wreg[NBUF][NWL];
     u32x2_t w4reg[NBUF];
     uint32_t sreg[NBUF];
@@ -208,7 +211,10 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
             if (a == 0)
                 asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(w4reg[buf]) : "v"(src) : "memory");
             else
-                asm volatile("global_load_ushort %0, %1, off" : "=&v"(sreg[buf]) : "v"(ssrc + (size_t)stage * (KG / 2) * NTW * 64) : "memory");
+                asm volatile("global_load_ushort %0, %1, off"
+                             : "=&v"(sreg[buf])
+                             : "v"(ssrc + (size_t)((ks_begin + kgi + stage * KG) >> 1) * NTW * 64)  // a k-block is two k-steps
+                             : "memory");
         } else {
             asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(wreg[buf][a]) : "v"(src) : "memory");
         }
@@ -568,7 +574,9 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         const bool wide = mt_total > 4 && !m->batch_invariant;
         const int zb = (mt_total + 3) / 4;
         const int MT = wide ? 4 : (mt_total + zb - 1) / zb;
-        const int KG = wide ? WIDE_KG : NARROW_KG, CG = wide ? WIDE_CG : NARROW_CG;
+        // one block of four row tiles, no K slices, and column blocks of 512 that fill at least three quarters of the CUs
+        const bool broad = !wide && MT == 4 && plan.split == 1 && !m->batch_invariant && (NT + BROAD_CG * NW - 1) / (BROAD_CG * NW) >= 192;
+        const int KG = wide ? WIDE_KG : broad ? BROAD_KG : NARROW_KG, CG = wide ? WIDE_CG : broad ? BROAD_CG : NARROW_CG;
         gemm_args a;
         a.n_col = (NT + CG * NW - 1) / (CG * NW);
         a.n_split = plan.split;
@@ -596,6 +604,7 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.act_plane = act_plane;
         a.F_act = F_act;
         if (wide) return launch_epi<4, WIDE_KG, WIDE_CG>(epilogue, a);
+        if (broad) return launch_epi<4, BROAD_KG, BROAD_CG>(epilogue, a);
         switch (MT) {
             case 1: return launch_epi<1, NARROW_KG, NARROW_CG>(epilogue, a);
             case 2: return launch_epi<2, NARROW_KG, NARROW_CG>(epilogue, a);

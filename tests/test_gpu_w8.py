@@ -76,6 +76,15 @@ def test_8b_shape_two_layers_with_4bit_weights():
     _run(shape, w, [700, 33, 1500, 256, 90], [8, 2, 5, 0, 7], seed=6, tol=2e-2)
 
 
+@pytest.mark.parametrize("cls", [synth.SynthWeightsW8, synth.SynthWeightsW4])
+def test_full_vocabulary_head_with_lowbit_weights(cls):
+    """104 rows and the full 128256-token vocabulary: the LM head runs in its 512-column shape (no K groups), where
+    the 4-bit scale blocks advance by half a block per stage."""
+    shape = synth.scaled_shape(synth.SHAPES["llama8b"], n_layers=1)
+    w = cls(shape, seed=5, device="cuda")
+    _run(shape, w, [40] * 13, [7] * 13, seed=8, tol=2e-2)
+
+
 def test_weight_bits_argument_errors():
     shape = synth.SHAPES["tiny"]                # an fp32 model cannot take 8-bit weights
     m = sled.sled_model_create(shape)
