@@ -135,3 +135,38 @@ def test_512_rows_four_row_blocks_per_weight_tile():
     errs = _logit_errors(shape, w, batch, KV, got, sample, "8B layer shape, 512 rows")
     assert max(errs) < TOL_BF16
     v.destroy()
+
+
+@pytest.mark.parametrize("n_q,n_kv,k_max,ks", [
+    (8, 2, 8, [3, 0, 2, 1, 3]),           # G = 4, at most 16 query rows per (request, kv head): one query tile
+    (8, 2, 8, [7, 4, 5, 0]),              # 32 rows: two tiles
+    (8, 2, 15, [15, 12, 0, 7, 13, 15]),   # 64 rows: four tiles, drafts of up to 15 tokens
+    (8, 1, 9, [9, 4, 8, 0]),              # G = 8, 80 rows: five tiles, the largest supported
+    (8, 8, 15, [15, 3, 9]),               # no grouping (G = 1) with the longest drafts
+])
+def test_every_query_tile_count_of_the_attention_kernel(n_q, n_kv, k_max, ks):
+    """The attention kernel is instantiated for one to five 16-row query tiles per (request, kv head), chosen from
+    the batch's longest draft and the model's group size; every instantiation against the oracle, with contexts that
+    end inside a page, are shorter than a page, or are empty."""
+    from oracle import sled_oracle as O
+    from paper_2506_09397_amd.runtime import Verifier
+    from helpers import oracle_model, oracle_requests
+    shape = synth.scaled_shape(synth.SHAPES["tiny_bf16"], n_q_heads=n_q, n_kv_heads=n_kv, k_max=k_max)
+    w = synth.SynthWeights(shape, seed=9, device="cuda", std=0.03, gain_jitter=0.1)
+    B = len(ks)
+    ctx_len = [0, 5, 16, 131, 700, 257][:B]
+    budget = sum(ctx_len) + (k_max + 1) * B
+    v = Verifier(shape, w, budget // 16 + 3 * B + 8, B, B, budget)
+    batch = synth.make_batch(ctx_len, ks, shape.vocab, seed=3)
+    reqs = [v.open() for _ in range(B)]
+    Ks, Vs = [], []
+    for i in range(B):
+        K, V = synth.context_kv(shape, ctx_len[i], seed=3, req=i, device="cuda")
+        Ks.append(K); Vs.append(V)
+    v.append_context(reqs, Ks, Vs)
+    got = v.verify(reqs, ks, torch.from_numpy(batch.tokens).cuda()).cpu().numpy().astype(np.float64)
+    want = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w), oracle_requests(batch, Ks, Vs))], axis=0)
+    err = np.abs(got - want).max()
+    print(f"Hq/Hkv={n_q}/{n_kv} k_max={k_max} k={ks}: max |logit error| = {err:.3e} (logit std {want.std():.3f})")
+    assert err < 5e-3
+    v.destroy()
