@@ -14,10 +14,10 @@ from helpers import oracle_model, oracle_requests
 pytestmark = pytest.mark.gpu
 
 
-def _run(shape, w, ctx_len, k, seed, tol):
+def _run(shape, w, ctx_len, k, seed, tol, batch_invariant=False):
     B = len(k)
     budget = sum(ctx_len) + 9 * B
-    v = Verifier(shape, w, budget // 16 + 3 * B + 8, B, B, budget)
+    v = Verifier(shape, w, budget // 16 + 3 * B + 8, B, B, budget, batch_invariant=batch_invariant)
     batch = synth.make_batch(ctx_len, k, shape.vocab, seed=seed)
     reqs = [v.open() for _ in range(B)]
     Ks, Vs = [], []
@@ -83,6 +83,32 @@ def test_full_vocabulary_head_with_lowbit_weights(cls):
     shape = synth.scaled_shape(synth.SHAPES["llama8b"], n_layers=1)
     w = cls(shape, seed=5, device="cuda")
     _run(shape, w, [40] * 13, [7] * 13, seed=8, tol=2e-2)
+
+
+@pytest.mark.parametrize("cls", [synth.SynthWeightsW8, synth.SynthWeightsW4])
+def test_lowbit_weights_in_batch_invariant_mode(cls):
+    """390 rows with the batch-invariant switch: three row blocks through the narrow projection shape."""
+    shape = synth.SHAPES["tiny_bf16"]
+    w = cls(shape, seed=2, device="cuda", std=0.02, gain_jitter=0.1)
+    _run(shape, w, [200, 40, 333] * 15, [8, 7, 8] * 15, seed=4, tol=5e-3, batch_invariant=True)
+
+
+@pytest.mark.parametrize("cls", [synth.SynthWeightsW8, synth.SynthWeightsW4])
+def test_prompt_ingest_with_lowbit_weights(cls):
+    """sled_prefill on a model with 8- or 4-bit weights: many-row slices (the wide projection shape) and the one-row
+    LM head, against the oracle's plain causal forward over the prompt."""
+    shape = synth.SHAPES["tiny_bf16"]
+    w = cls(shape, seed=6, device="cuda", std=0.05, gain_jitter=0.1)
+    v = Verifier(shape, w, 64, 2, 40, 1024)
+    om = oracle_model(shape, w)
+    for L in (9, 300):
+        p = synth.context_tokens(L, shape.vocab, seed=70 + L)
+        r = v.open()
+        got = v.prefill(r, torch.from_numpy(p.astype(np.int32)).cuda()).cpu().numpy().astype(np.float64)
+        err = np.abs(got - O.prefill(om, p)["logits"][-1]).max()
+        print(f"{w.bits}-bit weights, prompt of {L}: max |last-token logit error| = {err:.3e}")
+        assert err < 5e-3 and v.lengths([r]) == [L]
+    v.destroy()
 
 
 def test_weight_bits_argument_errors():
