@@ -144,7 +144,7 @@ def main():
     # grew by about one token per step); used for the algorithmic K/V bytes
     lens = v.lengths(reqs)
     kv_bytes = sum(lens) * shape.kv_bytes_per_token()
-    weight_bytes = shape.streamed_params() * {"bf16": 32, "fp8": 16, "fp4": 8.5}[args.weights] / 16   # fp4: codes + a scale byte per 32
+    weight_bytes = int(shape.streamed_params() * {"bf16": 32, "fp8": 16, "fp4": 8.5}[args.weights] / 16)   # fp4: codes + a scale byte per 32
     logits_bytes = T * shape.vocab * 4
 
     # event-instrumented region: per-class kernel time on the stream the kernels run on
