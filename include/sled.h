@@ -116,7 +116,9 @@ SLED_API int sled_model_load(sled_model* m, int tensor_id, int layer, const void
  * W[n][k] = fp8[n][k] * scale[n]: weight-only quantisation, the 8-bit point of the paper's bit-width sweep
  * (Sec. 5).  Activations, K/V cache and arithmetic stay as in a bf16 model (an FP8 value is exact in bf16; the
  * scale is applied to the float32 accumulator), so the weight stream halves and nothing else changes.
- * Call it right after sled_model_create, before any sled_model_load; the matrices are then loaded as FP8 bytes
+ * Call it right after sled_model_create, before any sled_model_load: the matrices' device storage is given back and
+ * allocated anew at bits/8 bytes per weight (a 70B-shaped model takes 141, 71 or 37 GB), so whatever was loaded
+ * before is lost, and after SLED_ENOMEM the model can only be destroyed.  The matrices are then loaded as FP8 bytes
  * [out, in] (dev) and their scales under SLED_T_SCALE + id.  NaN encodings are the caller's to avoid.  bf16
  * models whose projection widths are multiples of 64 only.  bits = 16 restores the default.
  * bits = 4: the 4-bit point of the same sweep, in the MXFP4 arrangement -- FP4 E2M1 codes (0, 0.5, 1, 1.5, 2, 3, 4, 6

@@ -45,6 +45,18 @@ static int model_alloc(sled_model* m, void** out, size_t bytes) {
     return SLED_OK;
 }
 
+// replaces the allocation *p by one of `bytes` bytes (contents are not kept)
+static int model_resize(sled_model* m, void** p, size_t bytes) {
+    for (size_t i = 0; i < m->allocs.size(); i++)
+        if (m->allocs[i] == *p) {
+            (void)hipFree(*p);
+            m->allocs.erase(m->allocs.begin() + i);
+            break;
+        }
+    *p = nullptr;
+    return model_alloc(m, p, bytes);
+}
+
 extern "C" int sled_model_create(const sled_shape* shape, sled_model** out) {
     if (!shape || !out) SLED_FAIL(SLED_EINVAL, "sled_model_create: null argument");
     const sled_shape& s = *shape;
@@ -213,15 +225,31 @@ struct prof_scope {
 
 extern "C" int sled_model_set_weight_bits(sled_model* m, int bits) {
     if (!m) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: null model");
-    if (bits == 16) {
-        m->wbits = 16;
-        return SLED_OK;
-    }
-    if (bits != 8 && bits != 4) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: %d bits unsupported (16, 8 or 4)", bits);
+    if (bits != 16 && bits != 8 && bits != 4) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: %d bits unsupported (16, 8 or 4)", bits);
     const sled_shape& s = m->s;
+    if (bits == 16 && s.dtype != SLED_BF16) return SLED_OK;  // an fp32 model has no other format
     if (s.dtype != SLED_BF16) SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: 8- and 4-bit weights need a bf16 model");
-    if (m->n_qkv % 64 || s.d_model % 64 || (2 * s.d_ffn) % 64 || s.vocab % 64)
+    if (bits != 16 && (m->n_qkv % 64 || s.d_model % 64 || (2 * s.d_ffn) % 64 || s.vocab % 64))
         SLED_FAIL(SLED_EINVAL, "sled_model_set_weight_bits: output widths must be multiples of 64");
+    if (bits != m->wbits) {
+        // the projection matrices take bits/8 bytes per weight: give back what the previous format held
+        SLED_HIP(hipDeviceSynchronize());
+        int rc = SLED_OK;
+        auto R = [&](void** p, size_t rows, size_t K) {
+            if (rc == SLED_OK) rc = model_resize(m, p, rows * K * bits / 8);
+        };
+        const size_t d = s.d_model, HD = (size_t)s.n_q_heads * s.head_dim, F = s.d_ffn;
+        R(&m->lm_head, s.vocab, d);
+        for (auto& w : m->layers) {
+            R(&w.w_qkv, m->n_qkv, d);
+            R(&w.w_o, d, HD);
+            R(&w.w_gu, 2 * F, d);
+            R(&w.w_down, d, F);
+        }
+        if (rc != SLED_OK) return rc;  // the model is unusable now: destroy it
+        m->wbits = bits;
+    }
+    if (bits == 16) return SLED_OK;
     if (!m->s_lm) {
         // room for either kind of scales: a float per row, or a byte per row and 32 k
         int rc = SLED_OK;
