@@ -558,7 +558,10 @@ int attn_pages_per_item(const std::vector<int>& np, int Hkv) {
         longest = std::max(longest, n);
     }
     const int cap = attn_item_cap((int)np.size(), Hkv);
-    int tgt = (int)std::max<int64_t>(8, (total * Hkv + cap - 1) / cap);
+    // at least 32 pages (eight rounds of the page loop) per item and at most eight items per (request, kv head):
+    // beyond that the hand-over between the items of a pair -- the last one to arrive reads the others' states, a round
+    // trip to memory for every four of them -- costs more than the extra workgroups save
+    int tgt = (int)std::max<int64_t>(std::max(32, ceil_div(longest, 8)), (total * Hkv + cap - 1) / cap);
     for (; tgt < longest; tgt++) {
         int64_t items = 0;
         for (int n : np) items += (int64_t)Hkv * ceil_div(n, tgt);
