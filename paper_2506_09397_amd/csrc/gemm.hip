@@ -354,42 +354,57 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
     // in runs (k-group g owns units g * UPW .. (g + 1) * UPW - 1, i.e. whole row tiles when MT is a multiple of KG, so
     // that the stores of one wavefront fill whole 128-byte lines of an output row): each sends the units it does not
     // own to their owners and adds what it receives to its own, always in ascending k-group order.  Afterwards all
-    // eight wavefronts hold a disjoint share of the block's outputs and all of them run the epilogue.  One column
-    // tile per pass, so that the exchange fits in the ring's memory.
-    constexpr int UPW = 4 * MT / KG;  // units per wavefront and column tile
-    auto owner = [](int b2, int q) { return (4 * b2 + q) / UPW; };
-    {
+    // eight wavefronts hold a disjoint share of the block's outputs and all of them run the epilogue.
+    // With two k-groups (the wide shape) k-group 0 owns everything instead and k-group 1 is done after sending: measured
+    // 2 % faster there than sharing the epilogue.
+    constexpr bool ALL_TO_0 = KG == 2;
+    constexpr int UPW = ALL_TO_0 ? 4 * MT : 4 * MT / KG;  // units per owning wavefront and column tile
+    auto owner = [](int b2, int q) { return ALL_TO_0 ? 0 : (4 * b2 + q) / UPW; };
+    // both column tiles in one pass where the parcels of both fit into the CU's 160 KiB, else one tile per pass
+    constexpr int PARCELS_PER_TILE = ALL_TO_0 ? CG * UPW : WAVES * (KG - 1) * UPW;  // KiB
+    constexpr int PASSES = PARCELS_PER_TILE * NW <= 160 ? 1 : NW, TILES_PER_PASS = NW / PASSES;
+    if (KG > 1) {
         float4_t* red = reinterpret_cast<float4_t*>(smem);
-        // parcel (destination k-group, source k-group, unit): 64 lanes x 16 bytes
-        auto parcel = [&](int dest, int src, int u) {
+        // parcel (destination k-group, source k-group, unit, column tile within the pass): 64 lanes x 16 bytes
+        auto parcel = [&](int dest, int src, int u, int ap) {
             // the destination has no slot of its own; src == dest is never accessed and maps to slot 0 to stay in range
             const int s2 = src < dest ? src : (src > dest ? src - 1 : 0);
-            return red + ((size_t)(((cg * KG + dest) * (KG - 1) + s2) * UPW + (u - dest * UPW))) * 64 + lane;
+            const int slot = ALL_TO_0 ? cg * UPW + u : ((cg * KG + dest) * (KG - 1) + s2) * UPW + (u - dest * UPW);
+            return red + ((size_t)(slot * TILES_PER_PASS + ap)) * 64 + lane;
         };
 #pragma unroll
-        for (int a = 0; a < NW; a++) {
+        for (int pass = 0; pass < PASSES; pass++) {
 #pragma unroll
-            for (int b2 = 0; b2 < MT; b2++)
+            for (int ap = 0; ap < TILES_PER_PASS; ap++) {
+                const int a = pass * TILES_PER_PASS + ap;
 #pragma unroll
-                for (int q = 0; q < 4; q++)
-                    if (owner(b2, q) != kgi)
-                        *parcel(owner(b2, q), kgi, 4 * b2 + q) =
-                            float4_t{acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
+                for (int b2 = 0; b2 < MT; b2++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++)
+                        if (owner(b2, q) != kgi)
+                            *parcel(owner(b2, q), kgi, 4 * b2 + q, ap) =
+                                float4_t{acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
+            }
             __syncthreads();
 #pragma unroll
-            for (int b2 = 0; b2 < MT; b2++)
+            for (int ap = 0; ap < TILES_PER_PASS; ap++) {
+                const int a = pass * TILES_PER_PASS + ap;
 #pragma unroll
-                for (int q = 0; q < 4; q++)
-                    if (owner(b2, q) == kgi) {
-                        const float4_t own = {acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
-                        float4_t v = kgi == 0 ? own : *parcel(kgi, 0, 4 * b2 + q);
+                for (int b2 = 0; b2 < MT; b2++)
 #pragma unroll
-                        for (int src = 1; src < KG; src++) v += kgi == src ? own : *parcel(kgi, src, 4 * b2 + q);
+                    for (int q = 0; q < 4; q++)
+                        if (owner(b2, q) == kgi) {
+                            const float4_t own = {acc[a][b2][4 * q], acc[a][b2][4 * q + 1], acc[a][b2][4 * q + 2], acc[a][b2][4 * q + 3]};
+                            float4_t v = kgi == 0 ? own : *parcel(kgi, 0, 4 * b2 + q, ap);
 #pragma unroll
-                        for (int i = 0; i < 4; i++) acc[a][b2][4 * q + i] = v[i];
-                    }
-            if (a + 1 < NW) __syncthreads();  // the parcels have been read: the next pass may overwrite them
+                            for (int src = 1; src < KG; src++) v += kgi == src ? own : *parcel(kgi, src, 4 * b2 + q, ap);
+#pragma unroll
+                            for (int i = 0; i < 4; i++) acc[a][b2][4 * q + i] = v[i];
+                        }
+            }
+            if (pass + 1 < PASSES) __syncthreads();  // the parcels have been read: the next pass may overwrite them
         }
+        if (ALL_TO_0 && kgi != 0) return;
     }
 
     // epilogue: lane holds row (token) mt*32 + lane%32 and, in registers 4q .. 4q+3, the columns
@@ -583,8 +598,9 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
         a.n_zb = zb;
         a.grid = dim3((a.n_col * a.n_split + 7) / 8 * 8 * a.n_zb, 1, 1);
         // the ring of activation stages; afterwards the same memory holds the parcels the k-groups exchange
-        // (one column tile at a time: every wavefront sends (KG - 1) / KG of its MT * 4 groups of 1 KiB)
-        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (size_t)WAVES * (KG - 1) * (4 * MT / KG) * 1024);
+        // (every wavefront sends (KG - 1) / KG of its MT * 4 groups of 1 KiB per column tile)
+        const size_t parcels = (size_t)WAVES * (KG - 1) * (4 * MT / KG);  // KiB per column tile; both tiles at once if they fit
+        a.lds = std::max((size_t)NXB * PLANES * MT * KG * 1024, (parcels * NW <= 160 ? parcels * NW : parcels) * 1024);
         a.st = st;
         a.X = static_cast<const bf16_t*>(X);
         a.x_plane = x_plane;

@@ -1,7 +1,7 @@
 """Measurement sweeps around the batched verify step (one MI355X, synthetic inputs, through the C ABI).
 
     python -m paper_2506_09397_amd.sweeps batch     # step latency vs batch size and speculative length
-    python -m paper_2506_09397_amd.sweeps rows      # projection time vs number of packed rows (MFMA regime)
+    python -m paper_2506_09397_amd.sweeps rows [llama70b] [sizes]   # projection time vs number of packed rows (MFMA regime)
     python -m paper_2506_09397_amd.sweeps prefill   # prompt ingest (sled_prefill): prompt length x rows per slice
     python -m paper_2506_09397_amd.sweeps weights   # verify step with bf16, FP8 and FP4 weights, by rows
 
@@ -78,8 +78,8 @@ def batch_sweep(seed=0):
         v.destroy()
 
 
-def rows_sweep(seed=0, sizes=(128, 256, 512, 1024, 2048, 4096)):
-    shape = synth.SHAPES["llama8b"]
+def rows_sweep(seed=0, sizes=(128, 256, 512, 1024, 2048, 4096), kind="llama8b"):
+    shape = synth.SHAPES[kind]
     weights = synth.SynthWeights(shape, seed=seed, device="cuda")
     rng = np.random.default_rng(seed)
     flop_per_row = 2.0 * shape.streamed_params()
@@ -172,8 +172,10 @@ if __name__ == "__main__":
     if which == "batch":
         batch_sweep()
     elif which == "rows":
-        # optional list of row counts, e.g. `rows 1024` for a counter run over one size
-        rows_sweep(sizes=tuple(int(a) for a in sys.argv[2:]) or (128, 256, 512, 1024, 2048, 4096))
+        # optional shape name and list of row counts, e.g. `rows 1024` for a counter run over one size, `rows llama70b`
+        args = sys.argv[2:]
+        kind = args.pop(0) if args and args[0] in synth.SHAPES else "llama8b"
+        rows_sweep(sizes=tuple(int(a) for a in args) or (128, 256, 512, 1024, 2048, 4096), kind=kind)
     elif which == "prefill":
         prefill_sweep()
     elif which == "weights":
