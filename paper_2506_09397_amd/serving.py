@@ -289,6 +289,8 @@ def main() -> None:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-invariant", action="store_true",
                     help="make a request's logits independent of its batch to the last bit (sled_model_set_batch_invariant)")
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "fp8", "fp4"],
+                    help="projection weight format of the target (sled_model_set_weight_bits)")
     ap.add_argument("--sweep", action="store_true", help="run batch sizes 4..32 x k in {2, 4, 8} instead of --batch/--k")
     args = ap.parse_args()
     sled.lib()
@@ -299,7 +301,8 @@ def main() -> None:
     rng = np.random.default_rng(args.seed)
     ctx = rng.integers(args.context // 2, args.context * 3 // 2 + 1, size=args.devices).tolist()
     budget = sum(ctx) + args.devices * (2 * args.tokens + 4 * (shape.k_max + 1))
-    weights = synth.SynthWeights(shape, seed=args.seed, device="cuda")
+    weights = {"bf16": synth.SynthWeights, "fp8": synth.SynthWeightsW8, "fp4": synth.SynthWeightsW4}[args.weights](
+        shape, seed=args.seed, device="cuda")
     v = Verifier(shape, weights, budget // 16 + 3 * args.devices + 8, args.devices, args.devices, budget,
                  batch_invariant=args.batch_invariant)
     server = Server(v, args.batch)
