@@ -245,8 +245,8 @@ def load_weights(model: int, weights) -> None:
     (synth.SynthWeightsW4) as packed FP4 codes plus block exponents."""
     bits = getattr(weights, "bits", 16)
     w8 = bits != 16
-    if w8:
-        _check(lib().sled_model_set_weight_bits(model, bits))
+    if weights.shape.dtype == "bf16":
+        _check(lib().sled_model_set_weight_bits(model, bits))   # also back to 16 on a model that held another format
 
     def put(name: str, layer: int) -> None:
         if w8 and name in weights.MATRICES:

@@ -111,6 +111,32 @@ def test_prompt_ingest_with_lowbit_weights(cls):
     v.destroy()
 
 
+def test_one_model_reloaded_in_every_weight_format():
+    """sled_model_set_weight_bits gives the matrices' storage back and allocates it anew for the next format: the
+    same model handle loaded with 8-bit, 4-bit and 16-bit weights in turn matches the oracle each time."""
+    shape = synth.SHAPES["tiny_bf16"]
+    ctx_len, k = [33, 200, 0], [5, 8, 2]
+    B = len(k)
+    v = Verifier(shape, synth.SynthWeightsW8(shape, seed=2, device="cuda", gain_jitter=0.1), 64, B, B, 512)
+    batch = synth.make_batch(ctx_len, k, shape.vocab, seed=9)
+    reqs = [v.open() for _ in range(B)]
+    Ks, Vs = [], []
+    for i in range(B):
+        K, V = synth.context_kv(shape, ctx_len[i], seed=9, req=i, device="cuda")
+        Ks.append(K); Vs.append(V)
+    v.append_context(reqs, Ks, Vs)
+    tokens = torch.from_numpy(batch.tokens).cuda()
+    for cls in (synth.SynthWeightsW8, synth.SynthWeightsW4, synth.SynthWeights, synth.SynthWeightsW4):
+        w = cls(shape, seed=2, device="cuda", gain_jitter=0.1)
+        sled.load_weights(v.model, w)
+        got = v.verify(reqs, k, tokens).cpu().numpy().astype(np.float64)
+        want = np.concatenate([r["logits"] for r in O.verify_batch(oracle_model(shape, w), oracle_requests(batch, Ks, Vs))], axis=0)
+        err = np.abs(got - want).max()
+        print(f"{getattr(w, 'bits', 16)}-bit weights on the reused model: max |logit error| = {err:.3e}")
+        assert err < 5e-3
+    v.destroy()
+
+
 def test_weight_bits_argument_errors():
     shape = synth.SHAPES["tiny"]                # an fp32 model cannot take 8-bit weights
     m = sled.sled_model_create(shape)
