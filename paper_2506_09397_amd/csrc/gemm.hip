@@ -13,10 +13,11 @@
 //     with both planes.  All wavefronts of a workgroup need all of them: they go from L2 into a
 //     ring of five LDS stage buffers with direct-to-LDS loads, four stages ahead.
 //   - A workgroup is 8 wavefronts (two per SIMD), all alike: 2 column groups x 4 k-groups (4 x 2 when the
-//     batch has several blocks of rows, see the two shapes below).  A stage is one k-step of 16 per k-group;
+//     batch has several blocks of rows, 8 x 1 for the LM head; see the shapes below).  A stage is one k-step of 16 per k-group;
 //     k-group g works on the g-th of them for the 64 columns (two 32-column
 //     tiles) of its column group and all rows of the block (MT 32-row tiles), and the k-groups'
-//     sums are added through LDS at the end, in a fixed order.  This shape follows from three
+//     sums are exchanged through LDS at the end and added in a fixed order, after which every wavefront stores a
+//     share of the outputs.  This shape follows from three
 //     per-CU limits that all sit within a factor of two of the HBM time: one wavefront sustains
 //     only about 4-5 bytes per clock from L2, so the activation stream (twice the weight bytes per
 //     CU) has to be issued by all eight; ds_read_b128 runs at about 64 bytes per clock, so each
@@ -29,6 +30,9 @@
 //   - Split-K over blockIdx.y gives every CU work on the narrow projections; partial sums go to a
 //     [split, T, N] fp32 buffer that the following row kernel reduces in a fixed order (no float
 //     atomics: results are reproducible run to run).
+//   - Weights may also be stored in 8 bits (FP8 E4M3, a scale per output row) or 4 bits (FP4 E2M1, a power-of-two
+//     scale per row and 32 k): the same tiles at half or a quarter of the bytes, widened to bf16 in registers by
+//     the hardware conversions; everything else is unchanged.
 //   - The weight tile is the A operand, the activation tile the B operand, so a lane ends up with
 //     groups of 4 consecutive output columns of one row: float4 stores, and gate/up pairs for
 //     SwiGLU in-lane.
