@@ -431,7 +431,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
                 float4_t v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
                 if (W8) v *= sc[q];
                 if (EPI == SLED_EPI_PARTIAL) {
-                    if (tok < T_pad) *reinterpret_cast<float4_t*>(out + ((size_t)by * T_pad + tok) * N + n) = v;
+                    if (tok < T) *reinterpret_cast<float4_t*>(out + ((size_t)by * T_pad + tok) * N + n) = v;  // padding rows are never read
                 } else if (EPI == SLED_EPI_STORE) {
                     if (tok < T) *reinterpret_cast<float4_t*>(out + (size_t)tok * N + n) = v;
                 } else {  // SwiGLU: columns are (gate f, up f, gate f+1, up f+1)
