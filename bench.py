@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # L2 fetch + write-back bytes per projection launch (FETCH_SIZE and WRITE_SIZE of rocprofv3, each scaled by
 # what the counter reads for a 1 GiB copy; profiles/verify_step_llama8b_b16_hbm_traffic.txt).  Taken with the
 # projection kernel as it stands; to be reset to None whenever that kernel changes.
-MEASURED_TRAFFIC = {"llama8b_b16": 150.2e6}
+MEASURED_TRAFFIC = {"llama8b_b16": 149.9e6}
 CPU_SAMPLE_REQUESTS, CPU_SAMPLE_LAYERS = 16, 24   # the oracle's bounded sample (about 10-20 s of CPU work)
 
 

@@ -435,7 +435,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
                 } else if (EPI == SLED_EPI_STORE) {
                     if (tok < T) *reinterpret_cast<float4_t*>(out + (size_t)tok * N + n) = v;
                 } else {  // SwiGLU: columns are (gate f, up f, gate f+1, up f+1)
-                    if (tok < T_pad) {
+                    if (tok < T) {  // padding rows: what a consumer reads there only reaches its own padding rows
                         const int f = n >> 1;
                         const float a0 = v[0] / (1.f + __expf(-v[0])) * v[1];
                         const float a1 = v[2] / (1.f + __expf(-v[2])) * v[3];
