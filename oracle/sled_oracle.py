@@ -9,7 +9,7 @@ context plus its draft tokens; the answer is the rejected position and a correct
 token):
 
   1. the target model's logits for the request's k+1 query tokens
-     [pending, draft_1 .. draft_k], scored "with one single forwarding" (Sec. 3.1)
+     [pending, draft_1 .. draft_k], all scored by a single forward pass (Sec. 3.1)
      on top of the request's cached context K/V -- forward_rows() / verify_batch();
   2. the acceptance decision of Eq. 1 (Sec. 3.1): accept draft x with probability
      min(1, p_target(x) / p_draft(x)), on failure resample from the normalised
@@ -26,19 +26,22 @@ position embedding with the half-split pairing (i, i + D/2) used by the public
 LLaMA implementations, grouped-query attention (query head h reads kv head
 h // group), SwiGLU MLP, no biases, untied LM head.
 
-Storage-rounding option (round_points).  A bf16 model keeps tensors in bf16 between
-operators; the oracle can round (to nearest, ties to even) exactly those tensors and
-nothing else.  All sums, the softmax denominator, the residual stream and the logits
-stay float64 in every mode.
-  "exact"   rounds nothing (weights and given context K/V are bf16 values already).
-  "bf16x2"  K and V of the new tokens are rounded to bf16 -- that is what a bf16 K/V cache
-            holds; every other activation between operators (normalised activations, q,
-            softmax numerators, attention output, SwiGLU product) is kept as a PAIR of
-            bf16 numbers hi + lo (about 16 significant bits).  This is the storage contract
-            of a SLED_BF16 model in the HIP library and the default for parity tests.
-  "bf16"    every one of those tensors is a single bf16 number: the usual all-bf16
-            inference pipeline, kept to measure what it would cost (at 8B shape its
-            logits sit 5e-2..1e-1 away from "exact", beyond the 2e-2 tolerance).
+Storage option (round_points).  All sums, the softmax, the residual stream and the
+logits are float64 in every mode.
+  "exact"     rounds nothing (weights and given context K/V are bf16 values already).
+  "kv_bf16"   the definition for a model whose K/V cache is bf16 (what parity of a
+              SLED_BF16 model is judged against): exact arithmetic, except that K and V
+              of the new tokens are rounded to bf16 (nearest, ties to even) when they
+              enter the cache -- the cache of such a model holds bf16 numbers, so every
+              later key/value read sees the rounded value.  Nothing else is rounded.
+Storage-contract studies, NOT used for parity ("parity unpinned" for these three; they
+exist to measure what an activation format would cost, see tests/test_oracle_forward.py
+for the bound that ties them to "kv_bf16"):
+  "bf16x2"    as "kv_bf16", and every other activation between operators (normalised
+              activations, q, softmax numerators, attention output, SwiGLU product) kept as a
+              PAIR of bf16 numbers hi + lo (about 16 significant bits)
+  "bf16"      ... as a single bf16 number
+  "fp16"      ... as a single IEEE half (11 significant bits)
 
 Pins (tests/test_oracle_*.py, no GPU): Hugging Face's LlamaForCausalLM in float64
 for the forward; closed forms, brute force over the uniforms, chi-square
@@ -72,15 +75,30 @@ def bf16x2_round(x: np.ndarray) -> np.ndarray:
     return hi + bf16_round(np.asarray(x, dtype=np.float64) - hi)
 
 
+def fp16_round(x: np.ndarray) -> np.ndarray:
+    """Nearest IEEE half of each element, returned as float64 (study mode only)."""
+    return np.asarray(x, dtype=np.float64).astype(np.float16).astype(np.float64)
+
+
+STUDY_MODES = ("bf16x2", "bf16", "fp16")
+
+
 def _rounder(round_points: str, cached: bool = False):
-    """Storage rounding of an activation.  `cached` marks K and V, which live in the bf16 cache as
-    single bf16 numbers in every bf16 mode; "bf16x2" keeps all other activations as bf16 pairs."""
+    """Storage rounding of an activation.  `cached` marks K and V of the new tokens, which enter a
+    bf16 cache as single bf16 numbers in every mode but "exact"; the other activations are rounded
+    only by the storage-contract study modes."""
     if round_points == "exact":
+        return lambda a: a
+    if cached:
+        return bf16_round
+    if round_points == "kv_bf16":
         return lambda a: a
     if round_points == "bf16":
         return bf16_round
     if round_points == "bf16x2":
-        return bf16_round if cached else bf16x2_round
+        return bf16x2_round
+    if round_points == "fp16":
+        return fp16_round
     raise ValueError(round_points)
 
 
@@ -116,11 +134,11 @@ def attention_rows(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int, grou
     Row j attends to keys 0 .. n_ctx + j: the whole context and the new keys up to
     itself.  Scores are scaled by 1/sqrt(D).  Returns [n, Hq, D].
 
-    round_points="bf16": the softmax numerators that multiply V are stored in bf16.  They
-    are taken relative to a power of two, p = 2^(t - M) with t the score in log2 units and
-    M the smallest whole number >= max t, because only then is their rounding independent
-    of the reference (scaling by 2^n commutes with rounding).  The denominator sums the
-    unrounded numerators."""
+    Storage-contract study modes only: the softmax numerators that multiply V are stored
+    rounded.  They are taken relative to a power of two, p = 2^(t - M) with t the score in
+    log2 units and M the smallest whole number >= max t, because only then is their rounding
+    independent of the reference (scaling by 2^n commutes with rounding).  The denominator
+    sums the unrounded numerators."""
     n, Hq, D = q.shape
     out = np.empty_like(q)
     scale = 1.0 / math.sqrt(D)
@@ -129,7 +147,7 @@ def attention_rows(q: np.ndarray, K: np.ndarray, V: np.ndarray, n_ctx: int, grou
         for j in range(n):
             m = n_ctx + j + 1
             s = (K[:m, g, :] @ q[j, h, :]) * scale
-            if round_points == "exact":
+            if round_points not in STUDY_MODES:
                 p = np.exp(s - s.max())
                 out[j, h, :] = (p @ V[:m, g, :]) / p.sum()
             else:
@@ -296,16 +314,20 @@ def accept_sample(logits: np.ndarray, drafts: Sequence[int], q: np.ndarray, u_ac
     i.e. with probability min(1, p(d)/q(d)).  At the first rejection the emitted token is
     drawn by inverse CDF with u_smp from max(0, p - q[j]) normalised (from p itself if that
     residual has no mass); if nothing is rejected a bonus token is drawn from row k.
+    A draft id outside [0, V) has target probability 0 and is rejected where it stands.
     margin_acc: smallest |u q - p| / p over the tests taken; margin_cdf: see inverse_cdf."""
     k = len(drafts)
+    V = logits.shape[1]
     margin_acc = math.inf
     for j in range(k):
         p = softmax64(logits[j], temperature)
         d = int(drafts[j])
-        lhs = float(u_acc[j]) * float(q[j, d])
-        pd = float(p[d])
-        margin_acc = min(margin_acc, abs(lhs - pd) / max(pd, 1e-300))
-        if not (lhs <= pd):
+        inside = 0 <= d < V
+        if inside:
+            lhs = float(u_acc[j]) * float(q[j, d])
+            pd = float(p[d])
+            margin_acc = min(margin_acc, abs(lhs - pd) / max(pd, 1e-300))
+        if not inside or not (lhs <= pd):
             r = np.maximum(0.0, p - np.asarray(q[j], dtype=np.float64))
             if r.sum() <= 0.0:
                 r = p

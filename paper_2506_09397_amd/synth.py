@@ -137,14 +137,15 @@ class SynthWeights:
 
 
 class SynthWeightsW8(SynthWeights):
-    """The same model with 8-bit projection weights: W[n][k] = q[n][k] * scale[n], q an FP8 E4M3 number (the
-    encoding torch calls float8_e4m3fn) drawn as N(0, 16) rounded to FP8, scale[n] a bf16-representable value
-    around std / 16 (so that the product is exact in float32 and the matrix still has entries of standard
-    deviation about std).  Both the 8-bit numbers and the scales are inputs: nothing is quantised by the code
-    under test.  Embedding and gains as in SynthWeights.
+    """The same model with 8-bit projection weights: the stored numbers are one byte per weight (an OCP FP8 E4M3
+    code, the encoding torch calls float8_e4m3fn) and one scale per output row.  The bytes are drawn the way a
+    quantiser would produce them -- N(0, 16) rounded to the nearest FP8 number -- and the scales as
+    bf16-representable values around std / 16, so that the matrix the bytes stand for has entries of standard
+    deviation about std.  Bytes and scales are the *inputs* of both the HIP library and the CPU oracle; what they
+    mean (the float matrix) is decoded by each side on its own, never here.
 
-    tensor() / layer() / final() return the dequantised float32 matrices (exact), which is what a reference
-    implementation multiplies with; q() and scale() return what the 8-bit library path loads."""
+    q() returns the bytes, uint8 [out, in]; scale() the float32 row scales [out].  Embedding and gains as in
+    SynthWeights (tensor() serves only those)."""
 
     bits = 8
     MATRICES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "lm_head")
@@ -152,7 +153,7 @@ class SynthWeightsW8(SynthWeights):
     def q(self, name: str, layer: int = -1) -> torch.Tensor:
         out_f, in_f = self._dims()[name]
         z = torch.clamp(self._randn(name, layer, out_f, in_f) * 16.0, -240.0, 240.0)
-        return z.to(torch.float8_e4m3fn)
+        return z.to(torch.float8_e4m3fn).view(torch.uint8)   # the quantiser's rounding; only the bytes leave
 
     def scale(self, name: str, layer: int = -1) -> torch.Tensor:
         out_f, _ = self._dims()[name]
@@ -172,22 +173,29 @@ class SynthWeightsW8(SynthWeights):
 
     def tensor(self, name: str, layer: int = -1) -> torch.Tensor:
         if name in self.MATRICES:
-            return self.q(name, layer).to(torch.float32) * self.scale(name, layer)[:, None]
-        return super().tensor(name, layer)
+            raise TypeError(f"{name}: a low-bit matrix exists only as codes and scales (q(), scale()); "
+                            "what they mean is for the consumer to decode")
+        return SynthWeights.tensor(self, name, layer)
+
+    def layer(self, l: int):
+        raise TypeError("low-bit weights have no float layer(): use q() / scale() per matrix")
+
+    def final(self):
+        raise TypeError("low-bit weights have no float final(): use q() / scale() per matrix")
 
 
 class SynthWeightsW4(SynthWeightsW8):
-    """The same model with 4-bit projection weights in the MXFP4 arrangement: W[n][k] = fp4[n][k] * 2^(e[n][k // 32] - 127),
-    fp4 an E2M1 number (0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives), e one byte per row and block of 32 k.
-    The codes and exponents are drawn the way a quantiser would produce them from N(0, std) weights -- block
-    exponent from the block's largest magnitude, each weight rounded to the nearest E2M1 value -- but they are
-    inputs: tensor() returns the exact dequantised float32 matrix that the stored numbers mean.
+    """The same model with 4-bit projection weights in the microscaling arrangement: a 4-bit code per weight, two
+    per byte, and one scale byte per output row and block of 32 inputs.  Codes and scale bytes are drawn the way a
+    quantiser would produce them from an N(0, std) matrix -- the block's scale is the smallest power of two that
+    brings its largest magnitude within the code range (6), each scaled weight goes to the nearest of the eight
+    code magnitudes -- and, as for 8 bits, they are inputs: decoding them is the consumer's business.
 
-    q() returns the packed codes, uint8 [out, in / 2], even k in the low nibble; scale() the exponent bytes,
-    uint8 [out, in / 32]."""
+    q() returns the packed codes, uint8 [out, in / 2], even input index in the low nibble, bit 3 of a code the
+    sign; scale() the scale bytes (biased exponent, bias 127), uint8 [out, in / 32]."""
 
     bits = 4
-    _E2M1 = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)
+    _LEVELS = (0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0)   # quantiser's output levels, code = index (+ 8 if negative)
 
     def _codes(self, name: str, layer: int):
         out_f, in_f = self._dims()[name]
@@ -195,10 +203,10 @@ class SynthWeightsW4(SynthWeightsW8):
         blocks = w.view(out_f, in_f // 32, 32)
         amax = blocks.abs().amax(dim=2).clamp_min(1e-30)
         e = torch.ceil(torch.log2(amax / 6.0)).clamp(-100, 100)           # smallest power of two with amax / 2^e <= 6
-        x = blocks / torch.exp2(e)[:, :, None]
-        table = torch.tensor(self._E2M1, device=w.device, dtype=torch.float32)
-        mid = (table[1:] + table[:-1]) / 2
-        mag = torch.bucketize(x.abs().contiguous(), mid)                  # index of the nearest magnitude
+        x = torch.ldexp(blocks, (-e).to(torch.int32)[:, :, None])
+        levels = torch.tensor(self._LEVELS, device=w.device, dtype=torch.float32)
+        mid = (levels[1:] + levels[:-1]) / 2
+        mag = torch.bucketize(x.abs().contiguous(), mid)                  # index of the nearest level
         code = (mag + 8 * (x < 0)).to(torch.uint8).view(out_f, in_f)
         return code, (e + 127).to(torch.uint8)
 
@@ -208,14 +216,6 @@ class SynthWeightsW4(SynthWeightsW8):
 
     def scale(self, name: str, layer: int = -1) -> torch.Tensor:
         return self._codes(name, layer)[1].contiguous()
-
-    def tensor(self, name: str, layer: int = -1) -> torch.Tensor:
-        if name in self.MATRICES:
-            code, e = self._codes(name, layer)
-            table = torch.tensor(self._E2M1 + tuple(-v for v in self._E2M1), device=code.device, dtype=torch.float32)
-            val = table[code.long()]
-            return (val.view(code.shape[0], -1, 32) * torch.exp2(e.to(torch.float32) - 127.0)[:, :, None]).view(code.shape)
-        return SynthWeights.tensor(self, name, layer)
 
 
 def as_f64(t: torch.Tensor) -> np.ndarray:

@@ -1,5 +1,5 @@
 """Models with 8-bit and 4-bit projection weights (weight-only quantisation, the 8- and 4-bit points of the
-bit-width sweep of Sec. 5): the library loads FP8 E4M3 bytes and their per-row scales, or FP4 E2M1 codes and
+bit-width sweep of Sec. 4.3): the library loads FP8 E4M3 bytes and their per-row scales, or FP4 E2M1 codes and
 their block exponents; the oracle multiplies with the dequantised matrices in float64.  Same storage contract
 for activations, same tolerance as for bf16 weights."""
 import numpy as np

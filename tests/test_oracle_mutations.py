@@ -85,6 +85,35 @@ attn_head_interleaved = _attention_variant(ok_scale, ok_keys, lambda h, group, H
 for _n in ("attn_unscaled", "attn_off_by_one", "attn_no_causal", "attn_head_interleaved"):
     globals()[_n].__name__ = _n
 
+def _layer_rows_variant(round_q, round_v, round_before_attention):
+    """layer_rows of the bf16-cache definition with the cache rounding misplaced."""
+    def layer_rows(model, W, h, positions, K_ctx, V_ctx):
+        cache_round = O.bf16_round if model.round_points != "exact" else (lambda a: a)
+        n = h.shape[0]
+        Hq, Hkv, D = model.n_q_heads, model.n_kv_heads, model.head_dim
+        x = O.rmsnorm(h, W["g_attn"], model.rms_eps)
+        q = O.rope((x @ W["wq"].T).reshape(n, Hq, D), positions, model.rope_theta)
+        k = O.rope((x @ W["wk"].T).reshape(n, Hkv, D), positions, model.rope_theta)
+        v = (x @ W["wv"].T).reshape(n, Hkv, D)
+        if round_q:
+            q = cache_round(q)
+        k_st, v_st = cache_round(k), (cache_round(v) if round_v else v)
+        k_at, v_at = (k_st, v_st) if round_before_attention else (k, v)
+        o = O.attention_rows(q, np.concatenate([K_ctx, k_at]), np.concatenate([V_ctx, v_at]), K_ctx.shape[0], model.group,
+                             model.round_points).reshape(n, Hq * D)
+        h = h + o @ W["wo"].T
+        x = O.rmsnorm(h, W["g_mlp"], model.rms_eps)
+        h = h + (O.silu(x @ W["wg"].T) * (x @ W["wu"].T)) @ W["wd"].T
+        return h, k_st, v_st
+    return layer_rows
+
+
+cache_round_after_attention = _layer_rows_variant(False, True, False)   # rows of one pass see unrounded new keys
+cache_forgets_v = _layer_rows_variant(False, False, True)               # V enters the cache unrounded
+cache_rounds_q_too = _layer_rows_variant(True, True, True)              # q rounded although it is never cached
+for _n in ("cache_round_after_attention", "cache_forgets_v", "cache_rounds_q_too"):
+    globals()[_n].__name__ = _n
+
 FORWARD_PINS = [
     lambda: TF.test_prefill_matches_hf_llama(TF.SMALL),
     TF.test_cached_verify_matches_hf_llama_with_cache,
@@ -94,6 +123,7 @@ FORWARD_PINS = [
     TF.test_attention_single_query_textbook,
     TF.test_rope_closed_forms,
     TF.test_rmsnorm_and_silu_closed_forms,
+    TF.test_kv_bf16_rounds_what_enters_the_cache_and_nothing_else,
 ]
 
 
@@ -102,6 +132,7 @@ FORWARD_MUTANTS = [
     ("rmsnorm", rmsnorm_no_eps), ("rmsnorm", rmsnorm_subtract_mean), ("silu", silu_as_sigmoid),
     ("attention_rows", attn_unscaled), ("attention_rows", attn_off_by_one), ("attention_rows", attn_no_causal),
     ("attention_rows", attn_head_interleaved),
+    ("layer_rows", cache_round_after_attention), ("layer_rows", cache_forgets_v), ("layer_rows", cache_rounds_q_too),
 ]
 
 
