@@ -204,6 +204,8 @@ __device__ inline Decision decide_request(int mode, int i, const KPack& kp, int 
             const int d = tokens[row0 + j + 1];
             if (mode == SLED_GREEDY) {
                 fail = (d != amax);
+            } else if (d < 0 || d >= V) {
+                fail = true;  // a draft outside the vocabulary has no target probability: rejected where it stands
             } else {
                 const double zd = (double)logits[(size_t)(row0 + j) * V + d];
                 const double pd = exp((zd - (double)m) * (double)inv_tau) / S;

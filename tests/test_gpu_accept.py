@@ -190,6 +190,32 @@ def test_sparse_token_outside_its_row_is_accepted_and_errors():
         sled.sled_accept_sparse(k, vocab, 0.0, case.logits, case.tokens, ids, probs, case.u_acc, case.u_smp, o, o.clone(), ws)
 
 
+@pytest.mark.parametrize("sparse", [False, True])
+def test_draft_outside_the_vocabulary_is_rejected_not_read(sparse):
+    """Draft ids come from the devices: one outside [0, V) ends the accepted prefix at its position (dense and
+    sparse q, and greedy), and is never used as an index."""
+    vocab, k = 2048, [4, 3, 5, 2]
+    if sparse:
+        case, ids, probs = _sparse_case(k, vocab, 16, 0.0, seed=11)
+    else:
+        case = synth.accept_case(k, vocab, 0.0, seed=11, device="cuda")      # q == p: every in-vocabulary draft passes
+    case.u_acc.zero_()                                                       # ... and so does every draft of a truncated q
+    bad = {0: (2, -1), 1: (0, vocab), 2: (4, 2**31 - 1), 3: (1, -(2**31))}     # request -> (draft index, bad id)
+    off = 0
+    for i, ki in enumerate(k):
+        j, v = bad[i]
+        case.tokens[off + 1 + j] = v
+        off += ki + 1
+    a, t = _run_sparse(case, vocab, ids, probs) if sparse else run_accept_gpu(sled.SAMPLE, case, vocab)
+    want = oracle_accept(sled.SAMPLE, case)
+    assert [w["accept_len"] for w in want] == [bad[i][0] for i in range(len(k))]
+    assert compare_accept(sled.SAMPLE, k, a, t, want) <= 1
+    assert [int(x) for x in a] == [bad[i][0] for i in range(len(k))]
+    g, tg = run_accept_gpu(sled.GREEDY, case, vocab)
+    wg = oracle_accept(sled.GREEDY, case)
+    assert compare_accept(sled.GREEDY, k, g, tg, wg) == 0 and all(int(g[i]) <= bad[i][0] for i in range(len(k)))
+
+
 def test_accept_argument_errors():
     vocab, k = 1024, [2, 2]
     case = synth.accept_case(k, vocab, 1.0, seed=1, device="cuda")

@@ -210,6 +210,25 @@ def test_sampling_invariants():
     assert O.accept_sample(z, [4], q0, [0.9999], 0.3)["accept_len"] == 1
 
 
+def test_draft_outside_the_vocabulary_is_rejected_where_it_stands():
+    """A device may send any integer: an id outside [0, V) has no target probability, so the accepted prefix ends
+    there, whatever the uniforms, and the corrective token comes from that position's residual (Eq. 1)."""
+    rng = np.random.default_rng(21)
+    z, p = _random_dists(rng, 4, 12)
+    _, q = _random_dists(rng, 3, 12)
+    good = [int(np.argmax(p[0])), int(np.argmax(p[1])), int(np.argmax(p[2]))]
+    for bad in (-1, 12, 10**6, -(2**31)):
+        for pos in range(3):
+            drafts = list(good)
+            drafts[pos] = bad
+            r = O.accept_sample(z, drafts, q, [0.0] * 3, 0.37)     # u = 0 would accept every in-vocabulary draft
+            assert r["accept_len"] == pos and 0 <= r["out_token"] < 12
+            want, _ = O.inverse_cdf(np.maximum(0.0, p[pos] - q[pos]), 0.37)
+            assert r["out_token"] == want
+            g = O.accept_greedy(z, drafts)
+            assert g["accept_len"] <= pos
+
+
 def test_temperature_is_logit_scaling():
     rng = np.random.default_rng(8)
     z, _ = _random_dists(rng, 4, 10)
