@@ -8,8 +8,8 @@
  * Sec. 3.4).  This library is that step and nothing else:
  *
  *   sled_verify_batch   target logits for a ragged batch of requests, each scored on
- *                       top of its own cached context (Sec. 3.1 "one single
- *                       forwarding"; Sec. 3.4 batching of heterogeneous devices)
+ *                       top of its own cached context (Sec. 3.1: all drafts in a single
+ *                       forward pass; Sec. 3.4 batching of heterogeneous devices)
  *   sled_accept         accepted-prefix length and one corrective / bonus token per
  *                       request (Eq. 1 and the resampling rule of Sec. 3.1; the
  *                       feedback message of Sec. 3.2)
@@ -114,7 +114,7 @@ SLED_API int sled_model_load(sled_model* m, int tensor_id, int layer, const void
 /* bits = 8: the projection matrices (WQ .. WDOWN, LM_HEAD) are stored as 8-bit floats -- FP8 E4M3 in the OCP
  * encoding, which gfx950 widens to bf16 in hardware -- with one float32 scale per output row,
  * W[n][k] = fp8[n][k] * scale[n]: weight-only quantisation, the 8-bit point of the paper's bit-width sweep
- * (Sec. 5).  Activations, K/V cache and arithmetic stay as in a bf16 model (an FP8 value is exact in bf16; the
+ * (Sec. 4.3).  Activations, K/V cache and arithmetic stay as in a bf16 model (an FP8 value is exact in bf16; the
  * scale is applied to the float32 accumulator), so the weight stream halves and nothing else changes.
  * Call it right after sled_model_create, before any sled_model_load: the matrices' device storage is given back and
  * allocated anew at bits/8 bytes per weight (a 70B-shaped model takes 141, 71 or 37 GB), so whatever was loaded
@@ -147,14 +147,22 @@ SLED_API int sled_model_destroy(sled_model* m);
  * reading of "each request carries its context".  K is stored already rotated. */
 SLED_API int sled_kvpool_create(const sled_model* m, int64_t n_pages, int max_requests, sled_kvpool** out);
 
-/* Opens an empty request (L = 0) and returns its id.  Errors: SLED_ENOMEM. */
+/* Opens an empty request (L = 0) and returns its id.  Host bookkeeping only: nothing is enqueued and nothing is
+ * waited for (the device-side length of the slot is reset by the first append, verify or prefill that names the
+ * request, on that call's stream).  Errors: SLED_ENOMEM. */
 SLED_API int sled_kvpool_open(sled_kvpool* p, int* req_id /*host out*/);
 
-/* Returns the request's pages to the pool.  Errors: SLED_EINVAL (unknown id). */
+/* Returns the request's pages to the pool.  Host bookkeeping only, no wait: the pages may be handed to another
+ * request at once, which is safe because all calls on one pool are issued on one stream (or ordered by the caller),
+ * so whatever still reads the pages runs before whatever writes them next.  A verify of this request that has
+ * not been committed is dropped.  Errors: SLED_EINVAL (unknown id). */
 SLED_API int sled_kvpool_close(sled_kvpool* p, int req_id);
 
-/* Waits for `stream`, then writes the exact committed context length of each listed request
- * to lens (host out, B ints) and tightens the host-side page accounting to it. */
+/* The one call of the pool that waits: synchronises `stream`, then writes the exact committed context length of
+ * each listed request to lens (host out, B ints) and tightens the host-side page accounting to it.  Rows staged by
+ * a verify that is not committed yet keep their pages, so the call may come between a verify and its commit.
+ * No other call needs it: a commit sends the exact lengths back to the host behind itself, and a later call on
+ * the pool picks them up, once they have arrived, without waiting. */
 SLED_API int sled_kvpool_lengths(sled_kvpool* p, int B, const int* req_ids /*host*/, int* lens /*host out*/, void* stream);
 
 SLED_API int sled_kvpool_destroy(sled_kvpool* p);
@@ -170,7 +178,10 @@ SLED_API int sled_kvpool_destroy(sled_kvpool* p);
  *     last sled_verify_batch staged for these requests: the pending token and the first
  *     accept_len[i] drafts become context, L_i += accept_len[i] + 1.  No data moves; the
  *     rejected tokens' slots are overwritten by the next verify.  n_tokens, k_src, v_src
- *     are ignored.  Requests must be the ones of the last verify (SLED_ESTATE otherwise).
+ *     are ignored.  The requests must be among those of the last verify, each at most once
+ *     (SLED_ESTATE otherwise); they may be committed in several calls, accept_len[i] always belonging
+ *     to req_ids[i] of the call at hand.  Page accounting on the host assumes every staged row was
+ *     accepted until the exact lengths, copied back asynchronously behind the commit, have arrived.
  *
  * Errors: SLED_EINVAL, SLED_ENOMEM (no free page), SLED_ESTATE. */
 SLED_API int sled_kv_append(sled_kvpool* p, int B, const int* req_ids /*host*/, const int* n_tokens /*host*/,
@@ -213,7 +224,8 @@ SLED_API int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int* 
  *   workspace            dev scratch, 256-byte aligned; any size that sled_verify_workspace_bytes returns for
  *                        B_max >= 1 will do: the prompt is cut into slices of as many blocks of k_max + 1 rows
  *                        as the workspace holds (larger workspace, fewer and larger slices)
- * Rows that an earlier, uncommitted sled_verify_batch staged for the request are overwritten.
+ * Rows that an earlier, uncommitted sled_verify_batch staged for the request are overwritten (that request can then no
+ * longer be committed; the other requests of that verify can).
  * Errors: SLED_EINVAL, SLED_ENOMEM (no free page). */
 SLED_API int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tokens, const int32_t* tokens /*dev*/,
                  float* logits_last /*dev or NULL*/, void* workspace /*dev*/, size_t workspace_bytes, void* stream);

@@ -380,6 +380,12 @@ extern "C" int sled_kvpool_create(const sled_model* m, int64_t n_pages, int max_
         if ((e = hipEventCreateWithFlags(&p->slot[i].ev, hipEventDisableTiming)) != hipSuccess)
             return fail(SLED_EHIP, "hipEventCreate", e);
     }
+    for (int i = 0; i < sled_kvpool::READBACKS; i++) {
+        if ((e = hipHostMalloc(reinterpret_cast<void**>(&p->rb[i].host), max_requests * sizeof(int32_t), hipHostMallocDefault)) != hipSuccess)
+            return fail(SLED_ENOMEM, "hipHostMalloc(length read-back)", e);
+        if ((e = hipEventCreateWithFlags(&p->rb[i].ev, hipEventDisableTiming)) != hipSuccess)
+            return fail(SLED_EHIP, "hipEventCreate", e);
+    }
     if ((e = hipDeviceSynchronize()) != hipSuccess) return fail(SLED_EHIP, "hipDeviceSynchronize", e);
     p->reqs.resize(max_requests);
     p->free_pages.reserve(n_pages);
@@ -396,6 +402,10 @@ extern "C" int sled_kvpool_destroy(sled_kvpool* p) {
         if (p->slot[i].dev) (void)hipFree(p->slot[i].dev);
         if (p->slot[i].ev) (void)hipEventDestroy(p->slot[i].ev);
     }
+    for (int i = 0; i < sled_kvpool::READBACKS; i++) {
+        if (p->rb[i].host) (void)hipHostFree(p->rb[i].host);
+        if (p->rb[i].ev) (void)hipEventDestroy(p->rb[i].ev);
+    }
     if (p->k_pool) (void)hipFree(p->k_pool);
     if (p->v_pool) (void)hipFree(p->v_pool);
     if (p->len_dev) (void)hipFree(p->len_dev);
@@ -407,12 +417,14 @@ extern "C" int sled_kvpool_open(sled_kvpool* p, int* req_id) {
     if (!p || !req_id) SLED_FAIL(SLED_EINVAL, "sled_kvpool_open: null argument");
     for (int i = 0; i < p->max_requests; i++)
         if (!p->reqs[i].open) {
-            // a closed slot's device length may be stale: the first append or verify after opening
-            // needs L = 0, so reset it in stream order of the default stream, synchronously (rare call)
-            int32_t zero = 0;
-            SLED_HIP(hipMemcpy(p->len_dev + i, &zero, sizeof(zero), hipMemcpyHostToDevice));
+            // A closed slot's device-side length may be stale.  This call has no stream, so nothing is enqueued
+            // here: the first append, verify or prefill that names the request resets the length on its own stream
+            // before anything reads it (reset_fresh_lengths).
+            const uint32_t gen = p->reqs[i].gen + 1;
             p->reqs[i] = sled_request();
             p->reqs[i].open = true;
+            p->reqs[i].fresh = true;
+            p->reqs[i].gen = gen;
             *req_id = i;
             return SLED_OK;
         }
@@ -422,11 +434,76 @@ extern "C" int sled_kvpool_open(sled_kvpool* p, int* req_id) {
 extern "C" int sled_kvpool_close(sled_kvpool* p, int req_id) {
     if (!p || req_id < 0 || req_id >= p->max_requests || !p->reqs[req_id].open)
         SLED_FAIL(SLED_EINVAL, "sled_kvpool_close: request %d is not open", req_id);
-    // work that still reads these pages must have finished before they are handed out again
-    SLED_HIP(hipDeviceSynchronize());
+    // No wait: work that still reads these pages was enqueued earlier on the pool's stream, and whoever is handed
+    // the pages next writes them from a later call on that stream (calls on one pool share a stream or are ordered
+    // by the caller).
     for (int pg : p->reqs[req_id].pages) p->free_pages.push_back(pg);
+    const uint32_t gen = p->reqs[req_id].gen;
     p->reqs[req_id] = sled_request();
+    p->reqs[req_id].gen = gen;
     p->last_batch.erase(std::remove(p->last_batch.begin(), p->last_batch.end(), req_id), p->last_batch.end());
+    return SLED_OK;
+}
+
+// pages a request has to keep: its committed tokens (upper bound) and the rows a verify has staged behind them
+static void trim_pages(sled_kvpool* p, sled_request& rq) {
+    const int keep = ceil_div(rq.len_ub + std::max(rq.staged, 0), 16);
+    while ((int)rq.pages.size() > keep) {
+        p->free_pages.push_back(rq.pages.back());
+        rq.pages.pop_back();
+    }
+}
+
+// Applies every length read-back whose copy has completed (never waits): the exact length L of a request right after
+// some commit, plus whatever has been added to its bound since, is a tighter bound than the one kept so far.
+static void poll_readbacks(sled_kvpool* p) {
+    for (int n = 0; n < sled_kvpool::READBACKS; n++) {
+        sled_kvpool::readback& rb = p->rb[(p->rb_next + n) % sled_kvpool::READBACKS];   // oldest first
+        if (!rb.pending) continue;
+        if (hipEventQuery(rb.ev) != hipSuccess) {
+            (void)hipGetLastError();   // hipErrorNotReady is not an error
+            continue;
+        }
+        rb.pending = false;
+        for (size_t i = 0; i < rb.req.size(); i++) {
+            sled_request& rq = p->reqs[rb.req[i]];
+            if (!rq.open || rq.gen != rb.gen_at[i]) continue;
+            const int64_t ub = (int64_t)rb.host[rb.req[i]] + (rq.added - rb.added_at[i]);
+            if (ub < rq.len_ub) {
+                rq.len_ub = (int)ub;
+                trim_pages(p, rq);
+            }
+        }
+    }
+}
+
+// the device-side length of a request that has just been opened is reset here, on the first stream that names it
+static int reset_fresh_lengths(sled_kvpool* p, int B, const int* req_ids, hipStream_t st) {
+    for (int i = 0; i < B; i++) {
+        sled_request& rq = p->reqs[req_ids[i]];
+        if (!rq.fresh) continue;
+        int rc = sled_launch_fill_i32(p->len_dev + req_ids[i], 0, 1, st);
+        if (rc != SLED_OK) return rc;
+        rq.fresh = false;
+    }
+    return SLED_OK;
+}
+
+// after a commit: copy the lengths back behind it, to be looked at by a later call
+static int enqueue_readback(sled_kvpool* p, int B, const int* req_ids, hipStream_t st) {
+    sled_kvpool::readback& rb = p->rb[p->rb_next];
+    if (rb.pending) return SLED_OK;   // the ring is full of copies nobody has looked at yet: skip this one
+    SLED_HIP(hipMemcpyAsync(rb.host, p->len_dev, p->max_requests * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    SLED_HIP(hipEventRecord(rb.ev, st));
+    rb.req.assign(req_ids, req_ids + B);
+    rb.added_at.resize(B);
+    rb.gen_at.resize(B);
+    for (int i = 0; i < B; i++) {
+        rb.added_at[i] = p->reqs[req_ids[i]].added;
+        rb.gen_at[i] = p->reqs[req_ids[i]].gen;
+    }
+    rb.pending = true;
+    p->rb_next = (p->rb_next + 1) % sled_kvpool::READBACKS;
     return SLED_OK;
 }
 
@@ -460,17 +537,14 @@ extern "C" int sled_kvpool_lengths(sled_kvpool* p, int B, const int* req_ids, in
     if (rc != SLED_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     SLED_HIP(hipStreamSynchronize(st));
+    poll_readbacks(p);
     std::vector<int32_t> all(p->max_requests);
     SLED_HIP(hipMemcpy(all.data(), p->len_dev, all.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
     for (int i = 0; i < B; i++) {
         sled_request& rq = p->reqs[req_ids[i]];
-        lens[i] = all[req_ids[i]];
+        lens[i] = rq.fresh ? 0 : all[req_ids[i]];   // a request nothing has touched yet is empty whatever the slot held
         rq.len_ub = lens[i];
-        const int keep = ceil_div(rq.len_ub, 16);
-        while ((int)rq.pages.size() > keep) {
-            p->free_pages.push_back(rq.pages.back());
-            rq.pages.pop_back();
-        }
+        trim_pages(p, rq);   // rows staged by a verify that is not committed yet keep their pages
     }
     return SLED_OK;
 }
@@ -482,12 +556,13 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
     if (rc != SLED_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const sled_model* m = p->m;
+    poll_readbacks(p);
     if (accept_len) {
         // commit what the last verify staged
-        if ((int)p->last_batch.size() != B) SLED_FAIL(SLED_ESTATE, "sled_kv_append: batch differs from the last verify");
         for (int i = 0; i < B; i++)
-            if (p->last_batch[i] != req_ids[i] || p->reqs[req_ids[i]].staged < 0)
-                SLED_FAIL(SLED_ESTATE, "sled_kv_append: request %d has nothing staged", req_ids[i]);
+            if (std::find(p->last_batch.begin(), p->last_batch.end(), req_ids[i]) == p->last_batch.end() ||
+                p->reqs[req_ids[i]].staged < 0)
+                SLED_FAIL(SLED_ESTATE, "sled_kv_append: request %d has nothing staged by the last verify", req_ids[i]);
         sled_stage_slot* sl;
         if ((rc = stage_acquire(p, B, &sl)) != SLED_OK) return rc;
         for (int i = 0; i < B; i++) sl->host[i] = req_ids[i];
@@ -496,13 +571,16 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
         if ((rc = stage_release(sl, st)) != SLED_OK) return rc;
         for (int i = 0; i < B; i++) {
             sled_request& rq = p->reqs[req_ids[i]];
-            rq.len_ub += rq.staged;  // upper bound: every staged row may have been accepted
+            rq.len_ub += rq.staged;  // upper bound: every staged row may have been accepted ...
+            rq.added += rq.staged;
             rq.staged = -1;
+            p->last_batch.erase(std::remove(p->last_batch.begin(), p->last_batch.end(), req_ids[i]), p->last_batch.end());
         }
-        p->last_batch.clear();
-        return SLED_OK;
+        // ... and the exact lengths follow behind the commit, without anybody waiting for them
+        return enqueue_readback(p, B, req_ids, st);
     }
     if (!n_tokens || !k_src || !v_src) SLED_FAIL(SLED_EINVAL, "sled_kv_append: null argument");
+    if ((rc = reset_fresh_lengths(p, B, req_ids, st)) != SLED_OK) return rc;
     size_t need = 2 * (size_t)B;
     for (int i = 0; i < B; i++) {
         if (n_tokens[i] < 0 || (n_tokens[i] > 0 && (!k_src[i] || !v_src[i])))
@@ -531,7 +609,8 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
     for (int i = 0; i < B; i++) {
         sled_request& rq = p->reqs[req_ids[i]];
         rq.len_ub += n_tokens[i];
-        rq.staged = -1;
+        rq.added += n_tokens[i];
+        rq.staged = -1;   // rows staged by an uncommitted verify are overwritten: nothing of this request is left to commit
     }
     return SLED_OK;
 }
@@ -815,9 +894,14 @@ extern "C" int sled_verify_batch(sled_model* m, sled_kvpool* p, int B, const int
         if (k[i] < 0 || k[i] > m->s.k_max) SLED_FAIL(SLED_EINVAL, "sled_verify_batch: k[%d] = %d outside [0, %d]", i, k[i], m->s.k_max);
         ent[i] = step_entry{req_ids[i], 0, k[i] + 1};
     }
+    poll_readbacks(p);
+    if ((rc = reset_fresh_lengths(p, B, req_ids, static_cast<hipStream_t>(stream))) != SLED_OK) return rc;
     rc = run_forward(m, p, ent, tokens, logits, -1, nullptr, workspace, workspace_bytes, static_cast<hipStream_t>(stream),
                      "sled_verify_batch");
     if (rc != SLED_OK) return rc;
+    // what an earlier verify staged for requests that are not in this batch stays staged, but only the last batch
+    // can be committed
+    for (int r : p->last_batch) p->reqs[r].staged = -1;
     for (int i = 0; i < B; i++) p->reqs[req_ids[i]].staged = k[i] + 1;
     p->last_batch.assign(req_ids, req_ids + B);
     return SLED_OK;
@@ -847,8 +931,11 @@ extern "C" int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tok
     }
     const int blocks_per_step = lo;
     sled_request& rq = p->reqs[req_id];
-    rq.staged = -1;  // rows staged by an earlier verify are overwritten
-    p->last_batch.clear();
+    poll_readbacks(p);
+    if ((rc = reset_fresh_lengths(p, 1, &req_id, st)) != SLED_OK) return rc;
+    // rows staged for THIS request by an earlier verify are overwritten, so it has nothing left to commit; the other
+    // requests of that verify keep their staged rows and their commit stays valid
+    rq.staged = -1;
     for (int done = 0; done < n_tokens;) {
         const int rows = std::min(n_tokens - done, blocks_per_step * per);
         std::vector<step_entry> ent;
@@ -866,6 +953,7 @@ extern "C" int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tok
         if ((rc = sled_launch_len_add(p->len_dev, sl->dev, sl->dev + 1, nullptr, 1, st)) != SLED_OK) return rc;
         if ((rc = stage_release(sl, st)) != SLED_OK) return rc;
         rq.len_ub += rows;
+        rq.added += rows;
         done += rows;
     }
     return SLED_OK;

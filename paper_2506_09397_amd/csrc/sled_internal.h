@@ -149,8 +149,11 @@ struct sled_model {
 
 struct sled_request {
     bool open = false;
+    bool fresh = false;        // opened and not used yet: its device-side length is reset by the first call that has a stream
     int len_ub = 0;            // host-side upper bound of the committed length
     int staged = -1;           // k+1 of the last verify (rows staged), -1 if none
+    int64_t added = 0;         // everything ever added to len_ub (lets a late read-back of the exact length be applied)
+    uint32_t gen = 0;          // incarnation of the slot: a read-back taken for an earlier one is dropped
     std::vector<int> pages;
 };
 
@@ -176,6 +179,20 @@ struct sled_kvpool {
     stage_slot slot[RING];
     size_t stage_cap;          // ints per slot
     int stage_next;
+    // Exact committed lengths come back asynchronously after a commit: a copy of len_dev into pinned memory and an
+    // event behind it.  A later call that finds the event complete tightens the host-side bounds (and gives pages
+    // back) without ever waiting.
+    static const int READBACKS = 8;
+    struct readback {
+        int32_t* host = nullptr;          // pinned, max_requests ints
+        hipEvent_t ev = nullptr;
+        bool pending = false;
+        std::vector<int> req;             // requests the commit touched
+        std::vector<int64_t> added_at;    // their `added` right after that commit
+        std::vector<uint32_t> gen_at;
+    };
+    readback rb[READBACKS];
+    int rb_next = 0;
 };
 
 // per-step metadata blob, device side (offsets in int32 units from the blob start)

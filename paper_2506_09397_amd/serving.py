@@ -136,8 +136,8 @@ class Server:
         a, t = self.v.accept(sled.GREEDY, k, logits, tokens)
         self.v.commit(reqs, a)
         a_h, t_h = a.cpu().tolist(), t.cpu().tolist()     # the answers leave the GPU here
-        # the pool reserves pages for every staged row until it is told the committed lengths
-        self.v.lengths(reqs)
+        # (the pool reserves pages for every staged row only until the exact lengths, which follow the commit back
+        # to the host on their own, are picked up by its next call: nothing here waits for them)
         out = []
         for p, ai, ti in zip(batch, a_h, t_h):
             r = Response(p.device, p.round_no, int(ai), int(ti))
