@@ -1,8 +1,8 @@
 """Condense rocprofv3 CSV output of a bench.py run into the short text tables kept under profiles/.
 
-    python -m paper_2506_09397_amd.profsum stats  <dir with *_kernel_stats.csv>
-    python -m paper_2506_09397_amd.profsum traffic <FETCH_SIZE dir> <WRITE_SIZE dir>
-    python -m paper_2506_09397_amd.profsum mfma    <dir of a --pmc SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE --kernel-trace run>
+    python bench_profsum.py stats  <dir with *_kernel_stats.csv>
+    python bench_profsum.py traffic <FETCH_SIZE dir> <WRITE_SIZE dir>
+    python bench_profsum.py mfma    <dir of a --pmc SQ_VALU_MFMA_BUSY_CYCLES GRBM_GUI_ACTIVE --kernel-trace run>
 
 `traffic` scales the FETCH_SIZE / WRITE_SIZE counters (KiB per dispatch as rocprofv3 reports them) by
 what the same counters read for the 1 GiB device-to-device copy that `bench.py --copy-calibration`

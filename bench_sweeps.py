@@ -1,12 +1,12 @@
 """Measurement sweeps around the batched verify step (one MI355X, synthetic inputs, through the C ABI).
 
-    python -m paper_2506_09397_amd.sweeps batch     # step latency vs batch size and speculative length
-    python -m paper_2506_09397_amd.sweeps rows [llama70b] [sizes]   # projection time vs number of packed rows (MFMA regime)
-    python -m paper_2506_09397_amd.sweeps prefill   # prompt ingest (sled_prefill): prompt length x rows per slice
-    python -m paper_2506_09397_amd.sweeps weights   # verify step with bf16, FP8 and FP4 weights, by rows
+    python bench_sweeps.py batch     # step latency vs batch size and speculative length
+    python bench_sweeps.py rows [llama70b] [sizes]   # projection time vs number of packed rows (MFMA regime)
+    python bench_sweeps.py prefill   # prompt ingest (sled_prefill): prompt length x rows per slice
+    python bench_sweeps.py weights   # verify step with bf16, FP8 and FP4 weights, by rows
 
-`batch` is the one-GPU analogue of the paper's throughput-versus-batch-size curve (Sec. 5) and of its
-study of the speculative length: Llama-3-8B shape, contexts uniform in [512, 2048], every request
+`batch` is the one-GPU analogue of the paper's throughput-versus-batch-size curve (Sec. 4.1) and of its
+study of the speculative length (Sec. 4.2): Llama-3-8B shape, contexts uniform in [512, 2048], every request
 with the same k.  `rows` packs many short requests (16 context tokens, k = 8) so that attention is
 negligible and reads the time of the projection kernels from the library's timing hooks:
 useful FLOP = 2 * rows * streamed parameters.
@@ -19,8 +19,11 @@ import time
 import numpy as np
 import torch
 
-from . import sled, synth
-from .runtime import Verifier
+import os
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from paper_2506_09397_amd import sled, synth  # noqa: E402
+from paper_2506_09397_amd.runtime import Verifier  # noqa: E402
 
 MFMA_PEAK_BF16 = 2.5e15
 

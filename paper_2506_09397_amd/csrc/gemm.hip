@@ -537,30 +537,6 @@ int launch_epi(int epi, const gemm_args& a) {
     }
 }
 
-// tuning aid: SLED_GEMM_TUNE="N:K:split;..." overrides the number of K slices of the projections with
-// those N and K (read once)
-struct tune_entry {
-    int N, K, split;
-};
-const std::vector<tune_entry>& tune_table() {
-    static std::vector<tune_entry> t = [] {
-        std::vector<tune_entry> v;
-        const char* e = getenv("SLED_GEMM_TUNE");
-        if (!e) return v;
-        std::string s(e);
-        size_t pos = 0;
-        while (pos < s.size()) {
-            size_t end = s.find(';', pos);
-            if (end == std::string::npos) end = s.size();
-            tune_entry te{0, 0, 0};
-            if (sscanf(s.substr(pos, end - pos).c_str(), "%d:%d:%d", &te.N, &te.K, &te.split) == 3) v.push_back(te);
-            pos = end + 1;
-        }
-        return v;
-    }();
-    return t;
-}
-
 }  // namespace
 
 // Number of K slices for a projection of N columns over K.  More slices mean more workgroups (the
@@ -570,8 +546,6 @@ sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs
     sled_gemm_plan p{1};
     if (m->s.dtype != SLED_BF16) return p;
     auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * NARROW_KG * NBUF) == 0; };  // legal for both shapes
-    for (const auto& te : tune_table())
-        if (te.N == N && te.K == K && legal(te.split) && (!needs_full_k || te.split == 1)) return sled_gemm_plan{te.split};
     const int n_wg = (N + NARROW_COLS - 1) / NARROW_COLS;
     if (!needs_full_k)
         while (n_wg * p.split < 160 && legal(p.split * 2)) p.split *= 2;
