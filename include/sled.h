@@ -255,6 +255,19 @@ SLED_API int sled_accept(int mode, int B, const int* k /*host*/, int vocab, floa
                 int32_t* accept_len /*dev out*/, int32_t* out_token /*dev out*/,
                 void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
+/* sled_accept for callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: same arguments and results as sled_accept without the workspace.  The row
+ * statistics go to a fixed 256 KiB array of device memory inside the library (one copy per GPU, held until the process
+ * ends); the call allocates nothing and frees nothing.  Limit: T <= 16384 packed rows (the array holds 16384 row-segment
+ * statistics, and T rows are scanned in at most ceil(8192 / T) segments each); beyond it the call fails with
+ * SLED_EINVAL and sled_accept is the one to use.  All calls
+ * on one GPU share that array and it keeps the last call's contents (nothing in it needs clearing): calls that
+ * overlap on one GPU -- two streams, two threads -- race; issue them on one stream.  Errors: SLED_EINVAL, SLED_EHIP. */
+SLED_API int sled_accept_static(int mode, int B, const int* k /*host*/, int vocab, float temperature,
+                       const float* logits /*dev*/, const int32_t* tokens /*dev*/,
+                       const float* draft_q /*dev*/, const float* u_acc /*dev*/, const float* u_smp /*dev*/,
+                       int32_t* accept_len /*dev out*/, int32_t* out_token /*dev out*/, void* stream);
+
 /* sled_accept in sampling mode with the draft distributions given sparsely: draft j's distribution q_j is
  * q_probs[j][i] on token q_ids[j][i] (i < q_m) and zero elsewhere.  This is exact, not an approximation, when
  * the device drew its draft from that very distribution -- e.g. from its top-q_m tokens renormalised -- because

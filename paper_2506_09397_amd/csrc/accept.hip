@@ -510,6 +510,60 @@ int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, flo
     return SLED_OK;
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// sled_accept for callers that cannot allocate: the row statistics live in a fixed array of device memory that is
+// part of the library's code object (one copy per GPU, held until the process ends) instead of a caller's workspace.
+constexpr size_t SLED_STATIC_STATS = 16384;   // row-segment statistics: 256 KiB
+static __device__ __align__(256) unsigned char scratch[SLED_STATIC_STATS * sizeof(RowStat)];
+
+namespace {
+constexpr int SLED_MAX_DEVICES = 64;
+void* g_scratch_ptr[SLED_MAX_DEVICES];   // device address of `scratch` on each GPU (the array's name is no address on the host)
+
+// the address of this GPU's copy of the array, looked up once per device with that device current
+int static_scratch(void** out) {
+    int dev = -1;
+    SLED_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SLED_MAX_DEVICES) SLED_FAIL(SLED_EINVAL, "sled_accept_static: device %d unsupported", dev);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        SLED_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) SLED_FAIL(SLED_EHIP, "sled_accept_static: no device address for the static scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SLED_OK;
+}
+}  // namespace
+
+extern "C" int sled_accept_static(int mode, int B, const int* k, int vocab, float temperature, const float* logits,
+                                  const int32_t* tokens, const float* draft_q, const float* u_acc, const float* u_smp,
+                                  int32_t* accept_len, int32_t* out_token, void* stream) {
+    if (!k || !logits || !tokens || !accept_len || !out_token) SLED_FAIL(SLED_EINVAL, "sled_accept_static: null argument");
+    if (mode != SLED_GREEDY && mode != SLED_SAMPLE) SLED_FAIL(SLED_EINVAL, "sled_accept_static: unknown mode %d", mode);
+    if (B < 1 || B > 1024) SLED_FAIL(SLED_EINVAL, "sled_accept_static: batch size %d outside [1, 1024]", B);
+    if (vocab < 2 || vocab > 2000000) SLED_FAIL(SLED_EINVAL, "sled_accept_static: vocab %d unsupported", vocab);
+    if (!(temperature > 0.f)) SLED_FAIL(SLED_EINVAL, "sled_accept_static: temperature must be positive");
+    int T = 0, nd = 0;
+    for (int i = 0; i < B; i++) {
+        if (k[i] < 0 || k[i] > 255) SLED_FAIL(SLED_EINVAL, "sled_accept_static: k[%d] = %d outside [0, 255]", i, k[i]);
+        T += k[i] + 1;
+        nd += k[i];
+    }
+    if (mode == SLED_SAMPLE && (!u_smp || (nd > 0 && (!draft_q || !u_acc))))
+        SLED_FAIL(SLED_EINVAL, "sled_accept_static: sampling needs draft_q, u_acc and u_smp");
+    const size_t need = (size_t)T * sled_accept_pick_split(T, vocab);
+    if (need > SLED_STATIC_STATS)
+        SLED_FAIL(SLED_EINVAL, "sled_accept_static: %d rows in %d segments need %zu statistics, the static scratch holds %zu; use sled_accept",
+                  T, sled_accept_pick_split(T, vocab), need, SLED_STATIC_STATS);
+    void* ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc != SLED_OK) return rc;
+    // nothing in the array has to start at zero: the row scan writes every statistic the finish kernel reads
+    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, nullptr, nullptr, 0, u_acc, u_smp,
+                              accept_len, out_token, ws, static_cast<hipStream_t>(stream));
+}
+
 int sled_launch_row_confidence(int T, int vocab, float temperature, const float* logits, float* conf, int32_t* top, void* ws,
                                hipStream_t st) {
     const int n_split = sled_accept_pick_split(T, vocab);

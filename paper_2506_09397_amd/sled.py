@@ -32,7 +32,7 @@ EXPORTS = [
     "sled_model_set_weight_bits",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
     "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
-    "sled_accept_workspace_bytes", "sled_accept", "sled_accept_sparse", "sled_row_confidence", "sled_profile_enable", "sled_profile_read",
+    "sled_accept_workspace_bytes", "sled_accept", "sled_accept_static", "sled_accept_sparse", "sled_row_confidence", "sled_profile_enable", "sled_profile_read",
     "sled_strerror", "sled_last_error",
 ]
 PROF_PROJ, PROF_ATTN, PROF_ROWS, PROF_N = 0, 1, 2, 3
@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
     L.sled_accept_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int]
     L.sled_accept_workspace_bytes.restype = C.c_size_t
     L.sled_accept.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.sled_accept_static.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp]
     L.sled_accept_sparse.argtypes = [C.c_int, ip, C.c_int, C.c_float, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_row_confidence.argtypes = [C.c_int, C.c_int, C.c_float, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_profile_enable.argtypes = [vp, C.c_int]
@@ -203,6 +204,15 @@ def sled_accept(mode: int, k: Sequence[int], vocab: int, temperature: float, log
     _check(lib().sled_accept(mode, len(k), _ints(k), vocab, float(temperature), _ptr(logits), _ptr(tokens), _ptr(draft_q),
                              _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token), _ptr(workspace),
                              workspace.numel() * workspace.element_size(), _stream()))
+
+
+def sled_accept_static(mode: int, k: Sequence[int], vocab: int, temperature: float, logits: torch.Tensor, tokens: torch.Tensor,
+                       draft_q: Optional[torch.Tensor], u_acc: Optional[torch.Tensor], u_smp: Optional[torch.Tensor],
+                       accept_len: torch.Tensor, out_token: torch.Tensor) -> None:
+    assert logits.dtype == torch.float32 and tokens.dtype == torch.int32
+    assert accept_len.dtype == torch.int32 and out_token.dtype == torch.int32
+    _check(lib().sled_accept_static(mode, len(k), _ints(k), vocab, float(temperature), _ptr(logits), _ptr(tokens),
+                                    _ptr(draft_q), _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token), _stream()))
 
 
 def sled_accept_sparse(k: Sequence[int], vocab: int, temperature: float, logits: torch.Tensor, tokens: torch.Tensor,
