@@ -619,7 +619,7 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
 namespace {
 
 struct ws_plan {
-    size_t h, xa, xo, xf, q, x1, partial, cs, kvslot, part_o, part_ml, arrive, total, T_alloc;
+    size_t h, xa, xo, xf, q, x1, partial, cs, kvslot, plan, part_o, part_ml, arrive, total, T_alloc;
 };
 
 // Attention work list.  A work item is a run of pages of one (request, kv head), processed by one
@@ -676,6 +676,7 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     w.partial = take(part * sizeof(float));
     w.cs = take((size_t)T * s.head_dim * sizeof(float));
     w.kvslot = take((size_t)T * sizeof(int32_t));
+    w.plan = take((size_t)(n_work + 1) * 12 * sizeof(int32_t));   // one record per attention work item
     w.part_o = take((size_t)n_work * QT * 16 * 128 * sizeof(float));
     w.part_ml = take((size_t)n_work * 2 * QT * 16 * sizeof(float));
     w.arrive = take((size_t)(n_work + 1) * sizeof(int32_t));  // one counter per (request, kv head): at most n_work
@@ -817,6 +818,7 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     float* partial = reinterpret_cast<float*>(ws + wp.partial);
     float* cs = reinterpret_cast<float*>(ws + wp.cs);
     int32_t* kvslot = reinterpret_cast<int32_t*>(ws + wp.kvslot);
+    int32_t* plan = reinterpret_cast<int32_t*>(ws + wp.plan);
     float* part_o = reinterpret_cast<float*>(ws + wp.part_o);
     float* part_ml = reinterpret_cast<float*>(ws + wp.part_ml);
     int32_t* arrive = reinterpret_cast<int32_t*>(ws + wp.arrive);
@@ -832,6 +834,19 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     // kernel reduces the K slices and applies it
     sled_gemm_plan g_gu = sled_gemm_make_plan(m, 2 * F, d, false);
     const bool gu_fused = bf && g_gu.split == 1;
+    // The attention kernel takes the QKV projection's partial sums itself (sum over K slices, rotary, K/V write) when
+    // every block is a request of its own at offset 0, i.e. in a verification step.  The blocks of a prompt slice read
+    // keys that other blocks of the same slice write, so there all new K/V must be in the cache before attention
+    // starts: the stand-alone row kernel does it.
+    bool qkv_fused = bf;
+    for (const step_entry& e : ent) qkv_fused = qkv_fused && e.pos0 == 0;
+    if (qkv_fused) {
+        std::vector<char> seen(p->max_requests, 0);
+        for (const step_entry& e : ent) {
+            if (seen[e.req]) qkv_fused = false;
+            seen[e.req] = 1;
+        }
+    }
 
 #define SLED_TRY(x)                        \
     do {                                   \
@@ -847,12 +862,17 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     // arrival counters of the attention work items start at zero (each layer leaves them at zero)
     SLED_RUN(SLED_PROF_ROWS, sled_launch_fill_i32(arrive, 0, (size_t)B * Hkv, st));
     SLED_RUN(SLED_PROF_ROWS, sled_launch_rope_table(m, p, meta, cs, kvslot, st));
+    if (bf) SLED_RUN(SLED_PROF_ROWS, sled_launch_attn_plan(m, p, meta, plan, st));
     SLED_RUN(SLED_PROF_ROWS, sled_launch_embed_norm(m, tokens, T, h, xa, pl_d, m->layers[0].g_attn, st));
     for (int l = 0; l < s.n_layers; l++) {
         const sled_layer_weights& w = m->layers[l];
         SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xa, pl_d, w.w_qkv, w.s_qkv, T, T_pad, m->n_qkv, d, SLED_EPI_PARTIAL, g_qkv, partial, nullptr, 0, 0, st));
-        SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, T, l, partial, g_qkv.split, T_pad, cs, kvslot, qb, pl_hd, st));
-        SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, part_o, part_ml, arrive, xo, pl_hd, QT, st));
+        if (qkv_fused) {
+            SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, nullptr, 0, partial, g_qkv.split, T_pad, cs, kvslot, plan, part_o, part_ml, arrive, xo, pl_hd, QT, st));
+        } else {
+            SLED_RUN(SLED_PROF_ROWS, sled_launch_qkv_rope_store(m, p, T, l, partial, g_qkv.split, T_pad, cs, kvslot, qb, pl_hd, st));
+            SLED_RUN(SLED_PROF_ATTN, sled_launch_attention(m, p, meta, l, qb, pl_hd, nullptr, 0, 0, nullptr, nullptr, plan, part_o, part_ml, arrive, xo, pl_hd, QT, st));
+        }
         SLED_RUN(SLED_PROF_PROJ, sled_launch_gemm(m, xo, pl_hd, w.w_o, w.s_o, T, T_pad, d, HD, SLED_EPI_PARTIAL, g_o, partial, nullptr, 0, 0, st));
         SLED_RUN(SLED_PROF_ROWS, sled_launch_residual_norm(m, partial, g_o.split, T, T_pad, h, xa, pl_d, w.g_mlp, st));
         if (gu_fused) {

@@ -25,6 +25,11 @@
 // through LDS.  When a (request, kv head) is split over several work items, each stores its state and
 // the last one to arrive (a device-scope counter) merges them in a fixed order; either way the
 // output is written in the operand order of the following projection, as a bf16 pair.
+// FUSED (a verification step: every block is a request of its own): the kernel starts from the K-slice partial sums
+// of the QKV projection.  Each consumer wavefront adds up, rotates and splits into a bf16 pair the q rows of its own
+// tile; the consumers together do the same for the request's new k and v rows of this kv head and write them into
+// the cache pages (the work item that holds a row's page does), while the producers already stream the context
+// pages, which depend on none of this.  Only the pages that hold new rows wait for those stores.
 //
 // fp32 kernel (fp32 models): one wavefront per (row, query head), lanes over keys.
 #include "sled_internal.h"
@@ -44,10 +49,12 @@ constexpr int ATTN_RING = 3;  // page buffers per page group: the one being read
 // floats of one parked state in LDS: O tile [8][64 lanes][4] + max[16] + sum[16]
 constexpr int ATTN_PARK_F = 8 * 64 * 4 + 32;
 
-template <int QT>
+template <int QT, bool FUSED>
 __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_kernel(
     sled_step_meta meta, const int32_t* __restrict__ len_dev, const bf16_t* __restrict__ Q, size_t q_plane,
-    const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int64_t n_pages, int layer, int Hq, int Hkv,
+    const float* __restrict__ qkv_partial, int n_split, int T_pad, const float2* __restrict__ cs,
+    const int32_t* __restrict__ kvslot, const int32_t* __restrict__ plan, bf16_t* k_pool, bf16_t* v_pool, int64_t n_pages,
+    int layer, int Hq, int Hkv,
     float scale_log2, float* __restrict__ part_o, float* __restrict__ part_ml, int32_t* __restrict__ arrive,
     bf16_t* __restrict__ X, size_t x_plane) {
     constexpr int D = 128, NPG = attn_groups(QT), RING = ATTN_RING;
@@ -55,20 +62,22 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
     __shared__ int sh_last;
 
     const int w = blockIdx.x;
-    const int b = meta.work[4 * w + 0], g = meta.work[4 * w + 1];
-    const int page0 = meta.work[4 * w + 2], npg = meta.work[4 * w + 3];
+    // the work item's record, written once per step by attn_plan_kernel: one look-up instead of a chain of four
+    const int32_t* rec = plan + 12 * w;
+    const int b = rec[0], g = rec[1];
+    const int page0 = rec[2], npg = rec[3];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: page ids are then fetched by scalar loads
     const bool producer = wv >= NPG * QT;
     const int pgid = producer ? wv - NPG * QT : wv / QT, qt = producer ? 0 : wv - pgid * QT;
     const int G = Hq / Hkv;
-    const int L = len_dev[meta.req_id[b]] + meta.pos0[b];  // everything before the block's first row is context
-    const int n = meta.k[b] + 1;
+    const int L = rec[4];  // everything before the block's first row is context
+    const int n = rec[5];
     const int rows = G * n;
-    const int row0 = meta.cu_rows[b];
+    const int row0 = rec[6];
     const int n_valid_pages = (L + n + 15) >> 4;
     const int page_end = min(page0 + npg, n_valid_pages);
-    const int32_t* pages = meta.pages + meta.cu_pages[b];
+    const int32_t* pages = meta.pages + rec[7];
     const int lq = lane & 15, lg = lane >> 4;
 
     // Q operand of this wavefront's tile, both planes of the bf16 pair, straight into registers:
@@ -76,7 +85,11 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
     const int r_mine = qt * 16 + lq;
     const int jrow = r_mine / G;
     bf16x8_t qf[2][4];
-    {
+#pragma unroll
+    for (int pl = 0; pl < 2; pl++)
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) qf[pl][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(0u, 0u, 0u, 0u));
+    if (!FUSED) {
         const int hh = r_mine - jrow * G;
 #pragma unroll
         for (int pl = 0; pl < 2; pl++)
@@ -88,6 +101,131 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
                                                           ks * 32 + lg * 8);
                 qf[pl][ks] = __builtin_bit_cast(bf16x8_t, val);
             }
+    } else if (!producer) {
+        // Items: QT*16 rows x 16 quads of q (a quad = four neighbouring rotary pairs of one head: dims i..i+3 and
+        // i+64..i+67), then n x 16 quads of k, then n x 32 groups of four v values.  Lane `me` of the consumers takes
+        // items me, me + nc, ...; all loads of up to two items are in flight together, so the prologue costs one
+        // round trip to the partial sums, not one per K slice.
+        const int n_qkv = (Hq + 2 * Hkv) * D;
+        const size_t sstride = (size_t)T_pad * n_qkv;   // one K slice of the projection
+        const int nc = NPG * QT * 64, me = wv * 64 + lane;
+        const int NQ = QT * 16 * 16, NK = n * 16, NV = n * 32;
+        bf16_t* qtile = reinterpret_cast<bf16_t*>(smem) + (size_t)NPG * RING * 4096;   // behind the page rings
+        for (int it0 = me; it0 < NQ + NK + NV; it0 += 2 * nc) {
+            int kind[2];          // 0 q, 1 k, 2 v, -1 nothing to fetch
+            int jr[2], ci[2];     // row (q: query row of the tile set; k, v: row of the request), quad / group index
+            const float* src[2];  // first element of the item in K slice 0 (second quad of a rotary item 64 further)
+            float4 acc[2][2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int it = it0 + u * nc;
+                kind[u] = -1;
+                jr[u] = ci[u] = 0;
+                src[u] = qkv_partial;
+                acc[u][0] = acc[u][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (it < NQ) {
+                    jr[u] = it >> 4;
+                    ci[u] = it & 15;
+                    if (jr[u] < rows) {
+                        const int j = jr[u] / G, hh = jr[u] - j * G;
+                        kind[u] = 0;
+                        src[u] = qkv_partial + (size_t)(row0 + j) * n_qkv + (g * G + hh) * D + 4 * ci[u];
+                    }
+                } else if (it < NQ + NK + NV) {
+                    const bool isk = it < NQ + NK;
+                    const int e = isk ? it - NQ : it - NQ - NK;
+                    jr[u] = isk ? e >> 4 : e >> 5;
+                    ci[u] = isk ? e & 15 : e & 31;
+                    const int lp = (L + jr[u]) >> 4;
+                    if (lp >= page0 && lp < page_end) {   // the row's page belongs to this work item
+                        kind[u] = isk ? 1 : 2;
+                        src[u] = qkv_partial + (size_t)(row0 + jr[u]) * n_qkv + (Hq + (isk ? 0 : Hkv) + g) * D + 4 * ci[u];
+                    }
+                }
+            }
+            for (int sp0 = 0; sp0 < n_split; sp0 += 4) {   // K slices in ascending order, four at a time
+                float4 v[2][4][2];
+#pragma unroll
+                for (int u = 0; u < 2; u++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        const bool on = kind[u] >= 0 && sp0 + q < n_split;
+                        const float* ptr = src[u] + (size_t)(sp0 + q) * sstride;
+                        v[u][q][0] = on ? *reinterpret_cast<const float4*>(ptr) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        v[u][q][1] = (on && kind[u] < 2) ? *reinterpret_cast<const float4*>(ptr + D / 2) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+#pragma unroll
+                for (int u = 0; u < 2; u++)
+#pragma unroll
+                    for (int q = 0; q < 4; q++)
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; h2++) {
+                            acc[u][h2].x += v[u][q][h2].x;
+                            acc[u][h2].y += v[u][q][h2].y;
+                            acc[u][h2].z += v[u][q][h2].z;
+                            acc[u][h2].w += v[u][q][h2].w;
+                        }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int it = it0 + u * nc;
+                if (it >= NQ + NK + NV) continue;
+                const float x1[4] = {acc[u][0].x, acc[u][0].y, acc[u][0].z, acc[u][0].w};
+                const float x2[4] = {acc[u][1].x, acc[u][1].y, acc[u][1].z, acc[u][1].w};
+                if (it < NQ) {
+                    // q quad -> the tile's operand image in LDS: row r = qt'*16 + lq', dim d -> [plane][d/32][lane (d%32/8)*16 + lq'][d%8]
+                    uint32_t h1[2] = {0u, 0u}, l1[2] = {0u, 0u}, h2[2] = {0u, 0u}, l2[2] = {0u, 0u};
+                    if (kind[u] == 0) {
+                        const int j = jr[u] / G;
+                        const float4 c01 = *reinterpret_cast<const float4*>(cs + (size_t)(row0 + j) * (D / 2) + 4 * ci[u]);
+                        const float4 c23 = *reinterpret_cast<const float4*>(cs + (size_t)(row0 + j) * (D / 2) + 4 * ci[u] + 2);
+                        const float cc[4] = {c01.x, c01.z, c23.x, c23.z}, ss[4] = {c01.y, c01.w, c23.y, c23.w};
+                        float y1[4], y2[4];
+#pragma unroll
+                        for (int e = 0; e < 4; e++) rope_pair(x1[e], x2[e], cc[e], ss[e], y1[e], y2[e]);
+#pragma unroll
+                        for (int e2 = 0; e2 < 2; e2++) {
+                            const bf16_t a0 = f32_to_bf16(y1[2 * e2]), a1 = f32_to_bf16(y1[2 * e2 + 1]);
+                            const bf16_t b0 = f32_to_bf16(y2[2 * e2]), b1 = f32_to_bf16(y2[2 * e2 + 1]);
+                            h1[e2] = (uint32_t)a0 | ((uint32_t)a1 << 16);
+                            h2[e2] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+                            l1[e2] = (uint32_t)f32_to_bf16(y1[2 * e2] - bf16_to_f32(a0)) | ((uint32_t)f32_to_bf16(y1[2 * e2 + 1] - bf16_to_f32(a1)) << 16);
+                            l2[e2] = (uint32_t)f32_to_bf16(y2[2 * e2] - bf16_to_f32(b0)) | ((uint32_t)f32_to_bf16(y2[2 * e2 + 1] - bf16_to_f32(b1)) << 16);
+                        }
+                    }
+                    const int d = 4 * ci[u];   // < 64
+                    const int tq = jr[u] >> 4, ldst = (((d & 31) >> 3) << 4) + (jr[u] & 15), ks = d >> 5;
+                    bf16_t* base = qtile + (size_t)tq * 4096 + (size_t)ldst * 8 + (d & 7);
+                    *reinterpret_cast<uint2*>(base + (0 * 4 + ks) * 512) = make_uint2(h1[0], h1[1]);
+                    *reinterpret_cast<uint2*>(base + (1 * 4 + ks) * 512) = make_uint2(l1[0], l1[1]);
+                    *reinterpret_cast<uint2*>(base + (0 * 4 + ks + 2) * 512) = make_uint2(h2[0], h2[1]);
+                    *reinterpret_cast<uint2*>(base + (1 * 4 + ks + 2) * 512) = make_uint2(l2[0], l2[1]);
+                } else if (kind[u] == 1) {
+                    const int t = row0 + jr[u], i = 4 * ci[u];
+                    const float4 c01 = *reinterpret_cast<const float4*>(cs + (size_t)t * (D / 2) + i);
+                    const float4 c23 = *reinterpret_cast<const float4*>(cs + (size_t)t * (D / 2) + i + 2);
+                    const float cc[4] = {c01.x, c01.z, c23.x, c23.z}, ss[4] = {c01.y, c01.w, c23.y, c23.w};
+                    float y1[4], y2[4];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) rope_pair(x1[e], x2[e], cc[e], ss[e], y1[e], y2[e]);
+                    const int ps = kvslot[t];
+                    bf16_t* kp = k_pool + (((size_t)layer * n_pages + (ps >> 4)) * Hkv + g) * (16 * D);
+                    // four neighbouring dims share an 8-byte piece of the page's operand order
+                    *reinterpret_cast<uint2*>(kp + kpage_offset(ps & 15, i)) =
+                        make_uint2((uint32_t)f32_to_bf16(y1[0]) | ((uint32_t)f32_to_bf16(y1[1]) << 16),
+                                   (uint32_t)f32_to_bf16(y1[2]) | ((uint32_t)f32_to_bf16(y1[3]) << 16));
+                    *reinterpret_cast<uint2*>(kp + kpage_offset(ps & 15, i + D / 2)) =
+                        make_uint2((uint32_t)f32_to_bf16(y2[0]) | ((uint32_t)f32_to_bf16(y2[1]) << 16),
+                                   (uint32_t)f32_to_bf16(y2[2]) | ((uint32_t)f32_to_bf16(y2[3]) << 16));
+                } else if (kind[u] == 2) {
+                    const int t = row0 + jr[u], dd = 4 * ci[u];
+                    const int ps = kvslot[t];
+                    bf16_t* vp = v_pool + (((size_t)layer * n_pages + (ps >> 4)) * Hkv + g) * (16 * D);
+#pragma unroll
+                    for (int e = 0; e < 4; e++) vp[vpage_offset(ps & 15, dd + e)] = f32_to_bf16(x1[e]);
+                }
+            }
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the hand-counted waits below start from an empty queue
 
@@ -198,10 +336,24 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
     const int n_rounds = (page_end - page0 + NPG - 1) / NPG;                  // uniform over the workgroup
     const int my_rounds = max(0, (page_end - page0 - pgid + NPG - 1) / NPG);  // rounds in which this group has a page
     auto page_of = [&](int r) { return page0 + pgid + r * NPG; };
+    // FUSED: pages from the one that holds position L on may contain rows this kernel has just written; they are
+    // requested only after the barrier that follows those stores (pages ascend with the round, so the early ones
+    // are a prefix of the rounds and the order of issue stays the order of the rounds)
+    const int first_new_page = L >> 4;
     if (producer) {
+        int issued = 0;
 #pragma unroll
         for (int r = 0; r < PF; r++)
-            if (r < my_rounds) load_page(r % RING, page_of(r));
+            if (r < my_rounds && (!FUSED || page_of(r) < first_new_page)) {
+                load_page(r % RING, page_of(r));
+                issued = r + 1;
+            }
+        if (FUSED) {
+            __builtin_amdgcn_s_barrier();   // the consumers' K/V stores have been acknowledged (they waited before it)
+#pragma unroll
+            for (int r = 0; r < PF; r++)
+                if (r >= issued && r < my_rounds) load_page(r % RING, page_of(r));
+        }
         if (my_rounds > 1)
             asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         else
@@ -218,6 +370,15 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
             }
         }
     } else {
+        if (FUSED) {
+            __builtin_amdgcn_s_waitcnt(7 << 4 | 3 << 14 | 15);   // this wavefront's q quads are in LDS ...
+            __builtin_amdgcn_s_barrier();   // ... everybody's are, and (s_waitcnt vmcnt(0) above) every new K/V row is in memory
+            const bf16_t* qtile = reinterpret_cast<const bf16_t*>(smem) + (size_t)NPG * RING * 4096 + (size_t)qt * 4096 + lane * 8;
+#pragma unroll
+            for (int pl = 0; pl < 2; pl++)
+#pragma unroll
+                for (int ks = 0; ks < 4; ks++) qf[pl][ks] = *reinterpret_cast<const bf16x8_t*>(qtile + (pl * 4 + ks) * 512);
+        }
         for (int r = 0; r < n_rounds; r++) {
             __builtin_amdgcn_s_waitcnt(7 << 4 | 3 << 14 | 15);  // lgkmcnt(0): this wavefront's LDS reads are back
             __builtin_amdgcn_s_barrier();
@@ -274,7 +435,7 @@ __global__ __launch_bounds__(64 * (QT + 1) * attn_groups(QT)) void attn_bf16_ker
     // the merge: group p takes items p, p + NPG, ... in ascending order, then the groups are folded
     // through LDS as above.
     const int bg = b * Hkv + g;
-    const int w0 = meta.cu_work[bg], w1 = meta.cu_work[bg + 1];
+    const int w0 = rec[8], w1 = rec[9];
     const bool single = (w1 - w0) == 1;
     // Cross-workgroup hand-over without a device-scope fence (which writes back and invalidates a whole
     // L2 and, with one per workgroup, serialises on each XCD): the partial states are written and read
@@ -408,32 +569,40 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(sled_step_meta meta, const
 
 size_t sled_attn_lds_bytes(int QT) {
     const int npg = attn_groups(QT);
-    const size_t loop_bytes = (size_t)npg * ATTN_RING * 8192;                                      // page rings
+    const size_t loop_bytes = (size_t)npg * ATTN_RING * 8192 + (size_t)QT * 8192;                  // page rings, q tiles (fused prologue)
     const size_t merge_bytes = (size_t)(npg - 1) * QT * ATTN_PARK_F * sizeof(float);              // parked states
     return loop_bytes > merge_bytes ? loop_bytes : merge_bytes;
 }
 
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
-                          size_t q_plane, float* part_o, float* part_ml, int32_t* arrive, void* X_out, size_t x_plane,
-                          int QT, hipStream_t st) {
+                          size_t q_plane, const float* qkv_partial, int n_split, int T_pad, const float* cs,
+                          const int32_t* kvslot, const int32_t* plan, float* part_o, float* part_ml, int32_t* arrive,
+                          void* X_out, size_t x_plane, int QT, hipStream_t st) {
     const sled_shape& s = m->s;
     if (s.dtype == SLED_BF16) {
         const float scale_log2 = 1.4426950408889634f / sqrtf((float)s.head_dim);
         const size_t lds = sled_attn_lds_bytes(QT);
         dim3 grid(meta.n_work), blk(64 * (QT + 1) * attn_groups(QT));
-#define SLED_ATTN_CASE(N)                                                                                            \
-    case N: {                                                                                                        \
+        const bool fused = qkv_partial != nullptr;
+#define SLED_ATTN_LAUNCH(N, F)                                                                                       \
+    {                                                                                                                \
         static bool allowed = false;                                                                                 \
         if (!allowed) {                                                                                              \
-            SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<N>),                          \
+            SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<N, F>),                       \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                     \
             allowed = true;                                                                                          \
         }                                                                                                            \
-        hipLaunchKernelGGL(attn_bf16_kernel<N>, grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q),  \
-                           q_plane, static_cast<const bf16_t*>(p->k_pool), static_cast<const bf16_t*>(p->v_pool),     \
-                           p->n_pages, layer, s.n_q_heads, s.n_kv_heads, scale_log2, part_o, part_ml, arrive,         \
+        hipLaunchKernelGGL((attn_bf16_kernel<N, F>), grid, blk, lds, st, meta, p->len_dev, static_cast<const bf16_t*>(Q), \
+                           q_plane, qkv_partial, n_split, T_pad, reinterpret_cast<const float2*>(cs), kvslot, plan,  \
+                           static_cast<bf16_t*>(p->k_pool), static_cast<bf16_t*>(p->v_pool), p->n_pages, layer,      \
+                           s.n_q_heads, s.n_kv_heads, scale_log2, part_o, part_ml, arrive,                           \
                            static_cast<bf16_t*>(X_out), x_plane);                                                    \
-    } break;
+    }
+#define SLED_ATTN_CASE(N)                \
+    case N:                              \
+        if (fused) SLED_ATTN_LAUNCH(N, true) \
+        else SLED_ATTN_LAUNCH(N, false)  \
+        break;
         switch (QT) {
             SLED_ATTN_CASE(1)
             SLED_ATTN_CASE(2)
@@ -444,9 +613,11 @@ int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_
                 SLED_FAIL(SLED_EINVAL, "attention: %d query-row tiles unsupported", QT);
         }
 #undef SLED_ATTN_CASE
+#undef SLED_ATTN_LAUNCH
         SLED_LAUNCH_CHECK();
         return SLED_OK;
     }
+    if (qkv_partial) SLED_FAIL(SLED_EINVAL, "attention: the fused QKV prologue exists for bf16 models only");
     const float scale = 1.0f / sqrtf((float)s.head_dim);
     dim3 grid(meta.T, s.n_q_heads);
     if (s.head_dim == 64)

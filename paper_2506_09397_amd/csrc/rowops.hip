@@ -221,6 +221,29 @@ __global__ void rope_table_kernel(sled_step_meta meta, const int32_t* __restrict
     }
 }
 
+// Per attention work item, once per step: everything its workgroup needs to know before it can request its first
+// page, gathered into one 48-byte record -- otherwise each of the step's attention launches starts with a chain of
+// four dependent look-ups (item -> block -> request -> committed length).
+//   [0] block  [1] kv head  [2] first page  [3] pages  [4] L = context length of the block  [5] rows of the block
+//   [6] first packed row  [7] first entry of the block's page list  [8], [9] items of this (block, kv head): first, end
+__global__ void attn_plan_kernel(sled_step_meta meta, const int32_t* __restrict__ len_dev, int Hkv, int32_t* __restrict__ plan) {
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= meta.n_work) return;
+    const int b = meta.work[4 * w + 0], g = meta.work[4 * w + 1];
+    int32_t* r = plan + 12 * w;
+    r[0] = b;
+    r[1] = g;
+    r[2] = meta.work[4 * w + 2];
+    r[3] = meta.work[4 * w + 3];
+    r[4] = len_dev[meta.req_id[b]] + meta.pos0[b];
+    r[5] = meta.k[b] + 1;
+    r[6] = meta.cu_rows[b];
+    r[7] = meta.cu_pages[b];
+    r[8] = meta.cu_work[b * Hkv + g];
+    r[9] = meta.cu_work[b * Hkv + g + 1];
+    r[10] = r[11] = 0;
+}
+
 // Reduce the QKV partial sums of one head of row t (blockIdx = (t, head), heads ordered q, k, v),
 // rotate q and k, write q to Q[T, Hq, D] and k, v into the request's page slot for position L + j.
 template <bool BF16>
@@ -241,8 +264,8 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(const float* __restr
             const float2 sc = cs[(size_t)t * half + i];
             float x1 = 0.f, x2 = 0.f;
             add_slices1x2(x1, x2, prow + c1, prow + c2, stride, n_split);
-            const float y1 = x1 * sc.x - x2 * sc.y;
-            const float y2 = x2 * sc.x + x1 * sc.y;
+            float y1, y2;
+            rope_pair(x1, x2, sc.x, sc.y, y1, y2);
             if (head < Hq) {
                 if (BF16) {  // q is kept as a bf16 pair, like every activation that is not cached
                     bf16_t* q = static_cast<bf16_t*>(Q) + ((size_t)t * Hq + head) * D;
@@ -260,12 +283,10 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(const float* __restr
                 const int g = head - Hq;
                 const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
                 if (BF16) {
-                    // K page-head block in operand order: element (slot, dd) at
-                    //   (dd/32)*512 + (((dd%32)/8)*16 + slot)*8 + dd%8
+                    // K page-head block in operand order
                     bf16_t* kp = static_cast<bf16_t*>(k_pool) + base;
-                    const int d1 = i, d2 = i + half;
-                    kp[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) << 4) + slot) * 8 + (d1 & 7)] = f32_to_bf16(y1);
-                    kp[(d2 >> 5) * 512 + ((((d2 & 31) >> 3) << 4) + slot) * 8 + (d2 & 7)] = f32_to_bf16(y2);
+                    kp[kpage_offset(slot, i)] = f32_to_bf16(y1);
+                    kp[kpage_offset(slot, i + half)] = f32_to_bf16(y2);
                 } else {
                     float* kp = static_cast<float*>(k_pool) + base + (size_t)slot * D;
                     kp[i] = y1;
@@ -280,11 +301,7 @@ __global__ __launch_bounds__(64) void qkv_rope_store_kernel(const float* __restr
             const float v = add_slices1(0.f, prow + (Hq + Hkv) * D + g * D + dd, stride, n_split);
             const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
             if (BF16) {
-                // V page-head block: element (slot, dd) at
-                //   (((dd/16)/2)*64 + (slot/4)*16 + dd%16)*8 + ((dd/16)%2)*4 + slot%4
-                const int dt = dd >> 4;
-                static_cast<bf16_t*>(v_pool)[base + ((size_t)((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15))) * 8 +
-                                             (dt & 1) * 4 + (slot & 3)] = f32_to_bf16(v);
+                static_cast<bf16_t*>(v_pool)[base + vpage_offset(slot, dd)] = f32_to_bf16(v);
             } else {
                 static_cast<float*>(v_pool)[base + (size_t)slot * D + dd] = v;
             }
@@ -333,11 +350,8 @@ __global__ void kv_ingest_kernel(const void* __restrict__ k_src, const void* __r
         const size_t src = (((size_t)layer * n_tok + tk) * Hkv + g) * D + dd;
         const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
         if (BF16) {
-            const int dt = dd >> 4;
-            static_cast<bf16_t*>(k_pool)[base + (dd >> 5) * 512 + ((((dd & 31) >> 3) << 4) + slot) * 8 + (dd & 7)] =
-                static_cast<const bf16_t*>(k_src)[src];
-            static_cast<bf16_t*>(v_pool)[base + ((size_t)((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15))) * 8 +
-                                         (dt & 1) * 4 + (slot & 3)] = static_cast<const bf16_t*>(v_src)[src];
+            static_cast<bf16_t*>(k_pool)[base + kpage_offset(slot, dd)] = static_cast<const bf16_t*>(k_src)[src];
+            static_cast<bf16_t*>(v_pool)[base + vpage_offset(slot, dd)] = static_cast<const bf16_t*>(v_src)[src];
         } else {
             static_cast<float*>(k_pool)[base + (size_t)slot * D + dd] = static_cast<const float*>(k_src)[src];
             static_cast<float*>(v_pool)[base + (size_t)slot * D + dd] = static_cast<const float*>(v_src)[src];
@@ -559,6 +573,12 @@ int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled
                            hipStream_t st) {
     hipLaunchKernelGGL(rope_table_kernel, dim3(meta.T), dim3(64), 0, st, meta, p->len_dev, m->s.head_dim / 2,
                        (double)m->s.rope_theta, reinterpret_cast<float2*>(cs), kvslot);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_attn_plan(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int32_t* plan, hipStream_t st) {
+    hipLaunchKernelGGL(attn_plan_kernel, dim3((meta.n_work + 63) / 64), dim3(64), 0, st, meta, p->len_dev, m->s.n_kv_heads, plan);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

@@ -53,6 +53,22 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
     return (bf16_t)(u >> 16);
 }
 
+// Rotation of one rotary pair (x1 = element i, x2 = element i + D/2) by the angle whose cosine and sine are c, s.
+// Written with explicit roundings (one product, one fused multiply-add per output) so that every kernel that
+// rotates gets the same bits whatever the compiler would otherwise contract.
+__device__ inline void rope_pair(float x1, float x2, float c, float s, float& y1, float& y2) {
+    y1 = __fmaf_rn(x1, c, -__fmul_rn(x2, s));
+    y2 = __fmaf_rn(x2, c, __fmul_rn(x1, s));
+}
+
+// where element (token slot, dim dd) of a 16-token page of one kv head sits inside the page's 2048-element block
+// of the bf16 pool: K in the operand order of S = K Q^T, V in the operand order of O = V^T P^T
+__host__ __device__ inline int kpage_offset(int slot, int dd) { return (dd >> 5) * 512 + ((((dd & 31) >> 3) << 4) + slot) * 8 + (dd & 7); }
+__host__ __device__ inline int vpage_offset(int slot, int dd) {
+    const int dt = dd >> 4;
+    return ((dt >> 1) * 64 + (slot >> 2) * 16 + (dd & 15)) * 8 + (dt & 1) * 4 + (slot & 3);
+}
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
@@ -239,6 +255,8 @@ int sled_launch_residual_norm(const sled_model* m, const float* partial, int n_s
 // per packed row: the rotary table cs[T][head_dim/2] and kvslot[T] = 16 * page + slot of the row's position in the cache
 int sled_launch_rope_table(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, float* cs, int32_t* kvslot,
                            hipStream_t st);
+// one record of 12 ints per attention work item (see attn_plan_kernel)
+int sled_launch_attn_plan(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int32_t* plan, hipStream_t st);
 int sled_launch_qkv_rope_store(const sled_model* m, const sled_kvpool* p, int T, int layer, const float* partial, int n_split,
                                int T_pad, const float* cs, const int32_t* kvslot, void* Q, size_t q_plane, hipStream_t st);
 int sled_launch_swiglu_reduce(const sled_model* m, const float* gu, int n_split, int T, int T_pad, void* A, size_t plane,
@@ -260,9 +278,12 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
                      int F_act, hipStream_t st);
 
 // attention.hip
+// qkv_partial != nullptr (bf16 models, every block a request of its own): the kernel itself adds up the K slices of the
+// QKV projection, rotates q and k and writes the new K/V rows into the cache; Q is then not read.
 int sled_launch_attention(const sled_model* m, const sled_kvpool* p, const sled_step_meta& meta, int layer, const void* Q,
-                          size_t q_plane, float* part_o, float* part_ml, int32_t* arrive, void* X_out, size_t x_plane,
-                          int QT, hipStream_t st);
+                          size_t q_plane, const float* qkv_partial, int n_split, int T_pad, const float* cs,
+                          const int32_t* kvslot, const int32_t* plan, float* part_o, float* part_ml, int32_t* arrive,
+                          void* X_out, size_t x_plane, int QT, hipStream_t st);
 int sled_launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 
 // accept.hip
