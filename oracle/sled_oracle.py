@@ -203,7 +203,7 @@ def layer_rows(model: OracleModel, W: Dict[str, np.ndarray], h: np.ndarray, posi
     return h, k, v
 
 
-def verify_batch(model: OracleModel, requests: Sequence[dict]) -> List[dict]:
+def verify_batch(model: OracleModel, requests: Sequence[dict], progress=None) -> List[dict]:
     """Score every request's tokens on top of its own cached context.
 
     requests[i] = {"tokens": int[n_i] = [pending, draft_1..draft_k],
@@ -211,7 +211,8 @@ def verify_batch(model: OracleModel, requests: Sequence[dict]) -> List[dict]:
     The n_i tokens sit at positions L_i .. L_i + n_i - 1.  Logits row j is the target
     distribution of the token that follows tokens[j].
     Returns per request {"logits": [n_i, V], "K_new": [n_layers, n_i, Hkv, D], "V_new": same}.
-    Requests never interact: the loop over requests is the definition of the batch."""
+    Requests never interact: the loop over requests is the definition of the batch.
+    progress(l), if given, is called after layer l (long runs report where they are; no effect on any value)."""
     E = model.weights.embed()
     hs, pos = [], []
     for r in requests:
@@ -227,6 +228,8 @@ def verify_batch(model: OracleModel, requests: Sequence[dict]) -> List[dict]:
         for i, r in enumerate(requests):
             hs[i], Knew[i][l], Vnew[i][l] = layer_rows(model, W, hs[i], pos[i], r["K"][l], r["V"][l])
         del W
+        if progress is not None:
+            progress(l)
     F = model.weights.final()
     R = _rounder(model.round_points)
     out = []

@@ -21,6 +21,9 @@ sled_accept and sled_kv_append.  The pieces:
                   greedy text: verification is lossless (Sec. 3.1).  (It equals the precomputed
                   continuation token for token unless two logits tie to within the round-off that
                   separates two batchings of the same request; the tiny-model tests demand equality.)
+  SamplingDrafter stands in for a device that drafts by sampling: every draft comes with the distribution it was
+                  drawn from (dense, or its top entries as (id, probability) pairs), which is what the server's
+                  sampling mode (Eq. 1, seeded uniforms per device and round) verifies against.
   simulate        devices draft for an exponentially distributed time (mean k x per-token draft
                   time), queue at the server, wait for the batch to fill, get their answer after the
                   measured GPU time of the step; virtual clock, real GPU work.
@@ -50,6 +53,9 @@ class Pending:
     round_no: int
     pending_token: int
     drafts: List[int]
+    # speculative sampling only: the distributions the drafts were drawn from, one row per draft -- dense
+    # float32 [k, vocab], or sparse as (token ids int32 [k, m], probabilities float32 [k, m]); on the GPU
+    q: Optional[object] = None
 
 
 @dataclasses.dataclass
@@ -64,10 +70,20 @@ class Response:
 class Server:
     """Queue + static batch planner + the verification step for a set of devices."""
 
-    def __init__(self, verifier: Verifier, batch_size: int, device: str = "cuda"):
+    def __init__(self, verifier: Verifier, batch_size: int, device: str = "cuda", mode: str = "greedy",
+                 temperature: float = 1.0, seed: int = 0):
+        """mode "greedy": exact match against the target's argmax chain.  mode "sample": speculative sampling
+        (Eq. 1): every request carries the distributions its drafts were drawn from, and the uniforms of a round
+        are a function of (seed, device, round number) alone, so an answer does not depend on how the round
+        was batched and a retried round draws the same numbers."""
+        assert mode in ("greedy", "sample")
         self.v = verifier
         self.batch_size = batch_size
         self.device = device        # where the packed token ids of a step are put
+        self.mode = mode
+        self.temperature = float(temperature)
+        self.seed = int(seed)
+        self.observer = None        # called with everything a step consumed and produced (tests, tracing)
         self.queue: Deque[Pending] = collections.deque()
         self.req_of: Dict[int, int] = {}              # device -> request id in the pool
         self.last: Dict[int, Response] = {}           # device -> answer of its latest verified round
@@ -95,9 +111,10 @@ class Server:
         self.queue = collections.deque(p for p in self.queue if p.device != device)
 
     # ---- requests ---------------------------------------------------------------------------
-    def submit(self, device: int, round_no: int, pending_token: int, drafts: Sequence[int]) -> Optional[Response]:
+    def submit(self, device: int, round_no: int, pending_token: int, drafts: Sequence[int], q=None) -> Optional[Response]:
         """Queue a verification request.  A round the server has already verified (the device did not get the
-        answer and sent it again, possibly with more drafts) is answered at once from the record."""
+        answer and sent it again, possibly with more drafts) is answered at once from the record.  In sampling
+        mode q holds the draft distributions (see Pending)."""
         last = self.last.get(device)
         if last is not None and round_no <= last.round_no:
             if round_no < last.round_no:
@@ -105,8 +122,18 @@ class Server:
             return dataclasses.replace(last, replayed=True)
         if len(drafts) > self.v.shape.k_max:
             drafts = drafts[: self.v.shape.k_max]   # the rest is drafted again next round
-        self.queue.append(Pending(device, round_no, int(pending_token), [int(d) for d in drafts]))
+        if self.mode == "sample":
+            if len(drafts) and q is None:
+                raise ValueError("sampling mode: a request with drafts needs their distributions q")
+            if q is not None:
+                q = tuple(x[: len(drafts)] for x in q) if isinstance(q, tuple) else q[: len(drafts)]
+        self.queue.append(Pending(device, round_no, int(pending_token), [int(d) for d in drafts], q if self.mode == "sample" else None))
         return None
+
+    def round_uniforms(self, device: int, round_no: int, k: int) -> Tuple[np.ndarray, float]:
+        """The uniforms of one round: k for the accept tests, one for the resample / bonus draw (float32 values)."""
+        u = np.random.default_rng([self.seed, int(device), int(round_no)]).random(k + 1, dtype=np.float32)
+        return u[:k], float(u[k])
 
     def ready(self) -> bool:
         return len(self.queue) >= self.batch_size
@@ -133,8 +160,34 @@ class Server:
             toks += [p.pending_token] + p.drafts
         tokens = torch.tensor(toks, dtype=torch.int32, device=self.device)
         logits = self.v.verify(reqs, k, tokens)
-        a, t = self.v.accept(sled.GREEDY, k, logits, tokens)
+        extra = {}
+        if self.mode == "greedy":
+            a, t = self.v.accept(sled.GREEDY, k, logits, tokens)
+        else:
+            us = [self.round_uniforms(p.device, p.round_no, len(p.drafts)) for p in batch]
+            u_acc = torch.from_numpy(np.concatenate([u for u, _ in us]).astype(np.float32)).to(self.device)
+            u_smp = torch.tensor([x for _, x in us], dtype=torch.float32, device=self.device)
+            qs = [p.q for p in batch if len(p.drafts)]
+            sparse = bool(qs) and isinstance(qs[0], tuple)
+            assert all(isinstance(x, tuple) == sparse for x in qs), "one step takes dense or sparse draft distributions, not both"
+            B = len(batch)
+            if sparse:
+                m = max(int(ids.shape[1]) for ids, _ in qs)
+                pad = lambda x, fill: torch.nn.functional.pad(x, (0, m - x.shape[1]), value=fill)   # id -1 / probability 0: padding
+                q_ids = torch.cat([pad(ids.to(torch.int32), -1) for ids, _ in qs]).contiguous()
+                q_probs = torch.cat([pad(pr.to(torch.float32), 0.0) for _, pr in qs]).contiguous()
+                sled.sled_accept_sparse(k, self.v.shape.vocab, self.temperature, logits, tokens, q_ids, q_probs, u_acc, u_smp,
+                                        self.v.accept_len[:B], self.v.out_token[:B], self.v.acc_ws)
+                a, t = self.v.accept_len[:B], self.v.out_token[:B]
+                extra = {"q_ids": q_ids, "q_probs": q_probs}
+            else:
+                q = torch.cat(qs).contiguous() if qs else None
+                a, t = self.v.accept(sled.SAMPLE, k, logits, tokens, q, u_acc, u_smp, temperature=self.temperature)
+                extra = {"q": q}
+            extra.update({"u_acc": u_acc, "u_smp": u_smp})
         self.v.commit(reqs, a)
+        if self.observer is not None:
+            self.observer(dict(batch=batch, k=k, tokens=tokens, logits=logits, accept_len=a, out_token=t, **extra))
         a_h, t_h = a.cpu().tolist(), t.cpu().tolist()     # the answers leave the GPU here
         # (the pool reserves pages for every staged row only until the exact lengths, which follow the commit back
         # to the host on their own, are picked up by its next call: nothing here waits for them)
@@ -173,6 +226,35 @@ class ReplayDrafter:
                     wrong = (wrong + 1) % self.vocab
                 out.append(wrong)
         return out
+
+
+class SamplingDrafter:
+    """Stands in for a device that drafts by sampling: draft j of a round is drawn from a distribution
+    q_j = softmax(noise-perturbed seeded logits) that depends on (device seed, number of tokens so far, j) only --
+    not a language model, but all Eq. 1 asks of a drafter: each draft comes with the distribution it was drawn from.
+    top > 0 keeps the `top` most likely tokens, renormalised, and hands q over sparsely as (ids, probabilities)."""
+
+    truth = None
+
+    def __init__(self, vocab: int, seed: int, device: str = "cuda", sharpness: float = 2.0, top: int = 0):
+        self.vocab, self.seed, self.device, self.sharpness, self.top = vocab, seed, device, sharpness, top
+
+    def draft_with_q(self, n_done: int, k: int):
+        if k == 0:
+            return [], None
+        g = torch.Generator(device=self.device)
+        g.manual_seed((self.seed * 1_000_003 + n_done * 101 + 7) % (2**31 - 1))
+        z = self.sharpness * torch.randn(k, self.vocab, generator=g, device=self.device, dtype=torch.float32)
+        q = torch.softmax(z, dim=-1)
+        if self.top > 0:
+            top = torch.topk(q, self.top, dim=1)
+            probs = (top.values / top.values.sum(dim=1, keepdim=True)).float()
+            pick = torch.multinomial(probs, 1, generator=g).squeeze(1)
+            ids = top.indices.to(torch.int32)
+            drafts = ids[torch.arange(k, device=self.device), pick]
+            return [int(x) for x in drafts.cpu()], (ids.contiguous(), probs.contiguous())
+        drafts = torch.multinomial(q, 1, generator=g).squeeze(1)
+        return [int(x) for x in drafts.cpu()], q
 
 
 def greedy_continuations(server: Server, devices: Sequence[int], first_tokens: Sequence[int], n_new: int) -> List[List[int]]:
@@ -218,9 +300,13 @@ def simulate(server: Server, drafters: Dict[int, ReplayDrafter], first_tokens: D
 
     def send(d: int, t: float) -> None:
         nonlocal tie
-        drafts = drafters[d].draft(len(texts[d]), min(k, max(0, n_new - len(texts[d]) - 1)))
-        sent[d] = Pending(d, rounds[d], pend[d], drafts)
-        r = server.submit(d, rounds[d], pend[d], drafts)
+        kk = min(k, max(0, n_new - len(texts[d]) - 1))
+        if hasattr(drafters[d], "draft_with_q"):
+            drafts, q = drafters[d].draft_with_q(len(texts[d]), kk)
+        else:
+            drafts, q = drafters[d].draft(len(texts[d]), kk), None
+        sent[d] = Pending(d, rounds[d], pend[d], drafts, q)
+        r = server.submit(d, rounds[d], pend[d], drafts, q)
         assert r is None
 
     def apply(r: Response, t: float) -> None:
@@ -230,7 +316,7 @@ def simulate(server: Server, drafters: Dict[int, ReplayDrafter], first_tokens: D
         texts[d] += p.drafts[: r.accept_len] + [r.out_token]
         pend[d] = r.out_token
         rounds[d] += 1
-        if texts[d] != drafters[d].truth[: len(texts[d])]:
+        if drafters[d].truth is not None and texts[d] != drafters[d].truth[: len(texts[d])]:
             # the target took another path than the one the drafter replays (see main): the session ends here,
             # since a drafter that is always wrong would only add one-token rounds to the tail of the run
             left_path.add(d)
@@ -263,7 +349,7 @@ def simulate(server: Server, drafters: Dict[int, ReplayDrafter], first_tokens: D
             answers += 1
             if lose_every and answers % lose_every == 0:
                 # the answer is lost; the device's timer fires and it sends the same round again
-                again = server.submit(r.device, r.round_no, sent[r.device].pending_token, sent[r.device].drafts)
+                again = server.submit(r.device, r.round_no, sent[r.device].pending_token, sent[r.device].drafts, sent[r.device].q)
                 assert again is not None and again.replayed and (again.accept_len, again.out_token) == (r.accept_len, r.out_token)
                 r = again
             apply(r, now)

@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "slow: GPU parity at full model depth, minutes of oracle time (deselect with -m 'gpu and not slow')")
 
 
 def pytest_collection_modifyitems(config, items):

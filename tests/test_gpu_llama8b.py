@@ -65,30 +65,3 @@ def test_llama8b_two_layers_all_logits():
             n += 1
     assert n >= batch.B // 2
     v.destroy()
-
-
-def test_llama8b_full_depth_sampled_requests():
-    """All 32 layers, the batch of 16 as benchmarked; the oracle scores two of the requests
-    (requests are independent, so their rows are a sample of the batch's outputs)."""
-    shape = synth.SHAPES["llama8b"]
-    batch = synth.draw_batch("b16", shape.vocab, seed=0)
-    v, w, reqs, KV = _setup(shape, batch)
-    tokens = torch.from_numpy(batch.tokens).cuda()
-    got = v.verify(reqs, batch.k, tokens).cpu().numpy()
-    assert np.isfinite(got).all()
-    offs = batch.row_offsets()
-    sample = [int(np.argmax(batch.ctx_len)), int(np.argmin(batch.ctx_len))]
-    oreqs = [{"tokens": batch.tokens[offs[i]: offs[i + 1]], "K": synth.as_f64(KV[i][0]), "V": synth.as_f64(KV[i][1])}
-             for i in sample]
-    t0 = time.time()
-    res = O.verify_batch(oracle_model(shape, w, cache=False), oreqs)
-    t1 = time.time()
-    errs = []
-    for i, r in zip(sample, res):
-        e = np.abs(got[offs[i]: offs[i + 1]] - r["logits"]).max()
-        errs.append(e)
-        print(f"8B, 32 layers, request {i} (L={batch.ctx_len[i]}, k={batch.k[i]}): max |logit error| {e:.3e}, "
-              f"logit std {r['logits'].std():.3f}")
-    print(f"oracle time for {len(sample)} requests: {t1 - t0:.1f} s")
-    assert max(errs) < TOL_BF16
-    v.destroy()

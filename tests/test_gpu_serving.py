@@ -82,3 +82,139 @@ def test_static_batcher_order_and_duplicates():
     again = server.submit(1, 0, 7, [3, 4])
     assert again.replayed and again.round_no == 0
     v.destroy()
+
+
+def _densify(ids, probs, vocab):
+    q = np.zeros((ids.shape[0], vocab))
+    for r in range(ids.shape[0]):
+        for i, pr in zip(ids[r], probs[r]):
+            if 0 <= i < vocab and pr > 0:
+                q[r, i] = pr
+    return q
+
+
+@pytest.mark.parametrize("top", [0, 256])
+def test_serving_loop_with_speculative_sampling(top):
+    """Sampling mode of the loop (Eq. 1 over several rounds, Sec. 3.2; lost answers, Sec. 3.3): every step's decisions
+    equal the oracle's on the same logits, draft distributions and uniforms; the K/V the partial accepts commit is
+    what the oracle's cache holds (checked through the logits of every later round of one device); a retried
+    round gets the recorded answer.  top = 0: dense draft distributions; top = 256: sparse (id, probability) pairs."""
+    from gpu_common import MARGIN_ACC, MARGIN_CDF
+    shape = synth.SHAPES["tiny"]
+    n_dev, n_new = 6, 14
+    v, w = build_verifier(shape, 11, n_pages=64, max_requests=n_dev, B_max=n_dev, ctx_tokens_max=n_dev * 96,
+                          gain_jitter=0.1, std=0.08)
+    om = oracle_model(shape, w)
+    server = serving.Server(v, 4, mode="sample", temperature=0.9, seed=5)
+    lens = [6, 21, 13, 30, 9, 17]
+    prompts = [synth.context_tokens(L, shape.vocab, seed=90 + i).tolist() for i, L in enumerate(lens)]
+    steps = []
+
+    def observe(s):
+        rec = {"devices": [(p.device, p.round_no) for p in s["batch"]], "k": list(s["k"]),
+               "tokens": s["tokens"].cpu().numpy(), "logits": s["logits"].cpu().numpy().astype(np.float64),
+               "u_acc": s["u_acc"].cpu().numpy().astype(np.float64), "u_smp": s["u_smp"].cpu().numpy().astype(np.float64),
+               "a": s["accept_len"].cpu().numpy(), "t": s["out_token"].cpu().numpy()}
+        if "q_ids" in s:
+            rec["q"] = _densify(s["q_ids"].cpu().numpy(), s["q_probs"].cpu().numpy(), shape.vocab)
+        else:
+            rec["q"] = None if s["q"] is None else s["q"].cpu().numpy().astype(np.float64)
+        steps.append(rec)
+
+    server.observer = observe
+    for d in range(n_dev):
+        server.open(d, prompt=prompts[d][:-1])
+    drafters = {d: serving.SamplingDrafter(shape.vocab, seed=40 + d, top=top, sharpness=0.7) for d in range(n_dev)}
+    res = serving.simulate(server, drafters, {d: prompts[d][-1] for d in range(n_dev)}, n_new, k=4, draft_ms_per_token=1.0,
+                           seed=2, lose_every=3)
+    assert all(len(res["texts"][d]) == n_new for d in range(n_dev))
+    # 1. every step's decisions against the oracle's acceptance on what the step consumed
+    n_sub = n_req = 0
+    for s in steps:
+        q = s["q"] if s["q"] is not None else np.zeros((0, shape.vocab))      # a step of plain decode requests has no drafts
+        want = O.accept_batch("sample", s["k"], s["logits"], s["tokens"], q, s["u_acc"], s["u_smp"], temperature=0.9)
+        for i, r in enumerate(want):
+            n_req += 1
+            if r["margin_acc"] > MARGIN_ACC and r["margin_cdf"] > MARGIN_CDF:
+                assert (int(s["a"][i]), int(s["t"][i])) == (r["accept_len"], r["out_token"]), f"step {steps.index(s)} request {i}"
+            else:
+                n_sub += 1
+    assert n_req >= 2 * n_dev and n_sub <= 1
+    acc = np.concatenate([s["a"] for s in steps])
+    assert 0 < acc.sum() and acc.min() >= 0      # some drafts were accepted: the rounds commit partial prefixes
+    # 2. device 0: the rows it was given in every round are the oracle's on the oracle's own cache of its text so far
+    text, K, V = [], None, None
+    pf = O.prefill(om, prompts[0][:-1])
+    K, V = pf["K"], pf["V"]
+    pending = prompts[0][-1]
+    for s in steps:
+        for i, (d, rnd) in enumerate(s["devices"]):
+            if d != 0:
+                continue
+            row0 = int(sum(s["k"][:i]) + i)
+            toks = [int(x) for x in s["tokens"][row0: row0 + s["k"][i] + 1]]
+            assert toks[0] == pending
+            r = O.verify_batch(om, [{"tokens": toks, "K": K, "V": V}])[0]
+            assert np.abs(r["logits"] - s["logits"][row0: row0 + len(toks)]).max() < 1e-4
+            a = int(s["a"][i])
+            K = np.concatenate([K, r["K_new"][:, : a + 1]], axis=1)
+            V = np.concatenate([V, r["V_new"][:, : a + 1]], axis=1)
+            text += toks[1: 1 + a] + [int(s["t"][i])]
+            pending = int(s["t"][i])
+    assert text[:n_new] == res["texts"][0]
+    assert server.v.lengths([server.req_of[0]])[0] == len(prompts[0]) - 1 + len(text)
+    # 3. a round that was answered is answered again from the record, whatever is sent with it
+    last = server.last[0]
+    again = server.submit(0, last.round_no, 1, [2, 3], None if top == 0 else (torch.zeros(2, 1, dtype=torch.int32), torch.ones(2, 1)))
+    assert again.replayed and (again.accept_len, again.out_token) == (last.accept_len, last.out_token)
+    v.destroy()
+
+
+def test_sampling_serving_preserves_the_target_distribution_chi_square():
+    """Sec. 3.1: speculative sampling is lossless.  4096 one-round sessions on the same prompt, each with its own
+    drafter and uniforms, batched 64 at a time: the first token a session ends up with (the accepted first draft, or
+    the corrective token) must be distributed as the target's softmax at that position -- chi-square over 32 groups of
+    token ids against the oracle's float64 distribution."""
+    from scipy import stats
+    shape = synth.SHAPES["tiny"]
+    n_par, waves, tau = 64, 64, 1.0
+    v, w = build_verifier(shape, 13, n_pages=n_par * 2 + 8, max_requests=n_par, B_max=n_par, ctx_tokens_max=n_par * 32,
+                          gain_jitter=0.1, std=0.3)       # std 0.3: a target distribution with some shape to it
+    om = oracle_model(shape, w)
+    prompt = synth.context_tokens(9, shape.vocab, seed=123).tolist()
+    pf = O.prefill(om, prompt[:-1])
+    p = O.softmax64(O.verify_batch(om, [{"tokens": prompt[-1:], "K": pf["K"], "V": pf["V"]}])[0]["logits"][0], tau)
+    Kc = torch.from_numpy(pf["K"]).float().cuda()
+    Vc = torch.from_numpy(pf["V"]).float().cuda()
+    server = serving.Server(v, n_par, mode="sample", temperature=tau, seed=17)
+    counts = np.zeros(shape.vocab)
+    n_first_accepted = 0
+    for wv in range(waves):
+        devs = [wv * n_par + i for i in range(n_par)]
+        sent = {}
+        for d in devs:
+            server.open(d, Kc, Vc)
+            drafts, q = serving.SamplingDrafter(shape.vocab, seed=d, sharpness=0.6).draft_with_q(0, 3)
+            sent[d] = drafts
+            assert server.submit(d, 0, prompt[-1], drafts, q) is None
+        for r in server.run_batch():
+            first = sent[r.device][0] if r.accept_len >= 1 else r.out_token
+            n_first_accepted += r.accept_len >= 1
+            counts[first] += 1
+        for d in devs:
+            server.close(d)
+    n = n_par * waves
+    assert counts.sum() == n and 0.02 * n < n_first_accepted < 0.98 * n     # both branches of Eq. 1 were taken
+    groups = 32
+    obs = counts.reshape(groups, -1).sum(axis=1)
+    exp = p.reshape(groups, -1).sum(axis=1) * n
+    chi2 = float(((obs - exp) ** 2 / exp).sum())
+    pval = float(stats.chi2.sf(chi2, groups - 1))
+    print(f"first-token distribution over {n} sessions: chi2 = {chi2:.1f} on {groups - 1} dof, p = {pval:.3f}; "
+          f"first draft accepted in {n_first_accepted / n:.2f} of the sessions")
+    assert pval > 1e-3
+    # the same counts against the drafters' average distribution would fail: the test can tell the two apart
+    z = np.zeros(shape.vocab)
+    z[: shape.vocab // 2] = 2.0 / shape.vocab
+    assert stats.chi2.sf(float(((obs - z.reshape(groups, -1).sum(axis=1) * n + 1e-9) ** 2 / (z.reshape(groups, -1).sum(axis=1) * n + 1e-9)).sum()), groups - 1) < 1e-6
+    v.destroy()
