@@ -275,12 +275,20 @@ SLED_API int sled_accept_static(int mode, int B, const int* k /*host*/, int voca
  * per draft token on the uplink (Sec. 3.2 wants tokens, not activations, to travel) by q_m (id, probability) pairs.
  *   q_ids[sum k, q_m]     dev int32; distinct within a row; an id outside [0, vocab) marks padding
  *   q_probs[sum k, q_m]   dev float32; a probability of 0 marks padding
+ *   q_rest[sum k]         dev float32 or NULL.  NULL: q is zero off the list (the device drafted from the listed
+ *                         tokens alone, e.g. its top q_m renormalised).  Otherwise the pairs carry the drafter's
+ *                         probabilities as they were and q_rest[j] is the mass of everything it did not list, which
+ *                         both sides take to be spread evenly over the unlisted tokens:
+ *                         q_j(v) = q_rest[j] / (vocab - listed) for v off the list.  Exact when the device drew
+ *                         its draft from that reconstruction (top entries as they are, with probability q_rest an
+ *                         unlisted token chosen uniformly); it distorts the drafter less than renormalising, so
+ *                         more drafts are accepted, at the price of a second pass over the rejecting row.
  *   1 <= q_m <= 1024
- * Everything else as sled_accept (mode SLED_SAMPLE).  A drafted token that is not among its row's ids has
- * q = 0 and is accepted (product form of Eq. 1). */
+ * Everything else as sled_accept (mode SLED_SAMPLE).  A drafted token that is not among its row's ids has the
+ * probability of an unlisted token (0 without q_rest: it is then accepted, product form of Eq. 1). */
 SLED_API int sled_accept_sparse(int B, const int* k /*host*/, int vocab, float temperature, const float* logits /*dev*/,
                        const int32_t* tokens /*dev*/, int q_m, const int32_t* q_ids /*dev*/, const float* q_probs /*dev*/,
-                       const float* u_acc /*dev*/, const float* u_smp /*dev*/, int32_t* accept_len /*dev out*/,
+                       const float* q_rest /*dev or NULL*/, const float* u_acc /*dev*/, const float* u_smp /*dev*/, int32_t* accept_len /*dev out*/,
                        int32_t* out_token /*dev out*/, void* workspace /*dev*/, size_t workspace_bytes, void* stream);
 
 /* Confidence score of every row of a logits matrix: conf[t] = max_v softmax(logits[t] / temperature)[v], the quantity

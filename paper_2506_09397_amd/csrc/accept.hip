@@ -157,19 +157,40 @@ __device__ inline void row_stat(const RowStat* __restrict__ st, int n_split, flo
 // Where the draft distributions come from: dense rows q[sum k, V], or, per draft, `m` (token id, probability)
 // pairs of a distribution that is zero elsewhere (ids distinct; an entry with probability 0 or an id outside
 // the vocabulary is padding).
+// With `rest` (sparse only): the pairs carry the probabilities as the drafter had them, not renormalised, and
+// rest[draft] is the mass of everything not listed, taken to be spread evenly over the unlisted tokens.
 struct QSrc {
     const float* dense;
     const int32_t* ids;
     const float* probs;
+    const float* rest;
     int m;  // 0: dense
 };
+
+__device__ inline bool q_entry_real(int id, float pr, int V) { return id >= 0 && id < V && pr > 0.f; }
+
+// probability of an unlisted token: the remainder mass over the number of unlisted tokens
+__device__ inline double q_background(const QSrc& q, int qrow, int V, int n_real) {
+    if (!q.rest || n_real >= V) return 0.0;
+    return (double)q.rest[qrow] / (double)(V - n_real);
+}
 
 __device__ inline double q_of(const QSrc& q, int qrow, int V, int d) {
     if (q.m == 0) return (double)q.dense[(size_t)qrow * V + d];
     double v = 0.0;
-    for (int i = 0; i < q.m; i++)
-        if (q.ids[(size_t)qrow * q.m + i] == d) v = (double)q.probs[(size_t)qrow * q.m + i];
-    return v;
+    bool found = false;
+    int n_real = 0;
+    for (int i = 0; i < q.m; i++) {
+        const int id = q.ids[(size_t)qrow * q.m + i];
+        const float pr = q.probs[(size_t)qrow * q.m + i];
+        if (!q_entry_real(id, pr, V)) continue;
+        n_real++;
+        if (id == d) {
+            v = (double)pr;
+            found = true;
+        }
+    }
+    return found ? v : q_background(q, qrow, V, n_real);
 }
 
 struct Decision {
@@ -242,7 +263,7 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     __shared__ int sp_tile[SLED_SPARSE_Q_MAX];      //           and the tile it falls in (-1: padding)
     __shared__ double q_tile[WTILE];                //           q over the tile that holds the draw
     __shared__ Decision sh_dc;
-    __shared__ int sh_tile;
+    __shared__ int sh_tile, sh_real;
     __shared__ double sh_base, sh_total;
     const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, n_wv = blockDim.x >> 6;
     if (wv == 0) {
@@ -285,7 +306,8 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     };
     // this lane's 16 weights of tile t: exp((z - m)/tau) (proportional to p), or max(0, p - q) with p = that / S
     // (with sparse q the residual is only ever needed inside the tile that holds the draw, whose q is in q_tile)
-    auto weights = [&](int t, bool residual, double inv_S, double* w) {
+    // (qconst >= 0: the residual against the same q everywhere -- the background of a sparse q with remainder mass)
+    auto weights = [&](int t, bool residual, double inv_S, double* w, double qconst = -1.0) {
         const int v = t * WTILE + lane * 16;
         float zx[16], qx[16];
         load16(z, v, zx, -INFINITY);
@@ -294,7 +316,7 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
         for (int e = 0; e < 16; e++) {
             const double ev = exp(((double)zx[e] - m) * it);  // exp(-inf) = 0 beyond the row
             if (residual) {
-                const double r = ev * inv_S - (sparse ? q_tile[lane * 16 + e] : (double)qx[e]);
+                const double r = ev * inv_S - (qconst >= 0.0 ? qconst : sparse ? q_tile[lane * 16 + e] : (double)qx[e]);
                 w[e] = r > 0.0 ? r : 0.0;
             } else {
                 w[e] = ev;
@@ -302,10 +324,10 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
         }
     };
     // every wavefront sums whole tiles (lane order, then a butterfly): no workgroup barrier per tile
-    auto sweep = [&](bool residual, double inv_S) {
+    auto sweep = [&](bool residual, double inv_S, double qconst = -1.0) {
         for (int t = wv; t < n_tiles; t += n_wv) {
             double w[16];
-            weights(t, residual, inv_S, w);
+            weights(t, residual, inv_S, w, qconst);
             double acc = 0.0;
 #pragma unroll
             for (int e = 0; e < 16; e++) acc += w[e];
@@ -351,6 +373,7 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     };
 
     const double u = (double)u_smp[i];
+    double qbg = 0.0;   // sparse q with remainder mass: probability of a token that is not listed
     bool residual = false;
     double inv_S = 1.0;
     sweep(false, 1.0);  // tile sums of exp((z - m)/tau); their total is the normaliser S
@@ -361,25 +384,40 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
         if (!sparse) {
             sweep(true, 1.0 / S);
         } else {
-            // sum over a tile of max(0, p - q) = sum of p - sum over the entries in it of min(p, q): one pass over
-            // the m entries instead of a second pass over the vocabulary
+            // sum over a tile of max(0, p - q) = background - sum over the entries in it of what listing them takes
+            // away, where the background is the tile's residual against the probability c of an unlisted token.
+            // Without remainder mass c = 0: the background is the sum of p, known from the first sweep, and an entry
+            // takes min(p, q) -- one pass over the m entries instead of a second pass over the vocabulary.  With
+            // remainder mass the background needs that second pass (against the constant c), and an entry takes
+            // max(0, p - c) - max(0, p - q).
             const int32_t* ids = qsrc.ids + (size_t)dc.qrow * qsrc.m;
             const float* pr = qsrc.probs + (size_t)dc.qrow * qsrc.m;
+            if (tid == 0) {
+                int n_real = 0;
+                for (int e = 0; e < qsrc.m; e++) n_real += q_entry_real(ids[e], pr[e], V);
+                sh_real = n_real;
+            }
+            __syncthreads();
+            qbg = q_background(qsrc, dc.qrow, V, sh_real);
+            if (qbg > 0.0) {
+                sweep(true, 1.0 / S, qbg);
+            }
             for (int e = tid; e < qsrc.m; e += blockDim.x) {
                 const int id = ids[e];
                 const double qv = (double)pr[e];
-                const bool real = id >= 0 && id < V && qv > 0.0;
+                const bool real = q_entry_real(id, pr[e], V);
                 double take = 0.0;
                 if (real) {
                     const double pv = exp(((double)z[id] - m) * it) * (1.0 / S);
-                    take = pv < qv ? pv : qv;
+                    const double with_c = pv > qbg ? pv - qbg : 0.0, with_q = pv > qv ? pv - qv : 0.0;
+                    take = with_c - with_q;
                 }
                 sp_take[e] = take;
                 sp_tile[e] = real ? id / WTILE : -1;
             }
             __syncthreads();
             for (int t = tid; t < n_tiles; t += blockDim.x) {
-                double r = tile_sum[t] * (1.0 / S);
+                double r = qbg > 0.0 ? tile_sum[t] : tile_sum[t] * (1.0 / S);
                 for (int e = 0; e < qsrc.m; e++)   // in entry order: the result does not depend on the thread layout
                     if (sp_tile[e] == t) r -= sp_take[e];
                 tile_sum[t] = r > 0.0 ? r : 0.0;
@@ -400,12 +438,12 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     if (residual && sparse) {
         // q over the tile of the draw, dense in LDS
         const int tt0 = sh_tile;
-        for (int e = tid; e < WTILE; e += blockDim.x) q_tile[e] = 0.0;
+        for (int e = tid; e < WTILE; e += blockDim.x) q_tile[e] = qbg;
         __syncthreads();
         const int32_t* ids = qsrc.ids + (size_t)dc.qrow * qsrc.m;
         const float* pr = qsrc.probs + (size_t)dc.qrow * qsrc.m;
         for (int e = tid; e < qsrc.m; e += blockDim.x)
-            if (sp_tile[e] == tt0) q_tile[ids[e] - tt0 * WTILE] = (double)pr[e];
+            if (sp_tile[e] == tt0) q_tile[ids[e] - tt0 * WTILE] = (double)pr[e];   // (ids are distinct within a row)
         __syncthreads();
     }
     if (wv != 0) return;
@@ -484,14 +522,14 @@ int sled_accept_pick_split(int T, int vocab) {
 }
 
 int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, float temperature, const float* logits,
-                       const int32_t* tokens, const float* draft_q, const int32_t* q_ids, const float* q_probs, int q_m,
-                       const float* u_acc, const float* u_smp, int32_t* accept_len, int32_t* out_token, void* ws,
+                       const int32_t* tokens, const float* draft_q, const int32_t* q_ids, const float* q_probs,
+                       const float* q_rest, int q_m, const float* u_acc, const float* u_smp, int32_t* accept_len, int32_t* out_token, void* ws,
                        hipStream_t st) {
     if ((vocab + WTILE - 1) / WTILE > MAX_WTILES) SLED_FAIL(SLED_EINVAL, "accept: vocabulary %d too large", vocab);
     if (q_m < 0 || q_m > SLED_SPARSE_Q_MAX) SLED_FAIL(SLED_EINVAL, "accept: %d sparse entries per draft, at most %d", q_m, SLED_SPARSE_Q_MAX);
     KPack kp;
     for (int i = 0; i < B; i++) kp.k[i] = (uint8_t)k_host[i];
-    QSrc qsrc{draft_q, q_ids, q_probs, q_m};
+    QSrc qsrc{draft_q, q_ids, q_probs, q_m > 0 ? q_rest : nullptr, q_m};
     const int n_split = sled_accept_pick_split(T, vocab);
     int seg = (vocab + n_split - 1) / n_split;
     seg = (seg + 3) & ~3;
@@ -560,8 +598,8 @@ extern "C" int sled_accept_static(int mode, int B, const int* k, int vocab, floa
     int rc = static_scratch(&ws);
     if (rc != SLED_OK) return rc;
     // nothing in the array has to start at zero: the row scan writes every statistic the finish kernel reads
-    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, nullptr, nullptr, 0, u_acc, u_smp,
-                              accept_len, out_token, ws, static_cast<hipStream_t>(stream));
+    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, nullptr, nullptr, nullptr, 0, u_acc,
+                              u_smp, accept_len, out_token, ws, static_cast<hipStream_t>(stream));
 }
 
 int sled_launch_row_confidence(int T, int vocab, float temperature, const float* logits, float* conf, int32_t* top, void* ws,

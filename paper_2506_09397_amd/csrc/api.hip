@@ -1022,12 +1022,13 @@ extern "C" int sled_accept(int mode, int B, const int* k, int vocab, float tempe
     if (rc != SLED_OK) return rc;
     if (mode == SLED_SAMPLE && (!u_smp || (nd > 0 && (!draft_q || !u_acc))))
         SLED_FAIL(SLED_EINVAL, "sled_accept: sampling needs draft_q, u_acc and u_smp");
-    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, nullptr, nullptr, 0, u_acc, u_smp,
-                              accept_len, out_token, workspace, static_cast<hipStream_t>(stream));
+    return sled_launch_accept(mode, B, T, k, vocab, temperature, logits, tokens, draft_q, nullptr, nullptr, nullptr, 0, u_acc,
+                              u_smp, accept_len, out_token, workspace, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int sled_accept_sparse(int B, const int* k, int vocab, float temperature, const float* logits, const int32_t* tokens,
-                                  int q_m, const int32_t* q_ids, const float* q_probs, const float* u_acc, const float* u_smp,
+                                  int q_m, const int32_t* q_ids, const float* q_probs, const float* q_rest, const float* u_acc,
+                                  const float* u_smp,
                                   int32_t* accept_len, int32_t* out_token, void* workspace, size_t workspace_bytes,
                                   void* stream) {
     int T, nd;
@@ -1037,7 +1038,7 @@ extern "C" int sled_accept_sparse(int B, const int* k, int vocab, float temperat
     if (q_m < 1 || q_m > 1024) SLED_FAIL(SLED_EINVAL, "sled_accept_sparse: %d entries per draft outside [1, 1024]", q_m);
     if (!u_smp || (nd > 0 && (!q_ids || !q_probs || !u_acc)))
         SLED_FAIL(SLED_EINVAL, "sled_accept_sparse: needs q_ids, q_probs, u_acc and u_smp");
-    return sled_launch_accept(SLED_SAMPLE, B, T, k, vocab, temperature, logits, tokens, nullptr, q_ids, q_probs, q_m, u_acc,
+    return sled_launch_accept(SLED_SAMPLE, B, T, k, vocab, temperature, logits, tokens, nullptr, q_ids, q_probs, q_rest, q_m, u_acc,
                               u_smp, accept_len, out_token, workspace, static_cast<hipStream_t>(stream));
 }
 

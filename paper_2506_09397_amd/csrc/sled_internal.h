@@ -292,6 +292,6 @@ int sled_accept_pick_split(int T, int vocab);
 int sled_launch_row_confidence(int T, int vocab, float temperature, const float* logits, float* conf, int32_t* top, void* ws,
                                hipStream_t st);
 int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, float temperature, const float* logits,
-                       const int32_t* tokens, const float* draft_q, const int32_t* q_ids, const float* q_probs, int q_m,
-                       const float* u_acc, const float* u_smp, int32_t* accept_len, int32_t* out_token, void* ws,
+                       const int32_t* tokens, const float* draft_q, const int32_t* q_ids, const float* q_probs,
+                       const float* q_rest, int q_m, const float* u_acc, const float* u_smp, int32_t* accept_len, int32_t* out_token, void* ws,
                        hipStream_t st);

@@ -81,7 +81,7 @@ def lib() -> C.CDLL:
     L.sled_accept_workspace_bytes.restype = C.c_size_t
     L.sled_accept.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_accept_static.argtypes = [C.c_int, C.c_int, ip, C.c_int, C.c_float, vp, vp, vp, vp, vp, vp, vp, vp]
-    L.sled_accept_sparse.argtypes = [C.c_int, ip, C.c_int, C.c_float, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.sled_accept_sparse.argtypes = [C.c_int, ip, C.c_int, C.c_float, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_row_confidence.argtypes = [C.c_int, C.c_int, C.c_float, vp, vp, vp, vp, C.c_size_t, vp]
     L.sled_profile_enable.argtypes = [vp, C.c_int]
     L.sled_profile_read.argtypes = [vp, vp, C.POINTER(C.c_float), ip]
@@ -217,11 +217,13 @@ def sled_accept_static(mode: int, k: Sequence[int], vocab: int, temperature: flo
 
 def sled_accept_sparse(k: Sequence[int], vocab: int, temperature: float, logits: torch.Tensor, tokens: torch.Tensor,
                        q_ids: torch.Tensor, q_probs: torch.Tensor, u_acc: torch.Tensor, u_smp: torch.Tensor,
-                       accept_len: torch.Tensor, out_token: torch.Tensor, workspace: torch.Tensor) -> None:
+                       accept_len: torch.Tensor, out_token: torch.Tensor, workspace: torch.Tensor,
+                       q_rest: Optional[torch.Tensor] = None) -> None:
     assert logits.dtype == torch.float32 and tokens.dtype == torch.int32
     assert q_ids.dtype == torch.int32 and q_probs.dtype == torch.float32 and q_ids.shape == q_probs.shape
+    assert q_rest is None or (q_rest.dtype == torch.float32 and q_rest.numel() == q_ids.shape[0])
     _check(lib().sled_accept_sparse(len(k), _ints(k), vocab, float(temperature), _ptr(logits), _ptr(tokens), int(q_ids.shape[-1]),
-                                    _ptr(q_ids), _ptr(q_probs), _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token),
+                                    _ptr(q_ids), _ptr(q_probs), _ptr(q_rest), _ptr(u_acc), _ptr(u_smp), _ptr(accept_len), _ptr(out_token),
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 

@@ -171,6 +171,51 @@ def test_sparse_draft_distributions_match_oracle(vocab, k, m, pad, sigma):
     assert compare_accept(sled.SAMPLE, k, a2, t2, want) <= 1
 
 
+@pytest.mark.parametrize("vocab,k,m,pad", [
+    (1024, [4, 4, 4, 4], 8, 0),
+    (4099, [8, 0, 3, 5, 1], 64, 5),        # odd vocabulary, padding entries
+    (32000, [2, 4, 6, 8] * 4, 256, 0),
+    (128256, [2, 8, 5, 3, 7, 4] * 3, 64, 0),
+    (1000, [6, 6, 6], 1, 0),               # one listed token and the rest of the mass on everything else
+])
+@pytest.mark.parametrize("sigma", [0.5, 2.0])
+def test_sparse_draft_distributions_with_remainder_mass_match_oracle(vocab, k, m, pad, sigma):
+    """Top-m pairs as the drafter had them plus the mass of everything else, spread evenly over the unlisted tokens:
+    the library given (ids, probabilities, remainder) against the oracle given the reconstructed dense distribution;
+    drafts are drawn from that reconstruction, so some of them are unlisted tokens."""
+    case = synth.accept_case(k, vocab, sigma, seed=vocab + m + 1, device="cuda")
+    top = torch.topk(case.q, m, dim=1)
+    ids, probs = top.indices.int(), top.values.float().clone()
+    rest = (1.0 - probs.double().sum(dim=1)).clamp_min(0.0).float()
+    dense = (rest / (vocab - m))[:, None].expand(-1, vocab).clone()
+    dense.scatter_(1, ids.long(), probs)
+    g = torch.Generator(device="cuda").manual_seed(vocab + 7)
+    drafts = torch.multinomial(dense.double(), 1, generator=g).squeeze(1)
+    off = doff = 0
+    for ki in k:
+        case.tokens[off + 1: off + 1 + ki] = drafts[doff: doff + ki].int()
+        off += ki + 1
+        doff += ki
+    case.q = dense
+    if pad:
+        ids = torch.cat([ids, torch.full((ids.shape[0], pad), -1, dtype=torch.int32, device="cuda")], dim=1)
+        probs = torch.cat([probs, torch.zeros(probs.shape[0], pad, device="cuda")], dim=1)
+        perm = torch.randperm(ids.shape[1], generator=g, device="cuda")
+        ids, probs = ids[:, perm], probs[:, perm]
+    ids, probs = ids.contiguous(), probs.contiguous()
+    B, T = len(k), sum(k) + len(k)
+    ws = sled.workspace(sled.sled_accept_workspace_bytes(B, T, vocab))
+    a = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    t = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    sled.sled_accept_sparse(k, vocab, 1.0, case.logits, case.tokens, ids, probs, case.u_acc, case.u_smp, a, t, ws, q_rest=rest)
+    torch.cuda.synchronize()
+    want = oracle_accept(sled.SAMPLE, case)
+    n_sub = compare_accept(sled.SAMPLE, k, a.cpu().numpy(), t.cpu().numpy(), want, f"V={vocab} m={m} sigma={sigma} with remainder")
+    assert n_sub <= 1
+    n_off = sum(int(d) not in set(r.tolist()) for d, r in zip(drafts.cpu(), top.indices.cpu()))
+    assert m >= 64 or n_off > 0          # the short lists leave enough mass off the list for unlisted drafts to occur
+
+
 def test_sparse_token_outside_its_row_is_accepted_and_errors():
     vocab, k = 2048, [3, 2]
     case, ids, probs = _sparse_case(k, vocab, 16, 1.0, seed=3)

@@ -165,6 +165,37 @@ def test_truncated_draft_distribution_is_lossless_when_the_draft_was_drawn_from_
     assert stats.chisquare(bad, p[0] * N).pvalue < 1e-6
 
 
+def test_top_m_plus_remainder_mass_is_lossless_when_the_draft_was_drawn_from_the_reconstruction():
+    """The cheaper uplink with less distortion of the drafter: the device sends its top-m (id, probability) pairs as
+    they are plus the mass rho of everything else, and both sides agree that rho is spread evenly over the tokens that
+    are not listed.  Eq. 1 with that reconstructed distribution emits exactly p if the device drew its draft from the
+    reconstruction (top-m as is, with probability rho a uniformly random unlisted token) -- and not if it drew from its
+    full distribution, whose tail the server never saw.  Its acceptance rate beta = sum min(p, q) is at least that of
+    the renormalised top-m whenever the target puts weight on the tail."""
+    rng = np.random.default_rng(78)
+    V, m, N = 12, 4, 30000
+    z, p = _random_dists(rng, 2, V)
+    _, q_full = _random_dists(rng, 1, V, sharp=1.0)
+    top = np.argsort(-q_full[0])[:m]
+    rho = 1.0 - q_full[0, top].sum()
+    q_rec = np.full((1, V), rho / (V - m))
+    q_rec[0, top] = q_full[0, top]
+    assert abs(q_rec.sum() - 1.0) < 1e-12 and 0.05 < rho < 0.95
+    good, bad = np.zeros(V), np.zeros(V)
+    for _ in range(N):
+        d = int(rng.choice(V, p=q_rec[0]))
+        r = O.accept_sample(z, [d], q_rec, rng.random(1), rng.random())
+        good[([d][: r["accept_len"]] + [r["out_token"]])[0]] += 1
+        d = int(rng.choice(V, p=q_full[0]))
+        r = O.accept_sample(z, [d], q_rec, rng.random(1), rng.random())
+        bad[([d][: r["accept_len"]] + [r["out_token"]])[0]] += 1
+    assert stats.chisquare(good, p[0] * N).pvalue > 1e-3
+    assert stats.chisquare(bad, p[0] * N).pvalue < 1e-6
+    q_ren = np.zeros(V)
+    q_ren[top] = q_full[0, top] / q_full[0, top].sum()
+    assert np.minimum(p[0], q_rec[0]).sum() > np.minimum(p[0], q_ren).sum()
+
+
 def test_expected_accept_length_closed_form():
     """Same (p, q) in every row: E[accept_len] = beta (1 - beta^k) / (1 - beta)."""
     rng = np.random.default_rng(5)
