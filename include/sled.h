@@ -188,6 +188,15 @@ SLED_API int sled_kv_append(sled_kvpool* p, int B, const int* req_ids /*host*/, 
                    const void* const* k_src /*host array of dev ptrs*/, const void* const* v_src,
                    const int32_t* accept_len /*dev or NULL*/, void* stream);
 
+/* The way out of the cache (sled_kv_append with k_src/v_src is the way in): copies the K/V of positions
+ * first_token .. first_token + n_tokens - 1 of a request to k_dst and v_dst (dev, each
+ * [n_layers, n_tokens, n_kv_heads, head_dim] in the model dtype, K rotated as stored).  Positions may reach past the
+ * committed length into the rows a verify has staged (that is how a caller looks at what a step wrote), but not past
+ * the request's pages.  For moving a device's context to another server, and for inspection.  Asynchronous on
+ * `stream`.  Errors: SLED_EINVAL. */
+SLED_API int sled_kv_read(sled_kvpool* p, int req_id, int first_token, int n_tokens, void* k_dst /*dev out*/,
+                 void* v_dst /*dev out*/, void* stream);
+
 /* ---- the verification step ------------------------------------------------------- */
 
 /* Bytes of scratch sled_verify_batch needs for batches of at most B_max requests, T_max

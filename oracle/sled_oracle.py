@@ -177,12 +177,29 @@ class OracleModel:
         self.group = n_q_heads // n_kv_heads
 
 
+def bf16_ulp(x: np.ndarray) -> np.ndarray:
+    """Spacing of bfloat16 numbers at the magnitude of x (8 significant bits); that of the smallest normal for x = 0."""
+    a = np.maximum(np.abs(np.asarray(x, dtype=np.float64)), 2.0 ** -126)
+    return np.ldexp(1.0, np.floor(np.log2(a)).astype(np.int64) - 7)
+
+
 def layer_rows(model: OracleModel, W: Dict[str, np.ndarray], h: np.ndarray, positions: np.ndarray,
-               K_ctx: np.ndarray, V_ctx: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+               K_ctx: np.ndarray, V_ctx: np.ndarray, stored: Optional[Tuple[np.ndarray, np.ndarray]] = None,
+               audit: Optional[dict] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """One decoder layer for the n rows of one request.
 
     h[n, d] residual stream in; K_ctx, V_ctx[n_ctx, Hkv, D] this layer's cached context
-    (K already rotated).  Returns (h_out, k_new[n,Hkv,D] rotated, v_new[n,Hkv,D])."""
+    (K already rotated).  Returns (h_out, k_new[n,Hkv,D] rotated, v_new[n,Hkv,D]).
+
+    stored = (k, v)[n, Hkv, D], bf16 numbers: what a cache under test holds for the new rows.  Rounding to the cache
+    is a decision a floating-point value takes, and a value that lies within round-off of the midpoint of two bf16
+    numbers may go either way; a single such flip is a whole bf16 step and, twenty layers on, moves logits by more
+    than any tolerance.  With `stored` the decision is taken as the cache under test took it: the layer attends to
+    the stored numbers, and `audit` records how good they are as roundings of the exactly computed values:
+    "max_excess" = the largest |stored - exact| - half a bf16 step at exact, in units of the root mean square of the
+    element's head vector (0 or less: a correct rounding of the exact value itself; e: a correct rounding of a value
+    within e * rms of it), and "flips" = how many differ from the oracle's own rounding, of "elements" -- for the
+    caller to bound."""
     R, RC = _rounder(model.round_points), _rounder(model.round_points, cached=True)
     n = h.shape[0]
     Hq, Hkv, D = model.n_q_heads, model.n_kv_heads, model.head_dim
@@ -191,8 +208,19 @@ def layer_rows(model: OracleModel, W: Dict[str, np.ndarray], h: np.ndarray, posi
     k = (x @ W["wk"].T).reshape(n, Hkv, D)
     v = (x @ W["wv"].T).reshape(n, Hkv, D)
     q = R(rope(q, positions, model.rope_theta))
-    k = RC(rope(k, positions, model.rope_theta))
-    v = RC(v)
+    k = rope(k, positions, model.rope_theta)
+    if stored is None:
+        k, v = RC(k), RC(v)
+    else:
+        for name, exact, given in (("k", k, stored[0]), ("v", v, stored[1])):
+            given = np.asarray(given, dtype=np.float64)
+            if audit is not None:
+                rms = np.sqrt((exact * exact).mean(axis=-1, keepdims=True))
+                excess = (np.abs(given - exact) - 0.5 * bf16_ulp(exact)) / np.maximum(rms, 1e-300)
+                audit["max_excess"] = max(audit.get("max_excess", -math.inf), float(excess.max()))
+                audit["flips"] = audit.get("flips", 0) + int((given != bf16_round(exact)).sum())
+                audit["elements"] = audit.get("elements", 0) + given.size
+        k, v = np.asarray(stored[0], dtype=np.float64), np.asarray(stored[1], dtype=np.float64)
     K_all = np.concatenate([K_ctx, k], axis=0)
     V_all = np.concatenate([V_ctx, v], axis=0)
     o = R(attention_rows(q, K_all, V_all, K_ctx.shape[0], model.group, model.round_points)).reshape(n, Hq * D)
@@ -207,7 +235,9 @@ def verify_batch(model: OracleModel, requests: Sequence[dict], progress=None) ->
     """Score every request's tokens on top of its own cached context.
 
     requests[i] = {"tokens": int[n_i] = [pending, draft_1..draft_k],
-                   "K": [n_layers, L_i, Hkv, D], "V": same}   (L_i may be 0).
+                   "K": [n_layers, L_i, Hkv, D], "V": same}   (L_i may be 0);
+                  optionally "K_stored", "V_stored": [n_layers, n_i, Hkv, D], the bf16 numbers a cache under test
+                  holds for the new rows (see layer_rows); the result then carries "audit".
     The n_i tokens sit at positions L_i .. L_i + n_i - 1.  Logits row j is the target
     distribution of the token that follows tokens[j].
     Returns per request {"logits": [n_i, V], "K_new": [n_layers, n_i, Hkv, D], "V_new": same}.
@@ -223,10 +253,12 @@ def verify_batch(model: OracleModel, requests: Sequence[dict], progress=None) ->
     del E
     Knew = [np.empty((model.n_layers, len(r["tokens"]), model.n_kv_heads, model.head_dim)) for r in requests]
     Vnew = [np.empty_like(a) for a in Knew]
+    audits = [{} if "K_stored" in r else None for r in requests]
     for l in range(model.n_layers):
         W = model.weights.layer(l)
         for i, r in enumerate(requests):
-            hs[i], Knew[i][l], Vnew[i][l] = layer_rows(model, W, hs[i], pos[i], r["K"][l], r["V"][l])
+            st = (r["K_stored"][l], r["V_stored"][l]) if audits[i] is not None else None
+            hs[i], Knew[i][l], Vnew[i][l] = layer_rows(model, W, hs[i], pos[i], r["K"][l], r["V"][l], st, audits[i])
         del W
         if progress is not None:
             progress(l)
@@ -236,6 +268,8 @@ def verify_batch(model: OracleModel, requests: Sequence[dict], progress=None) ->
     for i in range(len(requests)):
         x = R(rmsnorm(hs[i], F["g_final"], model.rms_eps))
         out.append({"logits": x @ F["lm_head"].T, "K_new": Knew[i], "V_new": Vnew[i]})
+        if audits[i] is not None:
+            out[-1]["audit"] = audits[i]
     return out
 
 

@@ -203,7 +203,7 @@ struct Decision {
 
 // One wavefront decides one request: lane j judges draft j+1 against row j; the first failing lane ends the
 // accepted prefix (Eq. 1; in greedy mode the test is equality with the row's argmax).
-__device__ inline Decision decide_request(int mode, int i, const KPack& kp, int V, int n_split, float inv_tau,
+__device__ inline Decision decide_request(int mode, int i, const KPack& kp, int V, int n_split, float inv_tau, double it,
                                           const float* __restrict__ logits, const int32_t* __restrict__ tokens,
                                           const QSrc& draft_q, const float* __restrict__ u_acc,
                                           const RowStat* __restrict__ stats, int lane) {
@@ -216,9 +216,10 @@ __device__ inline Decision decide_request(int mode, int i, const KPack& kp, int 
     int a = k;
     for (int j0 = 0; j0 < k; j0 += 64) {
         const int j = j0 + lane;
-        bool fail = false;
+        bool fail = false, close = false;
+        float m = 0.f;
+        double zd = 0.0, lhs = 0.0;
         if (j < k) {
-            float m;
             int amax;
             double S;
             row_stat(stats + (size_t)(row0 + j) * n_split, n_split, inv_tau, m, amax, S);
@@ -228,11 +229,26 @@ __device__ inline Decision decide_request(int mode, int i, const KPack& kp, int 
             } else if (d < 0 || d >= V) {
                 fail = true;  // a draft outside the vocabulary has no target probability: rejected where it stands
             } else {
-                const double zd = (double)logits[(size_t)(row0 + j) * V + d];
-                const double pd = exp((zd - (double)m) * (double)inv_tau) / S;
-                const double lhs = (double)u_acc[d0 + j] * q_of(draft_q, d0 + j, V, d);
+                zd = (double)logits[(size_t)(row0 + j) * V + d];
+                const double pd = exp((zd - (double)m) * it) / S;
+                lhs = (double)u_acc[d0 + j] * q_of(draft_q, d0 + j, V, d);
                 fail = !(lhs <= pd);
+                // S carries the float32 round-off of the row scan (about 1e-7): a test this close is decided again below
+                close = fabs(lhs - pd) <= 1e-4 * pd;
             }
+        }
+        // Rare: the two sides of Eq. 1 agree to four digits.  The whole wavefront then sums the row's normaliser in
+        // float64, in a fixed order (lane-strided partial sums, then a butterfly), and the lane decides again.
+        unsigned long long todo = __ballot(close);
+        while (todo) {
+            const int src = __ffsll((long long)todo) - 1;
+            todo &= todo - 1;
+            const float ms = __shfl(m, src);
+            const float* z = logits + (size_t)(row0 + j0 + src) * V;
+            double part = 0.0;
+            for (int v = lane; v < V; v += 64) part += exp(((double)z[v] - (double)ms) * it);
+            for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+            if (lane == src) fail = !(lhs <= exp((zd - (double)m) * it) / part);
         }
         const unsigned long long mask = __ballot(fail);
         if (mask) {
@@ -253,7 +269,7 @@ constexpr int SLED_SPARSE_Q_MAX = 1024;  // entries per draft of a sparse draft 
 constexpr int WTILE = 1024;        // elements per wavefront tile: 16 consecutive ones per lane
 constexpr int MAX_WTILES = 2048;   // covers vocabularies up to 2 097 152
 
-__global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V, int n_split, float inv_tau,
+__global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V, int n_split, float inv_tau, float temperature,
                                                       const float* __restrict__ logits, const int32_t* __restrict__ tokens,
                                                       QSrc qsrc, const float* __restrict__ u_acc,
                                                       const float* __restrict__ u_smp, const RowStat* __restrict__ stats,
@@ -267,7 +283,8 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     __shared__ double sh_base, sh_total;
     const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, n_wv = blockDim.x >> 6;
     if (wv == 0) {
-        const Decision dc = decide_request(mode, i, kp, V, n_split, inv_tau, logits, tokens, qsrc, u_acc, stats, lane);
+        // float64 work divides by the temperature as given (a float32 number), exactly as a float64 reference does
+        const Decision dc = decide_request(mode, i, kp, V, n_split, inv_tau, 1.0 / (double)temperature, logits, tokens, qsrc, u_acc, stats, lane);
         if (lane == 0) {
             sh_dc = dc;
             accept_len[i] = dc.a;
@@ -281,7 +298,7 @@ __global__ __launch_bounds__(1024) void accept_finish(int mode, KPack kp, int V,
     const bool sparse = qsrc.m > 0;
     const bool has_q = dc.qrow >= 0;
     const float* q = (has_q && !sparse) ? qsrc.dense + (size_t)dc.qrow * V : nullptr;
-    const double m = (double)dc.m, it = (double)inv_tau;
+    const double m = (double)dc.m, it = 1.0 / (double)temperature;
     const int n_tiles = (V + WTILE - 1) / WTILE;  // at most MAX_WTILES: the host rejects larger vocabularies
     const bool vec = (V & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0 &&
                      (reinterpret_cast<uintptr_t>(qsrc.dense) & 15) == 0;
@@ -543,7 +560,7 @@ int sled_launch_accept(int mode, int B, int T, const int* k_host, int vocab, flo
     SLED_LAUNCH_CHECK();
     // greedy needs only the deciding wavefront
     hipLaunchKernelGGL(accept_finish, dim3(B), dim3(mode == SLED_SAMPLE ? 1024 : 64), 0, st, mode, kp, vocab, n_split, inv_tau,
-                       logits, tokens, qsrc, u_acc, u_smp, stats, accept_len, out_token);
+                       temperature, logits, tokens, qsrc, u_acc, u_smp, stats, accept_len, out_token);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

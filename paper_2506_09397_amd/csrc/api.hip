@@ -615,6 +615,23 @@ extern "C" int sled_kv_append(sled_kvpool* p, int B, const int* req_ids, const i
     return SLED_OK;
 }
 
+extern "C" int sled_kv_read(sled_kvpool* p, int req_id, int first_token, int n_tokens, void* k_dst, void* v_dst, void* stream) {
+    if (!p || !k_dst || !v_dst) SLED_FAIL(SLED_EINVAL, "sled_kv_read: null argument");
+    int rc = check_requests(p, 1, &req_id, "sled_kv_read");
+    if (rc != SLED_OK) return rc;
+    const sled_request& rq = p->reqs[req_id];
+    if (first_token < 0 || n_tokens < 1 || (int64_t)first_token + n_tokens > (int64_t)rq.pages.size() * 16)
+        SLED_FAIL(SLED_EINVAL, "sled_kv_read: positions %d .. %d lie outside the %zu pages of request %d", first_token,
+                  first_token + n_tokens - 1, rq.pages.size(), req_id);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    sled_stage_slot* sl;
+    if ((rc = stage_acquire(p, rq.pages.size(), &sl)) != SLED_OK) return rc;
+    for (size_t i = 0; i < rq.pages.size(); i++) sl->host[i] = rq.pages[i];
+    SLED_HIP(hipMemcpyAsync(sl->dev, sl->host, rq.pages.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    if ((rc = sled_launch_kv_export(p->m, p, k_dst, v_dst, first_token, n_tokens, sl->dev, st)) != SLED_OK) return rc;
+    return stage_release(sl, st);
+}
+
 // ------------------------------------------------------------------------------------------ verify
 namespace {
 
@@ -937,11 +954,25 @@ extern "C" int sled_prefill(sled_model* m, sled_kvpool* p, int req_id, int n_tok
     if (rc != SLED_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const sled_shape& s = m->s;
-    const int per = s.k_max + 1;  // rows of one block: what the attention kernel's query tiles are sized for
-    const int QT = ceil_div(s.n_q_heads / s.n_kv_heads * per, 16);
-    // the largest number of blocks per step that the workspace holds
+    // Rows of one block.  Every block reads all keys before it, so longer blocks mean fewer passes over the cache:
+    // a prompt takes the most rows the attention kernel's five query tiles hold (80 stacked (head, row) pairs per kv
+    // head: 20 tokens at four query heads per kv head), not the k_max + 1 of a verification request.  A batch-invariant
+    // model keeps k_max + 1, the block its fixed summation order is defined for.
+    const int G = s.n_q_heads / s.n_kv_heads;
     const int64_t reach = (int64_t)p->reqs[req_id].len_ub + n_tokens;  // every block of a slice may see that many keys
-    auto fits = [&](int blocks) { return plan_workspace(m, blocks * per, max_work_items(m, blocks, blocks * reach), QT).total <= workspace_bytes; };
+    int per = s.k_max + 1, QT = ceil_div(G * per, 16);
+    auto fits_with = [&](int rows_per_block, int tiles, int blocks) {
+        return plan_workspace(m, blocks * rows_per_block, max_work_items(m, blocks, blocks * reach), tiles).total <= workspace_bytes;
+    };
+    if (s.dtype == SLED_BF16 && !m->batch_invariant) {
+        const int big = std::max(per, 80 / G), big_qt = ceil_div(G * big, 16);
+        if (fits_with(big, big_qt, 1)) {   // a workspace sized for verification requests alone may not hold such a block
+            per = big;
+            QT = big_qt;
+        }
+    }
+    // the largest number of blocks per step that the workspace holds
+    auto fits = [&](int blocks) { return fits_with(per, QT, blocks); };
     if (!fits(1)) SLED_FAIL(SLED_EINVAL, "sled_prefill: workspace of %zu bytes is too small for one block of %d rows", workspace_bytes, per);
     int lo = 1, hi = ceil_div(n_tokens, per);
     while (lo < hi) {  // fits(lo) holds

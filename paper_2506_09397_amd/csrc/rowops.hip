@@ -359,6 +359,30 @@ __global__ void kv_ingest_kernel(const void* __restrict__ k_src, const void* __r
     }
 }
 
+// the reverse: positions first .. first+n_tok-1 of a request -> [n_layers, n_tok, Hkv, D]
+template <bool BF16>
+__global__ void kv_export_kernel(void* __restrict__ k_dst, void* __restrict__ v_dst, int first, int n_tok, int Hkv, int D,
+                                 const int32_t* __restrict__ pages, const void* __restrict__ k_pool,
+                                 const void* __restrict__ v_pool, int64_t n_pages) {
+    const int tk = blockIdx.x, layer = blockIdx.y;
+    const int pos = first + tk;
+    const int page = pages[pos >> 4];
+    const int slot = pos & 15;
+    const size_t head_elems = (size_t)16 * D;
+    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+        const int g = e / D, dd = e - g * D;
+        const size_t dst = (((size_t)layer * n_tok + tk) * Hkv + g) * D + dd;
+        const size_t base = (((size_t)layer * n_pages + page) * Hkv + g) * head_elems;
+        if (BF16) {
+            static_cast<bf16_t*>(k_dst)[dst] = static_cast<const bf16_t*>(k_pool)[base + kpage_offset(slot, dd)];
+            static_cast<bf16_t*>(v_dst)[dst] = static_cast<const bf16_t*>(v_pool)[base + vpage_offset(slot, dd)];
+        } else {
+            static_cast<float*>(k_dst)[dst] = static_cast<const float*>(k_pool)[base + (size_t)slot * D + dd];
+            static_cast<float*>(v_dst)[dst] = static_cast<const float*>(v_pool)[base + (size_t)slot * D + dd];
+        }
+    }
+}
+
 // row t of an activation buffer -> row 0 of another one
 template <bool BF16>
 __global__ __launch_bounds__(256) void copy_act_row_kernel(const void* __restrict__ X, size_t plane, int t, void* __restrict__ X1,
@@ -622,6 +646,19 @@ int sled_launch_kv_ingest(const sled_model* m, const sled_kvpool* p, const void*
     else
         hipLaunchKernelGGL(kv_ingest_kernel<false>, grid, dim3(256), 0, st, k_src, v_src, n_tokens, m->s.n_kv_heads,
                            m->s.head_dim, p->len_dev, req_id, pages_dev, p->k_pool, p->v_pool, p->n_pages);
+    SLED_LAUNCH_CHECK();
+    return SLED_OK;
+}
+
+int sled_launch_kv_export(const sled_model* m, const sled_kvpool* p, void* k_dst, void* v_dst, int first, int n_tokens,
+                          const int32_t* pages_dev, hipStream_t st) {
+    dim3 grid(n_tokens, m->s.n_layers);
+    if (m->s.dtype == SLED_BF16)
+        hipLaunchKernelGGL(kv_export_kernel<true>, grid, dim3(256), 0, st, k_dst, v_dst, first, n_tokens, m->s.n_kv_heads,
+                           m->s.head_dim, pages_dev, p->k_pool, p->v_pool, p->n_pages);
+    else
+        hipLaunchKernelGGL(kv_export_kernel<false>, grid, dim3(256), 0, st, k_dst, v_dst, first, n_tokens, m->s.n_kv_heads,
+                           m->s.head_dim, pages_dev, p->k_pool, p->v_pool, p->n_pages);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
 }

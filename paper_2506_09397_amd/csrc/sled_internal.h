@@ -263,6 +263,8 @@ int sled_launch_swiglu_reduce(const sled_model* m, const float* gu, int n_split,
                               hipStream_t st);
 int sled_launch_kv_ingest(const sled_model* m, const sled_kvpool* p, const void* k_src, const void* v_src, int n_tokens,
                           int req_id, const int32_t* pages_dev, hipStream_t st);
+int sled_launch_kv_export(const sled_model* m, const sled_kvpool* p, void* k_dst, void* v_dst, int first, int n_tokens,
+                          const int32_t* pages_dev, hipStream_t st);
 int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int32_t* add_dev, const int32_t* accept_dev,
                         int B, hipStream_t st);
 

@@ -62,6 +62,14 @@ class Verifier:
     def commit(self, reqs: Sequence[int], accept_len: torch.Tensor) -> None:
         sled.sled_kv_append(self.pool, reqs, accept_len=accept_len)
 
+    def read_kv(self, req: int, first_token: int, n_tokens: int):
+        """K and V of positions first_token .. first_token + n_tokens - 1 as stored, each [n_layers, n_tokens, n_kv_heads, head_dim]."""
+        s = self.shape
+        K = torch.empty(s.n_layers, n_tokens, s.n_kv_heads, s.head_dim, dtype=s.torch_dtype, device="cuda")
+        V = torch.empty_like(K)
+        sled.sled_kv_read(self.pool, req, first_token, n_tokens, K, V)
+        return K, V
+
     def lengths(self, reqs: Sequence[int]) -> List[int]:
         return sled.sled_kvpool_lengths(self.pool, reqs)
 

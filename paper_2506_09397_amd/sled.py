@@ -31,7 +31,7 @@ EXPORTS = [
     "sled_model_create", "sled_model_load", "sled_model_destroy", "sled_model_set_batch_invariant",
     "sled_model_set_weight_bits",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
-    "sled_kv_append", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
+    "sled_kv_append", "sled_kv_read", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
     "sled_accept_workspace_bytes", "sled_accept", "sled_accept_static", "sled_accept_sparse", "sled_row_confidence", "sled_profile_enable", "sled_profile_read",
     "sled_strerror", "sled_last_error",
 ]
@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
     L.sled_kvpool_lengths.argtypes = [vp, C.c_int, ip, ip, vp]
     L.sled_kvpool_destroy.argtypes = [vp]
     L.sled_kv_append.argtypes = [vp, C.c_int, ip, ip, C.POINTER(vp), C.POINTER(vp), vp, vp]
+    L.sled_kv_read.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]
     L.sled_verify_workspace_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int64]
     L.sled_verify_workspace_bytes.restype = C.c_size_t
     L.sled_verify_batch.argtypes = [vp, vp, C.c_int, ip, ip, vp, vp, vp, C.c_size_t, vp]
@@ -171,6 +172,10 @@ def sled_kv_append(pool: int, req_ids: Sequence[int], n_tokens: Optional[Sequenc
     kp = (C.c_void_p * B)(*[_ptr(t) for t in k_src])
     vp = (C.c_void_p * B)(*[_ptr(t) for t in v_src])
     _check(lib().sled_kv_append(pool, B, _ints(req_ids), _ints(n_tokens), kp, vp, None, _stream()))
+
+
+def sled_kv_read(pool: int, req_id: int, first_token: int, n_tokens: int, k_dst: torch.Tensor, v_dst: torch.Tensor) -> None:
+    _check(lib().sled_kv_read(pool, int(req_id), int(first_token), int(n_tokens), _ptr(k_dst), _ptr(v_dst), _stream()))
 
 
 # ---------------------------------------------------------------------------------------- step

@@ -4,10 +4,10 @@ drafts; Sec. 3.4: one batch of heterogeneous requests): the library's logits aga
   * Llama-3-8B shape, 32 layers, the batch of 16 that bench.py times: every row of every request;
   * the same model with the 64-request heterogeneous mix: four requests (the 8192-token one among them), then
     speculative-sampling acceptance over full-vocabulary draft probabilities on the library's own logits;
-  * Llama-3-70B shape at the depth the oracle can score in about three minutes (20 of the 80 layers: both sides are
-    built with 20 layers followed by the final norm and the LM head), batch of 32, one request scored.
+  * Llama-3-70B shape at its full 80 layers, batch of 32, one request scored, with the cache-rounding decisions taken
+    as the library took them and audited (see the test).
 
-These are the slow tests of the suite (the oracle widens every layer to float64): about five minutes together.
+These are the slow tests of the suite (the oracle widens every layer to float64): about six minutes together.
 """
 import time
 
@@ -142,22 +142,49 @@ def test_llama8b_hetero64_32_layers_sampled_requests_and_sampling_acceptance(say
     v.destroy()
 
 
-def test_llama70b_shape_20_of_80_layers_one_request(say):
-    """The 70B layer shape at depth 20 (model and oracle both built with 20 layers; the full 80 would cost the oracle
-    about ten minutes): the batch of 32 as benchmarked, one request scored."""
-    shape = synth.scaled_shape(synth.SHAPES["llama70b"], n_layers=20)
+def test_llama70b_b32_80_layers_one_request(say):
+    """Llama-3-70B shape at its full depth of 80 layers, the batch of 32 as benchmarked, one request scored.
+
+    On this shape the rounding of new keys and values to the bf16 cache decides more than the tolerance: a value that
+    the library computes (float32 sums) a hair to the other side of a rounding midpoint than the oracle (float64) is
+    stored one bf16 step away, and a handful of such flips per layer move the final logits by 2e-2 and more -- for any
+    implementation that does not reproduce the oracle's sums to the last bit (measured on the oracle itself: relative
+    noise of 1e-5 on its projection outputs moves the logits of this shape by 3e-2 within 12 layers).  So the decision
+    is taken as the library took it (the oracle attends to the numbers the library stored, read back through
+    sled_kv_read) and audited: every stored number must be a correct rounding of a value within 1e-3 of its head
+    vector's root mean square of the oracle's exact value (a twentieth of the relative tolerance on the logits).
+    Everything else is the plain definition.  The error against the oracle left to its own rounding decisions is reported beside it."""
+    shape = synth.SHAPES["llama70b"]
     batch = synth.draw_batch("b32", shape.vocab, seed=0)
-    sample = [int(np.argsort(batch.ctx_len)[len(batch.ctx_len) // 2])]
-    say("\n70B shape, 20 layers, batch of 32: building the model")
-    v, w, reqs, KV = _setup(shape, batch, 0, set(sample))
+    i = int(np.argsort(batch.ctx_len)[len(batch.ctx_len) // 2])
+    say("\n70B shape, 80 layers, batch of 32: building the model (141 GB of weights)")
+    v, w, reqs, KV = _setup(shape, batch, 0, {i})
     tokens = torch.from_numpy(batch.tokens).cuda()
     got = v.verify(reqs, batch.k, tokens).cpu().numpy()
     assert np.isfinite(got).all()
+    n = batch.k[i] + 1
+    Ks, Vs = v.read_kv(reqs[i], batch.ctx_len[i], n)          # the rows the step staged behind the context
     offs = batch.row_offsets()
-    want, dt = _oracle_rows(shape, w, batch, KV, sample, say=say)
-    i = sample[0]
-    err = float(np.abs(got[offs[i]: offs[i + 1]] - want[0]).max())
-    say(f"70B shape, 20 layers, b32 (T={batch.T}): request {i} (L={batch.ctx_len[i]}, k={batch.k[i]}): "
-        f"max |logit error| {err:.3e}, logit std {want[0].std():.3f}; oracle {dt:.0f} s")
+    oreq = {"tokens": batch.tokens[offs[i]: offs[i + 1]], "K": synth.as_f64(KV[i][0]), "V": synth.as_f64(KV[i][1])}
+    say("  library step done; oracle, 80 layers, attending to the numbers the library stored")
+    t0 = time.time()
+
+    def progress(l):
+        if l % 8 == 7:
+            say(f"  oracle: layer {l + 1} of {shape.n_layers} done, {time.time() - t0:.0f} s")
+
+    om = oracle_model(shape, w, cache=False)
+    res = O.verify_batch(om, [dict(oreq, K_stored=synth.as_f64(Ks), V_stored=synth.as_f64(Vs))], progress)[0]
+    err = float(np.abs(got[offs[i]: offs[i + 1]] - res["logits"]).max())
+    au = res["audit"]
+    say(f"70B, 80 layers, b32 (T={batch.T}): request {i} (L={batch.ctx_len[i]}, k={batch.k[i]}): max |logit error| {err:.3e} "
+        f"(logit std {res['logits'].std():.3f}); stored K/V: {au['flips']} of {au['elements']} differ from the oracle's own "
+        f"rounding, worst {au['max_excess']:.2e} of the vector's rms beyond a correct rounding; oracle {time.time() - t0:.0f} s")
+    assert au["max_excess"] < 1e-3
     assert err < TOL_BF16
+    say("  oracle again, left to its own rounding decisions")
+    plain = O.verify_batch(om, [oreq], progress)[0]
+    err_plain = float(np.abs(got[offs[i]: offs[i + 1]] - plain["logits"]).max())
+    say(f"  against the oracle's own rounding decisions: max |logit error| {err_plain:.3e}")
+    assert err_plain < 0.25          # sanity only: this distance is the flips' doing, see above
     v.destroy()

@@ -105,3 +105,39 @@ def test_page_bounds_tighten_without_a_sync():
             torch.cuda.current_stream().synchronize()                # time passes (the copies land); no pool call waits
     assert v.lengths([r]) == [50]
     v.destroy()
+
+
+@pytest.mark.parametrize("kind", ["tiny", "tiny_bf16"])
+def test_kv_read_returns_what_append_and_verify_wrote(kind):
+    """sled_kv_read against both ways in: context appended from outside comes back bit for bit, and the rows a verify
+    stages are the oracle's new K/V (float32 model: to round-off; bf16 model: the same bf16 numbers, up to a rare
+    value that sits within round-off of a rounding midpoint and is stored one step away)."""
+    shape = synth.SHAPES[kind]
+    w = synth.SynthWeights(shape, seed=8, device="cuda", std=0.05, gain_jitter=0.1)
+    v = Verifier(shape, w, 32, 2, 2, 256)
+    om = oracle_model(shape, w)
+    L = 21
+    K, V = synth.context_kv(shape, L, seed=3, req=0, device="cuda")
+    r = v.open()
+    v.append_context([r], [K], [V])
+    Kb, Vb = v.read_kv(r, 0, L)
+    assert torch.equal(Kb, K) and torch.equal(Vb, V)
+    Kb, Vb = v.read_kv(r, 5, 9)
+    assert torch.equal(Kb, K[:, 5:14]) and torch.equal(Vb, V[:, 5:14])
+    toks = [int(t) for t in synth.context_tokens(7, shape.vocab, seed=4)]
+    v.verify([r], [6], _dev(toks))
+    Kn, Vn = v.read_kv(r, L, 7)
+    req = {"tokens": toks, "K": synth.as_f64(K), "V": synth.as_f64(V)}
+    if kind == "tiny":
+        want = O.verify_batch(om, [req])[0]
+        assert np.abs(synth.as_f64(Kn) - want["K_new"]).max() < 1e-5 and np.abs(synth.as_f64(Vn) - want["V_new"]).max() < 1e-5
+    else:
+        # every stored number is a correct rounding of a value within 1e-4 of its head vector's rms of what the oracle
+        # computes when it attends to the same stored numbers; few differ from the oracle's own rounding
+        au = O.verify_batch(om, [dict(req, K_stored=synth.as_f64(Kn), V_stored=synth.as_f64(Vn))])[0]["audit"]
+        print(f"{kind}: {au['flips']} of {au['elements']} stored numbers differ from the oracle's rounding, "
+              f"worst {au['max_excess']:.2e} of the vector's rms beyond a correct rounding")
+        assert au["max_excess"] < 1e-4 and au["flips"] < 0.02 * au["elements"] and au["elements"] == 2 * Kn.numel()
+    with pytest.raises(sled.SledError):
+        v.read_kv(r, 30, 10)                 # past the request's pages
+    v.destroy()

@@ -132,7 +132,7 @@ def test_serving_loop_with_speculative_sampling(top):
     n_sub = n_req = 0
     for s in steps:
         q = s["q"] if s["q"] is not None else np.zeros((0, shape.vocab))      # a step of plain decode requests has no drafts
-        want = O.accept_batch("sample", s["k"], s["logits"], s["tokens"], q, s["u_acc"], s["u_smp"], temperature=0.9)
+        want = O.accept_batch("sample", s["k"], s["logits"], s["tokens"], q, s["u_acc"], s["u_smp"], temperature=float(np.float32(0.9)))
         for i, r in enumerate(want):
             n_req += 1
             if r["margin_acc"] > MARGIN_ACC and r["margin_cdf"] > MARGIN_CDF:

@@ -268,6 +268,45 @@ def test_kv_bf16_rounds_what_enters_the_cache_and_nothing_else():
     assert np.array_equal(outs[0], outs[1])
 
 
+def test_stored_cache_numbers_replace_the_rounding_decision_and_are_audited():
+    """The oracle can take the cache-rounding decision as a cache under test took it: given the bf16 numbers stored
+    for the new rows it attends to those and reports how far they are from the exact values.  Its own numbers change
+    nothing and audit clean; numbers one bf16 step off change the logits and show in the audit; one pass still equals
+    row-by-row verification on the same stored numbers."""
+    shape = synth.scaled_shape(SMALL, dtype="bf16")
+    w = synth.SynthWeights(shape, seed=6, std=0.2)
+    om = oracle_model(shape, w, "kv_bf16")
+    ctx_kv = synth.context_kv(shape, 7, seed=2, req=0)
+    toks = [int(t) for t in synth.context_tokens(4, shape.vocab, seed=9)]
+    base = {"tokens": toks, "K": synth.as_f64(ctx_kv[0]), "V": synth.as_f64(ctx_kv[1])}
+    plain = O.verify_batch(om, [base])[0]
+    same = O.verify_batch(om, [dict(base, K_stored=plain["K_new"], V_stored=plain["V_new"])])[0]
+    assert np.array_equal(same["logits"], plain["logits"])
+    assert same["audit"]["flips"] == 0 and same["audit"]["max_excess"] <= 0.0 and same["audit"]["elements"] == 2 * plain["K_new"].size
+    # the spacing helper against torch's bf16 grid (bf16-representable, positive values: the step to the next one up)
+    x = np.array([1.0, 1.5, 1.984375, 2.0, 0.30078125, 5.0, 0.0009765625, 448.0])
+    xb = torch.from_numpy(x).to(torch.bfloat16)
+    assert np.array_equal(xb.to(torch.float64).numpy(), x)
+    nxt = torch.nextafter(xb, torch.full_like(xb, float("inf")))
+    assert np.array_equal(O.bf16_ulp(x), (nxt.to(torch.float64) - xb.to(torch.float64)).numpy())
+    assert np.array_equal(O.bf16_ulp(-x), O.bf16_ulp(x)) and np.array_equal(O.bf16_ulp(x * 1.003), O.bf16_ulp(x))
+    # three values moved by one bf16 step: used as given, and seen
+    K2 = plain["K_new"].copy()
+    for (l, j, g, d) in ((0, 1, 0, 3), (1, 2, 1, 5), (0, 3, 1, 0)):
+        K2[l, j, g, d] += O.bf16_ulp(K2[l, j, g, d])
+    moved = O.verify_batch(om, [dict(base, K_stored=K2, V_stored=plain["V_new"])])[0]
+    assert np.array_equal(moved["K_new"], K2) and not np.array_equal(moved["logits"], plain["logits"])
+    # (a whole step beyond a correct rounding, on an element of about the vector's size: 2^-8 .. 2^-7 of it and more)
+    assert moved["audit"]["flips"] >= 3 and 1e-3 < moved["audit"]["max_excess"] < 0.5
+    # rows of one pass attend to the stored numbers of the earlier rows, exactly as a later pass would
+    K, V, rows = base["K"], base["V"], []
+    for j, t in enumerate(toks):
+        r = O.verify_batch(om, [{"tokens": [t], "K": K, "V": V, "K_stored": K2[:, j: j + 1], "V_stored": plain["V_new"][:, j: j + 1]}])[0]
+        rows.append(r["logits"][0])
+        K, V = np.concatenate([K, K2[:, j: j + 1]], axis=1), np.concatenate([V, plain["V_new"][:, j: j + 1]], axis=1)
+    assert np.abs(np.stack(rows) - moved["logits"]).max() < 1e-12 * np.abs(moved["logits"]).max()
+
+
 def test_pair_contract_stays_within_2_to_minus_12_of_the_parity_definition():
     """The bf16-pair storage study ("bf16x2": what the HIP library stores between its kernels) against the parity
     definition, on the tiny bf16 shape and on two layers of the 8B shape: at most 2^-12 of the largest logit

@@ -87,7 +87,7 @@ for _n in ("attn_unscaled", "attn_off_by_one", "attn_no_causal", "attn_head_inte
 
 def _layer_rows_variant(round_q, round_v, round_before_attention):
     """layer_rows of the bf16-cache definition with the cache rounding misplaced."""
-    def layer_rows(model, W, h, positions, K_ctx, V_ctx):
+    def layer_rows(model, W, h, positions, K_ctx, V_ctx, stored=None, audit=None):
         cache_round = O.bf16_round if model.round_points != "exact" else (lambda a: a)
         n = h.shape[0]
         Hq, Hkv, D = model.n_q_heads, model.n_kv_heads, model.head_dim
