@@ -21,10 +21,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# L2 fetch + write-back bytes per projection launch (FETCH_SIZE and WRITE_SIZE of rocprofv3, each scaled by
-# what the counter reads for a 1 GiB copy; profiles/verify_step_llama8b_b16_hbm_traffic.txt).  Taken with the
-# projection kernel as it stands; to be reset to None whenever that kernel changes.
+# L2 fetch + write-back bytes per projection launch: a STORED counter figure, not read in this run (FETCH_SIZE and
+# WRITE_SIZE of rocprofv3 need runs of their own; each is scaled by what the counter reads for a 1 GiB copy;
+# profiles/verify_step_llama8b_b16_hbm_traffic.txt gives the commands and the table).  Taken with gemm_bf16_kernel as
+# it stands in csrc/gemm.hip (retaken after the last change to that file's kernel code: 149.9 MB both times); to be
+# reset to None whenever that kernel changes.
 MEASURED_TRAFFIC = {"llama8b_b16": 149.9e6}
+TRAFFIC_NOTE = "stored rocprofv3 FETCH_SIZE+WRITE_SIZE figure for gemm_bf16_kernel (profiles/verify_step_llama8b_b16_hbm_traffic.txt), not measured in this run"
 CPU_SAMPLE_REQUESTS, CPU_SAMPLE_LAYERS = 16, 24   # the oracle's bounded sample (about 10-20 s of CPU work)
 
 
@@ -160,13 +163,15 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "gemm_bf16_kernel (projection GEMMs, weight stream)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None if (w8 or args.batch_invariant) else MEASURED_TRAFFIC.get(args.workload),
+        "traffic": (traffic := None if (w8 or args.batch_invariant) else MEASURED_TRAFFIC.get(args.workload)),
+        "traffic_source": TRAFFIC_NOTE if traffic is not None else None,
         "launches_per_step": proj_launches, "avg_launch_us": round(proj_ms * 1e3 / max(proj_launches, 1), 2),
         "bytes_per_launch": round(weight_bytes / max(proj_launches, 1)),
     }
     step_bytes = weight_bytes + kv_bytes + logits_bytes
     copy_gbs = copy_bandwidth_gbs()
     breakdown = {
+        "verify_launches_per_step": sum(n) // psteps,
         "proj_ms": round(proj_ms, 4), "attn_ms": round(ms[sled.PROF_ATTN] / psteps, 4),
         "rows_ms": round(ms[sled.PROF_ROWS] / psteps, 4),
         "attn_GBps": round(kv_bytes / max(ms[sled.PROF_ATTN] / psteps, 1e-9) / 1e6, 1),

@@ -169,9 +169,12 @@ def weights_sweep(seed=0):
 
 
 if __name__ == "__main__":
+    which = sys.argv[1] if len(sys.argv) > 1 else ""
+    if which not in ("batch", "rows", "prefill", "weights"):
+        print(__doc__)
+        sys.exit(0 if which in ("-h", "--help") else 2)
     sled.lib()
     torch.cuda.set_device(0)
-    which = sys.argv[1] if len(sys.argv) > 1 else ""
     if which == "batch":
         batch_sweep()
     elif which == "rows":
@@ -181,8 +184,5 @@ if __name__ == "__main__":
         rows_sweep(sizes=tuple(int(a) for a in args) or (128, 256, 512, 1024, 2048, 4096), kind=kind)
     elif which == "prefill":
         prefill_sweep()
-    elif which == "weights":
-        weights_sweep()
     else:
-        print(__doc__)
-        sys.exit(2)
+        weights_sweep()
