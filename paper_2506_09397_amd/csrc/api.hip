@@ -640,30 +640,82 @@ struct ws_plan {
 };
 
 // Attention work list.  A work item is a run of pages of one (request, kv head), processed by one
-// workgroup; the chip wants about one item per CU (a multiple of 256 when there are more (request,
-// kv head) pairs than that), all of similar size.  Returns the largest number of pages an item may
-// hold so that the item count stays within that cap; each pair then splits its pages evenly.
-constexpr int ATTN_CUS = 256;
+// workgroup.  Workgroups are handed to the eight XCDs round robin in launch order and start as CUs become free, so
+// the launch takes as long as the busiest CU: one long request left whole can hold the launch for several times the
+// average (a 64-request mix with contexts of 128 to 8192 tokens: 512 pages in one item against 243 per CU).  The
+// pages-per-item bound is therefore chosen by playing the launch through on the host for a handful of candidate
+// bounds and taking the one that finishes first; each (request, kv head) then splits its pages evenly.
+//   - at least 32 pages (eight rounds of the page loop) per item and at most eight items per (request, kv head):
+//     beyond that the hand-over between the items of a pair -- the last one to arrive reads the others' states --
+//     costs more than the extra workgroups save;
+//   - at most ATTN_ROUNDS items per CU beyond one per pair (this bounds the workspace);
+//   - an item costs its pages plus a fixed part (prologue, folds, output, and that a CU which works alone at the end
+//     of a launch streams faster than one of 256), and a little more when its pair is split (stored state, arrival
+//     counter).  The two constants were fitted on the 64-request mix, the 70B batch and the 16-request batch: 16/8,
+//     32/12, 48/16, 64/16, 96/24 were tried; 48/16 and 64/16 did best on the mix, all but the first left the others alone.
+constexpr int ATTN_CUS = 256, ATTN_XCDS = 8, ATTN_ROUNDS = 4;
+constexpr int ATTN_ITEM_FIXED = 48, ATTN_ITEM_SPLIT = 16;   // in units of one page's streaming time
 constexpr int SLED_FIXED_CHUNK_PAGES = 48;  // 768 tokens; divisible by 4, 3 and 2 page groups
-int attn_item_cap(int B, int Hkv) { return ATTN_CUS * ((B * Hkv + ATTN_CUS - 1) / ATTN_CUS); }
-int attn_pages_per_item(const std::vector<int>& np, int Hkv) {
-    int64_t total = 0;
+int attn_item_cap(int B, int Hkv) { return ATTN_ROUNDS * ATTN_CUS * ((B * Hkv + ATTN_CUS - 1) / ATTN_CUS); }
+int attn_chunk(int np, int tgt) { return ceil_div(np, ceil_div(np, tgt)); }   // even split of a block's pages
+// when the last workgroup ends if the blocks, in the order given, are cut into items of at most tgt pages
+int64_t attn_makespan(const std::vector<int>& np, const std::vector<int>& order, int Hkv, int tgt) {
+    constexpr int PER = ATTN_CUS / ATTN_XCDS;
+    // per XCD a min-heap of the times its CUs become free; workgroup k goes to XCD k % 8
+    static thread_local std::vector<int64_t> heap;
+    heap.assign((size_t)ATTN_CUS, 0);
+    auto cmp = [](int64_t a, int64_t b) { return a > b; };
+    int64_t k = 0, end = 0;
+    for (int i : order) {
+        const int n = np[i], chunk = attn_chunk(n, tgt), pieces = ceil_div(n, chunk);
+        for (int g = 0; g < Hkv; g++)
+            for (int p0 = 0; p0 < n; p0 += chunk, k++) {
+                int64_t* h = heap.data() + (k % ATTN_XCDS) * PER;
+                std::pop_heap(h, h + PER, cmp);
+                h[PER - 1] += std::min(chunk, n - p0) + ATTN_ITEM_FIXED + (pieces > 1 ? ATTN_ITEM_SPLIT : 0);
+                end = std::max(end, h[PER - 1]);
+                std::push_heap(h, h + PER, cmp);
+            }
+    }
+    return end;
+}
+int attn_pages_per_item(const std::vector<int>& np, const std::vector<int>& order, int Hkv) {
     int longest = 1;
-    for (int n : np) {
-        total += n;
-        longest = std::max(longest, n);
+    for (int n : np) longest = std::max(longest, n);
+    const int base = ATTN_CUS * (((int)np.size() * Hkv + ATTN_CUS - 1) / ATTN_CUS);
+    const int lo = std::min(longest, std::max(32, ceil_div(longest, 8)));
+    auto items = [&](int tgt) {
+        int64_t k = 0;
+        for (int n : np) k += (int64_t)Hkv * ceil_div(n, tgt);
+        return k;
+    };
+    // candidates: the smallest bounds that give at most 1, 2, .. ATTN_ROUNDS items per CU (whole rounds of workgroups
+    // of similar size), and a coarse geometric ladder between the limits
+    int cand[ATTN_ROUNDS + 16], n_cand = 0;
+    for (int c = 1; c <= ATTN_ROUNDS; c++) {
+        int a = lo, b = longest;   // items() does not grow with the bound
+        while (a < b) {
+            const int mid = (a + b) / 2;
+            if (items(mid) <= (int64_t)c * base) b = mid;
+            else a = mid + 1;
+        }
+        cand[n_cand++] = a;
     }
-    const int cap = attn_item_cap((int)np.size(), Hkv);
-    // at least 32 pages (eight rounds of the page loop) per item and at most eight items per (request, kv head):
-    // beyond that the hand-over between the items of a pair -- the last one to arrive reads the others' states, a round
-    // trip to memory for every four of them -- costs more than the extra workgroups save
-    int tgt = (int)std::max<int64_t>(std::max(32, ceil_div(longest, 8)), (total * Hkv + cap - 1) / cap);
-    for (; tgt < longest; tgt++) {
-        int64_t items = 0;
-        for (int n : np) items += (int64_t)Hkv * ceil_div(n, tgt);
-        if (items <= cap) break;
+    for (int tgt = lo; n_cand < ATTN_ROUNDS + 15; tgt += std::max(8, tgt / 3)) {
+        cand[n_cand++] = std::min(tgt, longest);
+        if (tgt >= longest) break;
     }
-    return tgt;
+    int best = longest;
+    int64_t best_end = -1;
+    for (int c = 0; c < n_cand; c++) {
+        if (items(cand[c]) > attn_item_cap((int)np.size(), Hkv)) continue;
+        const int64_t end = attn_makespan(np, order, Hkv, cand[c]);
+        if (best_end < 0 || end < best_end || (end == best_end && cand[c] > best)) {   // ties: fewer items
+            best_end = end;
+            best = cand[c];
+        }
+    }
+    return best;
 }
 
 ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
@@ -759,24 +811,29 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     // Pages per attention work item.  Normally whatever spreads this batch evenly over the CUs; for a
     // batch-invariant model a fixed run of pages, so that the keys of a request are always summed in the same
     // groups (a multiple of every page-group count the kernel uses).
-    const int tgt = m->batch_invariant ? 0 : attn_pages_per_item(np_all, Hkv);
+    // Blocks with the most pages first: what is left for the end of the launch is then small.  (Batch-invariant:
+    // the order of the batch, nothing may depend on the other requests.)
+    std::vector<int> order(B);
+    for (int i = 0; i < B; i++) order[i] = i;
+    if (!m->batch_invariant) std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return np_all[a] > np_all[b]; });
+    const int tgt = m->batch_invariant ? 0 : attn_pages_per_item(np_all, order, Hkv);
     std::vector<int32_t> work;
-    std::vector<int32_t> cu_work(B * Hkv + 1);
-    for (int i = 0; i < B; i++) {
+    std::vector<int32_t> cu_work(2 * B * Hkv);   // first and end item of (block, kv head), by block and head
+    for (int i : order) {
         const int np = np_all[i];
-        const int chunk = m->batch_invariant ? SLED_FIXED_CHUNK_PAGES : ceil_div(np, ceil_div(np, tgt));  // even split of this block's pages
+        const int chunk = m->batch_invariant ? SLED_FIXED_CHUNK_PAGES : attn_chunk(np, tgt);
         for (int g = 0; g < Hkv; g++) {
-            cu_work[i * Hkv + g] = (int)(work.size() / 4);
+            cu_work[2 * (i * Hkv + g)] = (int)(work.size() / 4);
             for (int p0 = 0; p0 < np; p0 += chunk) {
                 work.push_back(i);
                 work.push_back(g);
                 work.push_back(p0);
                 work.push_back(std::min(chunk, np - p0));
             }
+            cu_work[2 * (i * Hkv + g) + 1] = (int)(work.size() / 4);
         }
     }
     const int n_work = (int)(work.size() / 4);
-    cu_work[B * Hkv] = n_work;
     // query tiles follow the longest block of the batch -- or, batch-invariant, of the model: the tile count sets
     // the number of page groups a workgroup splits its pages over
     const int QT = std::max(1, ceil_div(G * (m->batch_invariant ? s.k_max + 1 : nmax), 16));

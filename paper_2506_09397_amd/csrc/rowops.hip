@@ -239,8 +239,8 @@ __global__ void attn_plan_kernel(sled_step_meta meta, const int32_t* __restrict_
     r[5] = meta.k[b] + 1;
     r[6] = meta.cu_rows[b];
     r[7] = meta.cu_pages[b];
-    r[8] = meta.cu_work[b * Hkv + g];
-    r[9] = meta.cu_work[b * Hkv + g + 1];
+    r[8] = meta.cu_work[2 * (b * Hkv + g)];
+    r[9] = meta.cu_work[2 * (b * Hkv + g) + 1];
     r[10] = r[11] = 0;
 }
 

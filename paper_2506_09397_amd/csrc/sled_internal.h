@@ -222,7 +222,7 @@ struct sled_step_meta {
     const int32_t* row_j;      // [T]   index of the row inside its request
     const int32_t* pages;      // [sum pages]
     const int32_t* work;       // [n_work * 4]  attention work items: batch index, kv head, first page, n pages
-    const int32_t* cu_work;    // [B*Hkv + 1]   first work item of each (batch index, kv head)
+    const int32_t* cu_work;    // [B*Hkv][2]    first and end work item of each (batch index, kv head)
     int B, T, n_work;
 };
 

@@ -20,7 +20,8 @@ from paper_2506_09397_amd import sled, synth
 from gpu_common import build_verifier, MARGIN_ACC, MARGIN_CDF
 from helpers import oracle_model
 
-pytestmark = [pytest.mark.gpu, pytest.mark.slow]
+# the oracle passes take minutes: these tests carry their own time limit, whatever --timeout the run was given
+pytestmark = [pytest.mark.gpu, pytest.mark.slow, pytest.mark.timeout(600)]
 
 TOL_BF16 = 2e-2
 
