@@ -902,8 +902,11 @@ int run_forward(sled_model* m, sled_kvpool* p, const std::vector<step_entry>& en
     // distance between the hi and lo planes of each activation buffer (bf16 models)
     const size_t pl_d = bf ? wp.T_alloc * (size_t)d : 0, pl_hd = bf ? wp.T_alloc * (size_t)HD : 0,
                  pl_f = bf ? wp.T_alloc * (size_t)F : 0;
-    const sled_gemm_plan g_qkv = sled_gemm_make_plan(m, m->n_qkv, d, false), g_o = sled_gemm_make_plan(m, d, HD, false),
-                         g_dn = sled_gemm_make_plan(m, d, F, false), g_lm = sled_gemm_make_plan(m, s.vocab, d, true);
+    // K slices: the model's plan (which sized the workspace), thinned out for this step's number of rows
+    const sled_gemm_plan g_qkv = sled_gemm_plan_rows(m, sled_gemm_make_plan(m, m->n_qkv, d, false), m->n_qkv, d, T_pad),
+                         g_o = sled_gemm_plan_rows(m, sled_gemm_make_plan(m, d, HD, false), d, HD, T_pad),
+                         g_dn = sled_gemm_plan_rows(m, sled_gemm_make_plan(m, d, F, false), d, F, T_pad),
+                         g_lm = sled_gemm_make_plan(m, s.vocab, d, true);
     // gate/up applies SwiGLU in its epilogue when it runs unsplit; otherwise (and for fp32 models) a row
     // kernel reduces the K slices and applies it
     sled_gemm_plan g_gu = sled_gemm_make_plan(m, 2 * F, d, false);

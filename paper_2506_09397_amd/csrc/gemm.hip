@@ -552,6 +552,30 @@ sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs
     return p;
 }
 
+// With more than one block of rows (the wide shape) the workgroups of a projection are column blocks x row blocks x
+// K slices, and what counts is how many rounds of 256 they make: 288 workgroups take as long as 512.  Fewer K slices
+// also mean fewer partial sums to write and to read back.  Estimated time of a launch, in microseconds: rounds x
+// (fixed part + stages per workgroup x time per stage) + bytes of partial sums written and read / rate.
+sled_gemm_plan sled_gemm_plan_rows(const sled_model* m, sled_gemm_plan base, int N, int K, int T_pad) {
+    if (m->s.dtype != SLED_BF16 || m->batch_invariant || base.split <= 1 || T_pad / 32 <= 4) return base;
+    constexpr double FIXED_US = 9.0, STAGE_US = 0.8, PARTIAL_BYTES_PER_US = 4.0e6;
+    const int n_col = (N / 32 + WIDE_CG * NW - 1) / (WIDE_CG * NW), zb = (T_pad / 32 + 3) / 4;
+    const int stages = K / 16 / WIDE_KG;
+    sled_gemm_plan best = base;
+    double best_t = -1.0;
+    for (int sp = base.split; sp >= 1; sp /= 2) {
+        if ((K / 16) % (sp * NARROW_KG * NBUF)) continue;
+        const int64_t wgs = (int64_t)n_col * zb * sp;
+        const double t = (double)((wgs + 255) / 256) * (FIXED_US + (double)(stages / sp) * STAGE_US) +
+                         2.0 * sp * (double)T_pad * N * 4.0 / PARTIAL_BYTES_PER_US;
+        if (best_t < 0 || t < best_t) {
+            best_t = t;
+            best.split = sp;
+        }
+    }
+    return best;
+}
+
 int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const void* scale, int T, int T_pad,
                      int N, int K, int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane,
                      int F_act, hipStream_t st) {

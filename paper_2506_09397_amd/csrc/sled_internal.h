@@ -274,6 +274,9 @@ struct sled_gemm_plan {
     int split;   // K slices
 };
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
+// the plan for a step of T_pad rows: never more K slices than `base` (which sizes the workspace), fewer where several
+// blocks of rows already give every CU a workgroup
+sled_gemm_plan sled_gemm_plan_rows(const sled_model* m, sled_gemm_plan base, int N, int K, int T_pad);
 // `scale`: the scales of an 8-bit or 4-bit weight matrix (models with such weights), else nullptr
 int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const void* scale, int T, int T_pad,
                      int N, int K, int epilogue, sled_gemm_plan plan, float* out_f32, void* out_act, size_t act_plane,
