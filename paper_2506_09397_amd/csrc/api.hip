@@ -738,9 +738,9 @@ ws_plan plan_workspace(const sled_model* m, int T, int64_t n_work, int QT) {
     w.q = take(planes * T_alloc * HD * m->elem);
     w.x1 = take(planes * 32 * d * m->elem);  // one 32-row tile: the single row whose logits a prompt asks for
     size_t part = 0;
-    part = std::max(part, (size_t)sled_gemm_make_plan(m, m->n_qkv, s.d_model, false).split * T_pad * m->n_qkv);
-    part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, (int)HD, false).split * T_pad * d);
-    part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, s.d_ffn, false).split * T_pad * d);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, m->n_qkv, s.d_model, false).cap * T_pad * m->n_qkv);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, (int)HD, false).cap * T_pad * d);
+    part = std::max(part, (size_t)sled_gemm_make_plan(m, s.d_model, s.d_ffn, false).cap * T_pad * d);
     part = std::max(part, (size_t)sled_gemm_make_plan(m, 2 * s.d_ffn, s.d_model, false).split * T_pad * 2 * F);
     w.partial = take(part * sizeof(float));
     w.cs = take((size_t)T * s.head_dim * sizeof(float));

@@ -122,7 +122,7 @@ template <int MT, int EPI, int KG, int CG, int WB>
 __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __restrict__ Xp, size_t x_plane,
                                                                const bf16_t* __restrict__ Wp,
                                                                const void* __restrict__ scale_v, int NT, int KS,
-                                                               int ks_per_split, int n_col, int n_split, int n_zb,
+                                                               int n_col, int n_split, int n_zb,
                                                                int T, int T_pad, int N, float* __restrict__ out,
                                                                bf16_t* __restrict__ out_act, size_t act_plane,
                                                                int F_act) {
@@ -155,8 +155,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_bf16_kernel(const bf16_t* __r
         bx = t % n_col;
         by = t / n_col;
     }
-    const int ks_begin = by * ks_per_split;
-    const int n_stage = ks_per_split / KG;  // a positive multiple of NBUF (the host picks K slices accordingly)
+    // K slice `by`: K in units of KG * NBUF k-steps (one trip of the stage loop), dealt out as evenly as whole units
+    // allow -- the first `urem` slices hold one unit more (the host sees to n_split <= units)
+    const int units = KS / (KG * NBUF), ubase = units / n_split, urem = units - ubase * n_split;
+    const int ks_begin = (by * ubase + min(by, urem)) * (KG * NBUF);
+    const int n_stage = (ubase + (by < urem ? 1 : 0)) * NBUF;  // a positive multiple of NBUF
     const int mt_base = bz * MT;            // first 32-row tile handled by this block
 
     // ---- activations: this wavefront's tiles of stage 0 and where they land in a stage buffer -----
@@ -497,7 +500,7 @@ struct gemm_args {
     const bf16_t* W;
     const void* scale;
     int wbits;
-    int NT, KS, kps, n_col, n_split, n_zb, T, T_pad, N;
+    int NT, KS, n_col, n_split, n_zb, T, T_pad, N;
     float* out;
     bf16_t* out_act;
     size_t act_plane;
@@ -513,7 +516,7 @@ int launch_one(const gemm_args& a) {
         SLED_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds));
         allowed = true;
     }
-    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.scale, a.NT, a.KS, a.kps, a.n_col,
+    hipLaunchKernelGGL(kern, a.grid, dim3(64 * WAVES), a.lds, a.st, a.X, a.x_plane, a.W, a.scale, a.NT, a.KS, a.n_col,
                        a.n_split, a.n_zb, a.T, a.T_pad, a.N, a.out, a.out_act, a.act_plane, a.F_act);
     SLED_LAUNCH_CHECK();
     return SLED_OK;
@@ -543,12 +546,14 @@ int launch_epi(int epi, const gemm_args& a) {
 // chip wants at least one per CU) but more partial sums to reduce.  Each slice must hold a multiple
 // of 4 stages of 64 k.
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k) {
-    sled_gemm_plan p{1};
+    sled_gemm_plan p{1, 1};
     if (m->s.dtype != SLED_BF16) return p;
-    auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * NARROW_KG * NBUF) == 0; };  // legal for both shapes
+    auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * NARROW_KG * NBUF) == 0; };
     const int n_wg = (N + NARROW_COLS - 1) / NARROW_COLS;
     if (!needs_full_k)
         while (n_wg * p.split < 160 && legal(p.split * 2)) p.split *= 2;
+    // a step with several blocks of rows may pick another number of slices, up to twice as many
+    p.cap = needs_full_k || p.split == 1 ? p.split : std::min(2 * p.split, K / 16 / (NARROW_KG * NBUF));
     return p;
 }
 
@@ -560,14 +565,13 @@ sled_gemm_plan sled_gemm_plan_rows(const sled_model* m, sled_gemm_plan base, int
     if (m->s.dtype != SLED_BF16 || m->batch_invariant || base.split <= 1 || T_pad / 32 <= 4) return base;
     constexpr double FIXED_US = 9.0, STAGE_US = 0.8, PARTIAL_BYTES_PER_US = 4.0e6;
     const int n_col = (N / 32 + WIDE_CG * NW - 1) / (WIDE_CG * NW), zb = (T_pad / 32 + 3) / 4;
-    const int stages = K / 16 / WIDE_KG;
+    const int units = K / 16 / (WIDE_KG * NBUF);   // trips of the stage loop in all of K
     sled_gemm_plan best = base;
     double best_t = -1.0;
-    for (int sp = base.split; sp >= 1; sp /= 2) {
-        if ((K / 16) % (sp * NARROW_KG * NBUF)) continue;
+    for (int sp = 1; sp <= base.cap && sp <= units; sp++) {
         const int64_t wgs = (int64_t)n_col * zb * sp;
-        const double t = (double)((wgs + 255) / 256) * (FIXED_US + (double)(stages / sp) * STAGE_US) +
-                         2.0 * sp * (double)T_pad * N * 4.0 / PARTIAL_BYTES_PER_US;
+        const int stages = (units + sp - 1) / sp * NBUF;   // of the longest slice
+        const double t = (double)((wgs + 255) / 256) * (FIXED_US + stages * STAGE_US) + 2.0 * sp * (double)T_pad * N * 4.0 / PARTIAL_BYTES_PER_US;
         if (best_t < 0 || t < best_t) {
             best_t = t;
             best.split = sp;
@@ -581,7 +585,7 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
                      int F_act, hipStream_t st) {
     if (m->s.dtype == SLED_BF16) {
         const int NT = N / 32, KS = K / 16;
-        if (N % 32 || K % 16 || T_pad % 32 || plan.split < 1 || KS % (plan.split * NARROW_KG * NBUF))
+        if (N % 32 || K % 16 || T_pad % 32 || plan.split < 1 || KS % (NARROW_KG * NBUF) || plan.split > KS / (NARROW_KG * NBUF))
             SLED_FAIL(SLED_EINVAL, "gemm: unsupported shape N=%d K=%d T_pad=%d split=%d", N, K, T_pad, plan.split);
         const int mt_total = T_pad / 32;
         // rows are processed in blocks of at most 4 tiles (128 rows): one block -> narrow shape with exactly its
@@ -613,7 +617,6 @@ int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const v
             SLED_FAIL(SLED_EINVAL, "gemm: %d-bit weights need scales, N (%d) a multiple of 64 and K (%d) of 32", m->wbits, N, K);
         a.NT = NT;
         a.KS = KS;
-        a.kps = KS / plan.split;
         a.T = T;
         a.T_pad = T_pad;
         a.N = N;

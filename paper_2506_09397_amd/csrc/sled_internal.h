@@ -272,6 +272,7 @@ int sled_launch_len_add(int32_t* len_dev, const int32_t* req_ids_dev, const int3
 enum { SLED_EPI_PARTIAL = 0, SLED_EPI_SWIGLU = 1, SLED_EPI_STORE = 2 };
 struct sled_gemm_plan {
     int split;   // K slices
+    int cap;     // the most K slices a step may choose instead (sizes the partial-sum buffer)
 };
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k);
 // the plan for a step of T_pad rows: never more K slices than `base` (which sizes the workspace), fewer where several
