@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--batch-invariant", action="store_true",
                     help="time the step with sled_model_set_batch_invariant on (results independent of the batch to the last bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--contiguous-pages", action="store_true",
+                    help="give every request a run of consecutive physical pages instead of scattering them (for comparison)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy three times before the steps, so that a counter run "
                          "(FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale the counters by")
@@ -97,10 +99,20 @@ def main():
     reqs = [v.open() for _ in range(B)]
     KV = []
     for i in range(B):
-        K, V = synth.context_kv(shape, batch.ctx_len[i], seed=args.seed, req=i, device="cuda")
-        v.append_context([reqs[i]], [K], [V])
-        KV.append((K, V) if i < CPU_SAMPLE_REQUESTS else None)
-        del K, V
+        KV.append(synth.context_kv(shape, batch.ctx_len[i], seed=args.seed, req=i, device="cuda"))
+    # Physical pages: the pool hands out free pages in ascending order, so the contexts go in one page (16 tokens) at
+    # a time in a seeded random interleaving of the requests -- every request's pages end up scattered over the pool,
+    # as they are on a server whose sessions grow side by side.
+    rng = np.random.default_rng(args.seed + 11)
+    left = np.array([(L + 15) // 16 for L in batch.ctx_len])
+    done = np.zeros(B, dtype=np.int64)
+    while left.sum() > 0:
+        i = int(np.argmax(left > 0)) if args.contiguous_pages else int(rng.choice(B, p=left / left.sum()))
+        a, b = int(done[i]) * 16, min((int(done[i]) + 1) * 16, batch.ctx_len[i])
+        v.append_context([reqs[i]], [KV[i][0][:, a:b]], [KV[i][1][:, a:b]])
+        done[i] += 1
+        left[i] -= 1
+    KV = [kv if i < CPU_SAMPLE_REQUESTS else None for i, kv in enumerate(KV)]
     tokens = torch.from_numpy(batch.tokens).cuda()
     torch.cuda.synchronize()
 
