@@ -100,18 +100,8 @@ def main():
     KV = []
     for i in range(B):
         KV.append(synth.context_kv(shape, batch.ctx_len[i], seed=args.seed, req=i, device="cuda"))
-    # Physical pages: the pool hands out free pages in ascending order, so the contexts go in one page (16 tokens) at
-    # a time in a seeded random interleaving of the requests -- every request's pages end up scattered over the pool,
-    # as they are on a server whose sessions grow side by side.
-    rng = np.random.default_rng(args.seed + 11)
-    left = np.array([(L + 15) // 16 for L in batch.ctx_len])
-    done = np.zeros(B, dtype=np.int64)
-    while left.sum() > 0:
-        i = int(np.argmax(left > 0)) if args.contiguous_pages else int(rng.choice(B, p=left / left.sum()))
-        a, b = int(done[i]) * 16, min((int(done[i]) + 1) * 16, batch.ctx_len[i])
-        v.append_context([reqs[i]], [KV[i][0][:, a:b]], [KV[i][1][:, a:b]])
-        done[i] += 1
-        left[i] -= 1
+    # physical pages scattered over the pool (see Verifier.append_contexts_scattered)
+    v.append_contexts_scattered(reqs, KV, seed=args.seed + 11, contiguous=args.contiguous_pages)
     KV = [kv if i < CPU_SAMPLE_REQUESTS else None for i, kv in enumerate(KV)]
     tokens = torch.from_numpy(batch.tokens).cuda()
     torch.cuda.synchronize()

@@ -39,6 +39,23 @@ class Verifier:
         n = [int(k.shape[1]) for k in K]
         sled.sled_kv_append(self.pool, reqs, n, [k.contiguous() for k in K], [v.contiguous() for v in V])
 
+    def append_contexts_scattered(self, reqs: Sequence[int], KV: Sequence, seed: int = 0, contiguous: bool = False) -> None:
+        """Uploads the contexts KV[i] = (K, V) of all `reqs` one page (16 tokens) at a time in a seeded random
+        interleaving of the requests.  The pool hands out free pages in ascending order, so this scatters every
+        request's physical pages over the pool, as on a server whose sessions grow side by side.
+        contiguous=True uploads request after request instead (each on a run of consecutive pages)."""
+        import numpy as np
+        rng = np.random.default_rng(seed)
+        n_tok = [int(kv[0].shape[1]) for kv in KV]
+        left = np.array([(n + 15) // 16 for n in n_tok])
+        done = np.zeros(len(reqs), dtype=np.int64)
+        while left.sum() > 0:
+            i = int(np.argmax(left > 0)) if contiguous else int(rng.choice(len(reqs), p=left / left.sum()))
+            a, b = int(done[i]) * 16, min((int(done[i]) + 1) * 16, n_tok[i])
+            self.append_context([reqs[i]], [KV[i][0][:, a:b]], [KV[i][1][:, a:b]])
+            done[i] += 1
+            left[i] -= 1
+
     def verify(self, reqs: Sequence[int], k: Sequence[int], tokens: torch.Tensor) -> torch.Tensor:
         T = int(sum(k)) + len(k)
         out = self.logits[:T]

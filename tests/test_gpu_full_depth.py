@@ -31,14 +31,12 @@ def _setup(shape, batch, seed, keep):
     ctx_budget = sum(batch.ctx_len) + 9 * B
     v, w = build_verifier(shape, seed, n_pages=ctx_budget // 16 + 2 * B + 8, max_requests=B, B_max=B,
                           ctx_tokens_max=ctx_budget)
-    reqs, KV = [], {}
-    for i in range(B):
-        K, V = synth.context_kv(shape, batch.ctx_len[i], seed=seed, req=i, device="cuda")
-        reqs.append(v.open())
-        v.append_context([reqs[i]], [K], [V])
-        if i in keep:
-            KV[i] = (K.cpu(), V.cpu())
-        del K, V
+    # contexts on physical pages scattered over the pool, as bench.py lays them out
+    reqs = [v.open() for _ in range(B)]
+    dev = [synth.context_kv(shape, batch.ctx_len[i], seed=seed, req=i, device="cuda") for i in range(B)]
+    v.append_contexts_scattered(reqs, dev, seed=seed + 11)
+    KV = {i: (dev[i][0].cpu(), dev[i][1].cpu()) for i in keep}
+    del dev
     return v, w, reqs, KV
 
 
