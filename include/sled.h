@@ -203,6 +203,23 @@ SLED_API int sled_kv_read(sled_kvpool* p, int req_id, int first_token, int n_tok
  * packed rows and ctx_tokens_max total context tokens (sum of L_i + k_i + 1). */
 SLED_API size_t sled_verify_workspace_bytes(const sled_model* m, int B_max, int T_max, int64_t ctx_tokens_max);
 
+/* Planning aids (host only: no GPU is touched, no model needed).  They return what a step will do, so that a caller
+ * can size batches -- and so that the choices can be tested.
+ *
+ * sled_attention_partition: how the attention of a verification step (Sec. 3.4: requests of different lengths in one
+ * batch) is cut into work items, one per workgroup.  n_pages[B]: the K/V pages each request holds in the step
+ * (ceil((L_i + k_i + 1) / 16)).  Every (request, kv head) splits its pages evenly into ceil(n_pages[i] /
+ * *pages_per_item) items; *n_items is their total.  The bound is chosen by playing the launch through (256 CUs, work
+ * items handed out in order, longest requests first): at least 32 pages per item unless the request is shorter, at
+ * most eight items per (request, kv head).  Models in batch-invariant mode use fixed runs of 48 pages instead.
+ *
+ * sled_projection_slices: the number of K slices (partial sums that a row kernel or the attention prologue adds up)
+ * a projection of n_out outputs over n_in inputs runs with in a step of T packed rows of a bf16 model, and the most it
+ * may ever use (which sizes the workspace).  n_out a multiple of 32, n_in of 256. */
+SLED_API int sled_attention_partition(int n_kv_heads, int B, const int* n_pages /*host*/, int* pages_per_item /*host out*/,
+                             int* n_items /*host out*/);
+SLED_API int sled_projection_slices(int n_out, int n_in, int T, int* slices /*host out*/, int* max_slices /*host out*/);
+
 /* One batched verification forward.
  *   req_ids[B], k[B]   host; 0 <= k[i] <= k_max (k[i] = 0 is a plain decode step); a request
  *                      may appear only once in a batch

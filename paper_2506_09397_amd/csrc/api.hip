@@ -764,6 +764,22 @@ int max_work_items(const sled_model* m, int B, int64_t ctx_tokens) {
 
 }  // namespace
 
+extern "C" int sled_attention_partition(int n_kv_heads, int B, const int* n_pages, int* pages_per_item, int* n_items) {
+    if (n_kv_heads < 1 || B < 1 || !n_pages || !pages_per_item || !n_items) SLED_FAIL(SLED_EINVAL, "sled_attention_partition: bad argument");
+    std::vector<int> np(n_pages, n_pages + B), order(B);
+    for (int i = 0; i < B; i++) {
+        if (np[i] < 1) SLED_FAIL(SLED_EINVAL, "sled_attention_partition: request %d holds no page", i);
+        order[i] = i;
+    }
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return np[a] > np[b]; });
+    const int tgt = attn_pages_per_item(np, order, n_kv_heads);
+    int64_t items = 0;
+    for (int n : np) items += (int64_t)n_kv_heads * ceil_div(n, attn_chunk(n, tgt));
+    *pages_per_item = tgt;
+    *n_items = (int)items;
+    return SLED_OK;
+}
+
 extern "C" size_t sled_verify_workspace_bytes(const sled_model* m, int B_max, int T_max, int64_t ctx_tokens_max) {
     if (!m || B_max < 1 || T_max < 1 || ctx_tokens_max < 0) return 0;
     const int G = m->s.n_q_heads / m->s.n_kv_heads;

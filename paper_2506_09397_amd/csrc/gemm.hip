@@ -545,9 +545,16 @@ int launch_epi(int epi, const gemm_args& a) {
 // Number of K slices for a projection of N columns over K.  More slices mean more workgroups (the
 // chip wants at least one per CU) but more partial sums to reduce.  Each slice must hold a multiple
 // of 4 stages of 64 k.
+static sled_gemm_plan plan_one_block(int N, int K, bool needs_full_k);
+static sled_gemm_plan plan_for_rows(sled_gemm_plan base, int N, int K, int T_pad);
+
 sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs_full_k) {
+    if (m->s.dtype != SLED_BF16) return sled_gemm_plan{1, 1};
+    return plan_one_block(N, K, needs_full_k);
+}
+
+static sled_gemm_plan plan_one_block(int N, int K, bool needs_full_k) {
     sled_gemm_plan p{1, 1};
-    if (m->s.dtype != SLED_BF16) return p;
     auto legal = [&](int sp) { return sp >= 1 && (K / 16) % (sp * NARROW_KG * NBUF) == 0; };
     const int n_wg = (N + NARROW_COLS - 1) / NARROW_COLS;
     if (!needs_full_k)
@@ -562,7 +569,12 @@ sled_gemm_plan sled_gemm_make_plan(const sled_model* m, int N, int K, bool needs
 // also mean fewer partial sums to write and to read back.  Estimated time of a launch, in microseconds: rounds x
 // (fixed part + stages per workgroup x time per stage) + bytes of partial sums written and read / rate.
 sled_gemm_plan sled_gemm_plan_rows(const sled_model* m, sled_gemm_plan base, int N, int K, int T_pad) {
-    if (m->s.dtype != SLED_BF16 || m->batch_invariant || base.split <= 1 || T_pad / 32 <= 4) return base;
+    if (m->s.dtype != SLED_BF16 || m->batch_invariant) return base;
+    return plan_for_rows(base, N, K, T_pad);
+}
+
+static sled_gemm_plan plan_for_rows(sled_gemm_plan base, int N, int K, int T_pad) {
+    if (base.split <= 1 || T_pad / 32 <= 4) return base;
     constexpr double FIXED_US = 9.0, STAGE_US = 0.8, PARTIAL_BYTES_PER_US = 4.0e6;
     const int n_col = (N / 32 + WIDE_CG * NW - 1) / (WIDE_CG * NW), zb = (T_pad / 32 + 3) / 4;
     const int units = K / 16 / (WIDE_KG * NBUF);   // trips of the stage loop in all of K
@@ -578,6 +590,15 @@ sled_gemm_plan sled_gemm_plan_rows(const sled_model* m, sled_gemm_plan base, int
         }
     }
     return best;
+}
+
+extern "C" int sled_projection_slices(int n_out, int n_in, int T, int* slices /*host out*/, int* max_slices /*host out*/) {
+    if (!slices || !max_slices || n_out < 32 || n_in < 16 * NARROW_KG * NBUF || n_out % 32 || n_in % (16 * NARROW_KG * NBUF) || T < 1)
+        SLED_FAIL(SLED_EINVAL, "sled_projection_slices: bad argument");
+    const sled_gemm_plan base = plan_one_block(n_out, n_in, false);
+    *slices = plan_for_rows(base, n_out, n_in, (T + 31) / 32 * 32).split;
+    *max_slices = base.cap;
+    return SLED_OK;
 }
 
 int sled_launch_gemm(const sled_model* m, const void* X, size_t x_plane, const void* W, const void* scale, int T, int T_pad,

@@ -32,6 +32,7 @@ EXPORTS = [
     "sled_model_set_weight_bits",
     "sled_kvpool_create", "sled_kvpool_open", "sled_kvpool_close", "sled_kvpool_lengths", "sled_kvpool_destroy",
     "sled_kv_append", "sled_kv_read", "sled_verify_workspace_bytes", "sled_verify_batch", "sled_prefill",
+    "sled_attention_partition", "sled_projection_slices",
     "sled_accept_workspace_bytes", "sled_accept", "sled_accept_static", "sled_accept_sparse", "sled_row_confidence", "sled_profile_enable", "sled_profile_read",
     "sled_strerror", "sled_last_error",
 ]
@@ -75,6 +76,8 @@ def lib() -> C.CDLL:
     L.sled_kv_append.argtypes = [vp, C.c_int, ip, ip, C.POINTER(vp), C.POINTER(vp), vp, vp]
     L.sled_kv_read.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, vp]
     L.sled_verify_workspace_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int64]
+    L.sled_attention_partition.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    L.sled_projection_slices.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     L.sled_verify_workspace_bytes.restype = C.c_size_t
     L.sled_verify_batch.argtypes = [vp, vp, C.c_int, ip, ip, vp, vp, vp, C.c_size_t, vp]
     L.sled_prefill.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp, vp, C.c_size_t, vp]
@@ -181,6 +184,20 @@ def sled_kv_read(pool: int, req_id: int, first_token: int, n_tokens: int, k_dst:
 # ---------------------------------------------------------------------------------------- step
 def sled_verify_workspace_bytes(model: int, B_max: int, T_max: int, ctx_tokens_max: int) -> int:
     return int(lib().sled_verify_workspace_bytes(model, B_max, T_max, ctx_tokens_max))
+
+
+def sled_attention_partition(n_kv_heads: int, n_pages: Sequence[int]):
+    """(pages per attention work item, number of work items) for a step over requests holding n_pages[i] pages."""
+    a, b = C.c_int(0), C.c_int(0)
+    _check(lib().sled_attention_partition(n_kv_heads, len(n_pages), _ints(n_pages), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def sled_projection_slices(n_out: int, n_in: int, T: int):
+    """(K slices in a step of T rows, the most a step may use) for a projection n_in -> n_out of a bf16 model."""
+    a, b = C.c_int(0), C.c_int(0)
+    _check(lib().sled_projection_slices(n_out, n_in, T, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def sled_verify_batch(model: int, pool: int, req_ids: Sequence[int], k: Sequence[int], tokens: torch.Tensor,
