@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0
 # L2 fetch + write-back bytes per projection launch: a STORED counter figure, not read in this run (FETCH_SIZE and
 # WRITE_SIZE of rocprofv3 need runs of their own; each is scaled by what the counter reads for a 1 GiB copy;
 # profiles/verify_step_llama8b_b16_hbm_traffic.txt gives the commands and the table).  Taken with gemm_bf16_kernel as
-# it stands in csrc/gemm.hip (retaken after the last change to that file's kernel code: 149.9 MB both times); to be
-# reset to None whenever that kernel changes.
+# it stands in csrc/gemm.hip (retaken after every change to that file's kernel code, last after K slices became
+# uneven: 149.9 MB each time); to be reset to None whenever that kernel changes.
 MEASURED_TRAFFIC = {"llama8b_b16": 149.9e6}
 TRAFFIC_NOTE = "stored rocprofv3 FETCH_SIZE+WRITE_SIZE figure for gemm_bf16_kernel (profiles/verify_step_llama8b_b16_hbm_traffic.txt), not measured in this run"
 CPU_SAMPLE_REQUESTS, CPU_SAMPLE_LAYERS = 16, 24   # the oracle's bounded sample (about 10-20 s of CPU work)
